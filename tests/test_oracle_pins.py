@@ -1,0 +1,434 @@
+"""Pins for the CPU oracle: each checks it against something other than itself
+(published vectors, closed forms, library autograd/optimizers, invariants,
+brute force), so that a dropped term, a wrong sign or index, or a transposed
+operand in the oracle fails at least one of them."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2012_04201_amd import inputs
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+G = 0x9E3779B97F4A7C15
+M64 = 2**64 - 1
+
+
+def tiny_problem(seed, n=40, d=4, n_classes=3):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(n, d)).astype(np.float32)
+    if n_classes >= 2:
+        y = rng.integers(0, n_classes, size=n).astype(np.int32)
+    else:
+        y = (X[:, 0] - 0.5 * X[:, 1] + 0.1 * rng.normal(size=n)).astype(np.float32)
+    return X, y
+
+
+def unpack(theta, dims):
+    """Packed parameters -> [(W[in,out], b[out])] following the oracle's layout."""
+    out, off = [], 0
+    for l in range(len(dims) - 1):
+        fi, fo = dims[l], dims[l + 1]
+        W = theta[off:off + fi * fo].reshape(fi, fo)
+        off += fi * fo
+        b = theta[off:off + fo]
+        off += fo
+        out.append((W, b))
+    assert off == theta.shape[0]
+    return out
+
+
+def torch_loss(theta_t, dims, Xb, yb, n_classes, alpha):
+    """Library definition of the training objective (float64, autograd-able)."""
+    off, a = 0, Xb
+    pen = 0.0
+    L = len(dims) - 1
+    for l in range(L):
+        fi, fo = dims[l], dims[l + 1]
+        W = theta_t[off:off + fi * fo].reshape(fi, fo)
+        off += fi * fo
+        b = theta_t[off:off + fo]
+        off += fo
+        a = a @ W + b
+        if l + 1 < L:
+            a = torch.relu(a)
+        pen = pen + (W * W).sum()
+    m = Xb.shape[0]
+    if n_classes >= 2:
+        data = torch.nn.functional.cross_entropy(a, yb, reduction="mean")
+    else:
+        data = 0.5 * torch.nn.functional.mse_loss(a[:, 0], yb, reduction="mean")
+    return data + 0.5 * alpha * pen / m
+
+
+# ------------------------------------------------------------ RNG pins ----
+
+def test_mix64_published_vectors(oracle):
+    want = [int(l, 16) for l in open(os.path.join(GOLD, "splitmix64_kat.txt")) if l.startswith("0x")]
+    got = [oracle.mix64((k * G) & M64) for k in (1, 2, 3)]
+    assert got == want
+    # combine(h, v) is the SplitMix64 stream started at h read at position v
+    assert [oracle.combine(0, v) for v in range(3)] == want
+
+
+@pytest.mark.parametrize("n", list(range(1, 130)) + [255, 256, 257, 405, 455, 1023, 1024, 1025, 1438, 2048, 4097,
+                                                      16000, 20000])
+def test_permutation_is_bijection(oracle, n):
+    p = oracle.permutation(12345, 2, 7, n)
+    assert p.min() == 0 and p.max() == n - 1
+    assert np.array_equal(np.sort(p), np.arange(n))
+
+
+def test_permutation_depends_on_key_and_mixes(oracle):
+    n = 1000
+    a = oracle.permutation(1, 0, 0, n)
+    assert not np.array_equal(a, oracle.permutation(1, 0, 1, n))  # epoch
+    assert not np.array_equal(a, oracle.permutation(1, 1, 0, n))  # fold
+    assert not np.array_equal(a, oracle.permutation(2, 0, 0, n))  # seed
+    # no structure a sorted or shifted order would leave: displacement statistics of a random permutation
+    disp = np.abs(a - np.arange(n)).mean()
+    assert 0.25 * n < disp < 0.42 * n  # E|i - pi(i)| = n/3
+    assert (a == np.arange(n)).sum() < 8  # fixed points ~ Poisson(1)
+
+
+def test_fold_lists_partition_rows(oracle):
+    rng = np.random.default_rng(0)
+    fold = rng.integers(-1, 5, size=501).astype(np.int32)
+    for f in range(5):
+        tr, va = oracle.fold_lists(fold, f)
+        assert np.array_equal(va, np.nonzero(fold == f)[0])
+        assert np.array_equal(tr, np.nonzero((fold >= 0) & (fold != f))[0])
+
+
+def test_minibatches_cover_train_rows_once_per_epoch(oracle):
+    fold = inputs.make_folds(103, 5, 9)
+    hp = {"hidden": [3], "batch_size": 16, "seed": 77, "epochs": 2}
+    for f in (0, 3):
+        tr, _ = oracle.fold_lists(fold, f)
+        for ep in (0, 1):
+            steps = -(-len(tr) // 16)
+            got = [oracle.minibatch_rows(fold, hp, f, ep, s) for s in range(steps)]
+            assert all(len(g) == 16 for g in got[:-1]) and len(got[-1]) == len(tr) - 16 * (steps - 1)
+            assert np.array_equal(np.sort(np.concatenate(got)), tr)
+            perm = oracle.permutation(77, f, ep, len(tr))
+            assert np.array_equal(np.concatenate(got), tr[perm])
+    # batch_size 0 or larger than the fold => one full batch
+    for bs in (0, 1000):
+        hp2 = dict(hp, batch_size=bs)
+        tr, _ = oracle.fold_lists(fold, 1)
+        assert len(oracle.minibatch_rows(fold, hp2, 1, 0, 0)) == len(tr)
+
+
+def test_init_glorot_bounds_and_moments(oracle):
+    hp = {"hidden": [200, 150], "seed": 42}
+    d, c = 64, 10
+    th = oracle.init_params(d, c, hp, 1)
+    dims = [d, 200, 150, c]
+    for (W, b), fi, fo in zip(unpack(th, dims), dims[:-1], dims[1:]):
+        bound = float(np.float32(np.sqrt(6.0 / (fi + fo))))
+        for t in (W, b):
+            assert np.all(np.abs(t) <= bound)
+            assert np.array_equal(t, t.astype(np.float32).astype(np.float64))  # fp32 values
+        assert abs(W.mean()) < 4 * bound / np.sqrt(3 * W.size)
+        assert abs(W.var() / (bound**2 / 3) - 1) < 0.05
+    # different fold / seed / layer streams are different
+    assert not np.array_equal(th, oracle.init_params(d, c, hp, 2))
+    assert not np.array_equal(th, oracle.init_params(d, c, dict(hp, seed=43), 1))
+    # the draw is the top 24 bits of the element hash, centred: check one element by hand
+    km = oracle.combine(oracle.combine(42, 0x4D4C50), 1)
+    kt = oracle.combine(km, 16 + 2 * 0 + 0)
+    k24 = oracle.combine(kt, 5) >> 40
+    bound = np.float32(np.sqrt(6.0 / (64 + 200)))
+    assert th[5] == float(np.float32(float(bound) * ((k24 - 2**23) / 2**23)))
+
+
+def test_bf16_rounding_matches_library(oracle):
+    rng = np.random.default_rng(1)
+    bits = np.concatenate([
+        rng.integers(0, 2**32, size=200000, dtype=np.uint64).astype(np.uint32),
+        # ties, just-above/below ties, for many upper halves
+        (np.arange(0, 2**16, 7, dtype=np.uint32) << 16) | 0x8000,
+        (np.arange(0, 2**16, 7, dtype=np.uint32) << 16) | 0x8001,
+        (np.arange(0, 2**16, 7, dtype=np.uint32) << 16) | 0x7FFF,
+        np.array([0, 0x80000000, 0x7F800000, 0xFF800000, 0x00000001, 0x00008000, 0x7F7FFFFF], dtype=np.uint32),
+    ])
+    f = bits.view(np.float32)
+    want = torch.from_numpy(f.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got_gen = inputs.to_bf16_bits(f)
+    lib = oracle.lib().oracle_bf16_bits
+    import ctypes as C
+    sel = np.concatenate([np.arange(0, 200000, 37), np.arange(200000, bits.shape[0])])
+    nan = np.isnan(f)
+    for i in sel:
+        g = lib(C.c_float(f[i]))
+        if nan[i]:
+            assert (g & 0x7F80) == 0x7F80 and (g & 0x7F) != 0
+        else:
+            assert g == want[i], hex(int(bits[i]))
+    assert np.array_equal(got_gen[~nan], want[~nan])
+
+
+# ----------------------------------------------- forward/backward pins ----
+
+CASES = [
+    # (n_classes, hidden, alpha)
+    (3, [5], 0.3),
+    (2, [4], 0.0),
+    (3, [], 0.7),
+    (0, [5], 0.2),
+    (0, [], 0.0),
+    (4, [5, 3], 0.5),
+    (0, [4, 4, 3], 0.1),
+]
+
+
+@pytest.mark.parametrize("n_classes,hidden,alpha", CASES)
+def test_gradient_matches_autograd_and_finite_differences(oracle, n_classes, hidden, alpha):
+    X, y = tiny_problem(3, n=23, d=4, n_classes=n_classes)
+    hp = {"hidden": hidden, "alpha": alpha, "seed": 5}
+    dims = [4] + hidden + [n_classes if n_classes >= 2 else 1]
+    rng = np.random.default_rng(8)
+    theta = oracle.init_params(4, n_classes, hp, 0) + 0.3 * rng.normal(size=oracle.param_count(4, n_classes, hp))
+    rows = np.array([3, 17, 5, 8, 21, 0, 11], dtype=np.int32)
+    loss, grad = oracle.loss_grad(X, y, n_classes, rows, hp, theta, prec=1)
+
+    # library autograd on the textbook objective
+    tt = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
+    Xb = torch.tensor(X[rows], dtype=torch.float64)
+    yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 2 else torch.tensor(y[rows], dtype=torch.float64)
+    tl = torch_loss(tt, dims, Xb, yb, n_classes, float(np.float32(alpha)))
+    tl.backward()
+    assert abs(loss - tl.item()) < 1e-12 * max(1, abs(loss))
+    np.testing.assert_allclose(grad, tt.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+    # central finite differences of the oracle's own loss
+    eps = 1e-6
+    fd = np.zeros_like(theta)
+    for i in range(theta.shape[0]):
+        tp, tm = theta.copy(), theta.copy()
+        tp[i] += eps
+        tm[i] -= eps
+        fd[i] = (oracle.loss_grad(X, y, n_classes, rows, hp, tp, prec=1)[0]
+                 - oracle.loss_grad(X, y, n_classes, rows, hp, tm, prec=1)[0]) / (2 * eps)
+    assert np.linalg.norm(fd - grad) / np.linalg.norm(grad) < 1e-6
+
+
+def test_softmax_gradient_invariants_and_binary_equals_logistic(oracle):
+    X, y = tiny_problem(4, n=30, d=4, n_classes=2)
+    hp = {"hidden": [6], "alpha": 0.0, "seed": 1}
+    theta = oracle.init_params(4, 2, hp, 0)
+    rows = np.arange(12, dtype=np.int32)
+    loss, grad = oracle.loss_grad(X, y, 2, rows, hp, theta, prec=1)
+    (W1, b1), (W2, b2) = unpack(theta, [4, 6, 2])
+    gb2 = unpack(grad, [4, 6, 2])[1][1]
+    assert abs(gb2.sum()) < 1e-14  # softmax deltas sum to zero over classes
+    # two-class softmax == logistic regression on the logit difference
+    a1 = np.maximum(X[rows].astype(np.float64) @ W1 + b1, 0)
+    z = a1 @ W2 + b2
+    s = (2 * y[rows] - 1) * (z[:, 1] - z[:, 0])
+    assert abs(loss - np.mean(np.log1p(np.exp(-s)))) < 1e-13
+
+
+def test_fp32_mode_tracks_fp64_mode(oracle):
+    X, y = tiny_problem(5, n=64, d=4, n_classes=3)
+    hp = {"hidden": [16], "alpha": 0.01, "seed": 3}
+    theta = oracle.init_params(4, 3, hp, 0)
+    rows = np.arange(40, dtype=np.int32)
+    l64, g64 = oracle.loss_grad(X, y, 3, rows, hp, theta, prec=1)
+    l32, g32 = oracle.loss_grad(X, y, 3, rows, hp, theta, prec=0)
+    assert abs(l64 - l32) < 1e-6
+    assert np.linalg.norm(g64 - g32) / np.linalg.norm(g64) < 1e-6
+    assert np.array_equal(g32, g32.astype(np.float32).astype(np.float64))
+
+
+def test_bf16_mode_rounds_operands_only(oracle):
+    """bf16 configuration == the fp32 computation run on bf16-rounded operands
+    (checked for a linear model, where the only operands are X and W)."""
+    rng = np.random.default_rng(2)
+    Xf = rng.normal(size=(20, 8)).astype(np.float32)
+    Xb = inputs.to_bf16_bits(Xf).reshape(20, 8)
+    y = rng.integers(0, 3, size=20).astype(np.int32)
+    hp = {"hidden": [], "alpha": 0.5, "seed": 9}
+    theta = oracle.init_params(8, 3, hp, 0)
+    rows = np.arange(20, dtype=np.int32)
+    lb, gb = oracle.loss_grad(Xb, y, 3, rows, hp, theta, dtype=1, prec=0)
+    # reference: torch float64 on rounded X and rounded W (penalty on the unrounded W)
+    Xr = inputs.bf16_bits_to_f32(Xb).reshape(20, 8).astype(np.float64)
+    W = theta[:24].reshape(8, 3)
+    b = theta[24:]
+    Wr = inputs.bf16_bits_to_f32(inputs.to_bf16_bits(W.astype(np.float32))).reshape(8, 3).astype(np.float64)
+    z = torch.tensor(Xr @ Wr + b)
+    data = torch.nn.functional.cross_entropy(z, torch.tensor(y.astype(np.int64))).item()
+    want = data + 0.5 * float(np.float32(0.5)) * (W * W).sum() / 20
+    assert abs(lb - want) < 2e-6
+    # deltas are rounded to bf16 before the weight-gradient product
+    p = torch.softmax(z, dim=1).numpy()
+    p[np.arange(20), y] -= 1
+    dl = inputs.bf16_bits_to_f32(inputs.to_bf16_bits((p / 20).astype(np.float32))).reshape(20, 3).astype(np.float64)
+    gW = Xr.T @ dl + float(np.float32(0.5)) / 20 * W
+    np.testing.assert_allclose(gb[:24].reshape(8, 3), gW, rtol=2e-6, atol=1e-8)
+    np.testing.assert_allclose(gb[24:], dl.sum(axis=0), rtol=2e-6, atol=1e-8)
+
+
+# ------------------------------------------------------ optimizer pins ----
+
+def test_adam_first_step_closed_form(oracle):
+    rng = np.random.default_rng(3)
+    g = rng.normal(size=50) * 10.0 ** rng.integers(-3, 2, size=50)
+    theta = rng.normal(size=50)
+    hp = {"solver": "adam", "lr": 0.01, "beta1": 0.9, "beta2": 0.999, "eps": 1e-8}
+    th = theta.copy()
+    m, v = np.zeros(50), np.zeros(50)
+    t = oracle.opt_step(hp, th, g, m, v, 0, prec=1)
+    assert t == 1
+    b2, eps, lr = float(np.float32(0.999)), float(np.float32(1e-8)), float(np.float32(0.01))
+    want = theta - lr * g / (np.abs(g) + eps / np.sqrt(1 - b2))
+    np.testing.assert_allclose(th, want, rtol=1e-9, atol=1e-15)
+    big = np.abs(g) > 1e-2  # |g| >> eps: the first Adam step is lr * sign(g)
+    np.testing.assert_allclose(th[big], (theta - lr * np.sign(g))[big], atol=1e-6)
+
+
+@pytest.mark.parametrize("solver,nesterov", [("adam", False), ("sgd", False), ("sgd", True)])
+def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov):
+    """A few epochs of minibatch training in fp64 mode equal the same loop
+    written with library autograd + library optimizer, fed the oracle's own
+    minibatch rows and initial weights.  (Adam: eps is set tiny, where the two
+    published placements of eps coincide.)"""
+    n_classes = 3 if solver == "adam" else 0
+    X, y = tiny_problem(6, n=50, d=4, n_classes=n_classes)
+    fold = inputs.make_folds(50, 5, 1)
+    hp = {"hidden": [7], "solver": solver, "nesterov": nesterov, "lr": 0.02, "alpha": 0.05, "momentum": 0.8,
+          "batch_size": 16, "epochs": 3, "eps": 1e-30, "seed": 11}
+    f = 2
+    dims = [4, 7, n_classes if n_classes >= 2 else 1]
+    res = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1, step_begin=0, step_end=9)
+    tt = torch.tensor(oracle.init_params(4, n_classes, hp, f), dtype=torch.float64, requires_grad=True)
+    lr, mu = float(np.float32(0.02)), float(np.float32(0.8))
+    if solver == "adam":
+        opt = torch.optim.Adam([tt], lr=lr, betas=(float(np.float32(0.9)), float(np.float32(0.999))), eps=1e-30)
+    else:
+        opt = torch.optim.SGD([tt], lr=lr, momentum=mu, nesterov=nesterov)
+    k = 0
+    for ep in range(3):
+        for s in range(3):  # 40 train rows / 16 -> 3 steps, last one of 8 rows
+            rows = oracle.minibatch_rows(fold, hp, f, ep, s)
+            assert len(rows) == (16 if s < 2 else 8)
+            Xb = torch.tensor(X[rows], dtype=torch.float64)
+            yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 2 else torch.tensor(y[rows], dtype=torch.float64)
+            opt.zero_grad()
+            loss = torch_loss(tt, dims, Xb, yb, n_classes, float(np.float32(0.05)))
+            loss.backward()
+            assert abs(loss.item() - res["loss"][k]) < 1e-10
+            np.testing.assert_allclose(res["grad"][k], tt.grad.numpy(), rtol=1e-8, atol=1e-12)
+            opt.step()
+            np.testing.assert_allclose(res["theta_after"][k], tt.detach().numpy(), rtol=1e-8, atol=1e-12)
+            k += 1
+    np.testing.assert_allclose(res["theta"], tt.detach().numpy(), rtol=1e-8, atol=1e-12)
+
+
+def test_linear_mse_converges_to_least_squares_and_ridge(oracle):
+    rng = np.random.default_rng(4)
+    n, d = 60, 3
+    X = rng.normal(size=(n, d)).astype(np.float32)
+    y = (X @ np.array([1.0, -2.0, 0.5]) + 0.7 + 0.1 * rng.normal(size=n)).astype(np.float32)
+    fold = np.full(n, 1, dtype=np.int32)
+    fold[:12] = 0  # fold 0 held out; train on the other 48 rows, full batch
+    tr = np.arange(12, n)
+    Xd, yd = X[tr].astype(np.float64), y[tr].astype(np.float64)
+    for alpha in (0.0, 3.0):
+        hp = {"hidden": [], "solver": "sgd", "momentum": 0.0, "lr": 0.3, "alpha": alpha, "batch_size": 0,
+              "epochs": 400, "seed": 2}
+        res = oracle.train_one(X, y, 0, fold, hp, 0, prec=1)
+        w, b = res["theta"][:d], res["theta"][d]
+        Xc, yc = Xd - Xd.mean(0), yd - yd.mean()
+        w_ref = np.linalg.solve(Xc.T @ Xc + alpha * np.eye(d), Xc.T @ yc)  # intercept unpenalised
+        b_ref = yd.mean() - Xd.mean(0) @ w_ref
+        np.testing.assert_allclose(w, w_ref, rtol=1e-8, atol=1e-10)
+        assert abs(b - b_ref) < 1e-9
+        if alpha == 0.0:
+            w_ls = np.linalg.lstsq(np.c_[Xd, np.ones(len(tr))], yd, rcond=None)[0]
+            np.testing.assert_allclose(np.r_[w, b], w_ls, rtol=1e-8, atol=1e-10)
+        # the reported score is the plain mean squared error on the held rows
+        pred = X[:12].astype(np.float64) @ w + b
+        assert abs(res["scores"][0] - np.mean((pred - y[:12]) ** 2)) < 1e-12
+        assert res["scores"][1] == 0.0
+
+
+def test_full_batch_gradient_descent_loss_is_monotone(oracle):
+    X, y = tiny_problem(7, n=80, d=4, n_classes=3)
+    fold = inputs.make_folds(80, 5, 3)
+    hp = {"hidden": [10], "solver": "sgd", "momentum": 0.0, "lr": 0.05, "alpha": 0.1, "batch_size": 0, "epochs": 60,
+          "seed": 6}
+    res = oracle.train_one(X, y, 3, fold, hp, 0, prec=0, step_begin=0, step_end=60)
+    assert np.all(np.diff(res["loss"]) <= 1e-7)
+    assert res["loss"][-1] < res["loss"][0] - 0.05
+
+
+def test_zero_learning_rate_or_zero_epochs_keeps_init(oracle):
+    X, y = tiny_problem(8, n=40, d=4, n_classes=3)
+    fold = inputs.make_folds(40, 5, 3)
+    base = {"hidden": [6], "solver": "sgd", "momentum": 0.0, "alpha": 0.0, "batch_size": 8, "seed": 4}
+    init = oracle.init_params(4, 3, base, 1)
+    r0 = oracle.train_one(X, y, 3, fold, dict(base, lr=0.0, epochs=3), 1)
+    r1 = oracle.train_one(X, y, 3, fold, dict(base, lr=0.1, epochs=0), 1)
+    assert np.array_equal(r0["theta"], init) and np.array_equal(r1["theta"], init)
+    assert np.array_equal(r0["scores"], r1["scores"])
+    # score of the init, by the library definition
+    (W1, b1), (W2, b2) = unpack(init, [4, 6, 3])
+    _, va = oracle.fold_lists(fold, 1)
+    z = np.maximum(X[va].astype(np.float64) @ W1 + b1, 0) @ W2 + b2
+    nll = torch.nn.functional.cross_entropy(torch.tensor(z), torch.tensor(y[va].astype(np.int64))).item()
+    assert abs(r0["scores"][0] - nll) < 1e-6
+    assert abs(r0["scores"][1] - np.mean(z.argmax(1) == y[va])) < 1e-7
+
+
+# ------------------------------------------------ whole-call properties ----
+
+def test_cv_score_is_unweighted_mean_of_folds_and_batch_invariant(oracle):
+    cfg = inputs.make_config(0, epochs=5)
+    hps = cfg["hparams"]
+    s, st, pf = oracle.cv_eval(cfg["X"], cfg["y"], 3, cfg["fold_idx"], 5, hps)
+    np.testing.assert_allclose(s, pf.mean(axis=1), rtol=1e-6)
+    assert np.all(st == 0)
+    # each suggestion's score does not depend on what else is in the batch, nor on its position
+    order = [5, 2, 2, 7]
+    s2, _, _ = oracle.cv_eval(cfg["X"], cfg["y"], 3, cfg["fold_idx"], 5, [hps[i] for i in order])
+    assert np.array_equal(s2, s[order])
+    # per-fold value equals the single-model entry point
+    one = oracle.train_one(cfg["X"], cfg["y"], 3, cfg["fold_idx"], hps[3], 4)
+    assert np.array_equal(one["scores"], pf[3, 4])
+
+
+def test_stratified_folds_are_balanced():
+    cfg = inputs.make_config(0)
+    for f in range(5):
+        cnt = np.bincount(cfg["y"][cfg["fold_idx"] == f], minlength=3)
+        assert cnt.max() - cnt.min() <= 1 and cnt.sum() == 30
+
+
+def test_hidden_unit_permutation_symmetry(oracle):
+    X, y = tiny_problem(9, n=30, d=4, n_classes=3)
+    hp = {"hidden": [6], "alpha": 0.2, "seed": 3}
+    theta = oracle.init_params(4, 3, hp, 0)
+    (W1, b1), (W2, b2) = unpack(theta, [4, 6, 3])
+    perm = np.array([4, 0, 5, 2, 1, 3])
+    theta_p = np.concatenate([W1[:, perm].ravel(), b1[perm], W2[perm, :].ravel(), b2])
+    rows = np.arange(30, dtype=np.int32)
+    l0, g0 = oracle.loss_grad(X, y, 3, rows, hp, theta, prec=1)
+    l1, g1 = oracle.loss_grad(X, y, 3, rows, hp, theta_p, prec=1)
+    assert abs(l0 - l1) < 1e-13
+    (gW1, gb1), (gW2, gb2) = unpack(g0, [4, 6, 3])
+    want = np.concatenate([gW1[:, perm].ravel(), gb1[perm], gW2[perm, :].ravel(), gb2])
+    np.testing.assert_allclose(g1, want, rtol=1e-12, atol=1e-15)
+
+
+def test_divergent_run_sets_status_not_error(oracle):
+    X, y = tiny_problem(10, n=40, d=4, n_classes=0)
+    fold = inputs.make_folds(40, 5, 3)
+    bad = {"hidden": [8], "solver": "sgd", "momentum": 0.99, "nesterov": True, "lr": 50.0, "batch_size": 8,
+           "epochs": 60, "seed": 1}
+    good = dict(bad, lr=0.01, momentum=0.5)
+    s, st, _ = oracle.cv_eval(X, y, 0, fold, 5, [bad, good])
+    assert st[0] == 1 and not np.isfinite(s[0, 0])
+    assert st[1] == 0 and np.isfinite(s[1, 0])
