@@ -486,7 +486,7 @@ int64_t oracle_minibatch_rows(const int32_t* fold_idx, int64_t n, const oracle_h
 
 typedef struct {
   int64_t step_begin, step_end; /* global step window, [begin, end) */
-  double* out;                  /* per step: loss, grad[P], theta_after[P] */
+  double* out;                  /* per step: loss, grad[P], theta_after[P], m_after[P], v_after[P] */
   int stop_after;               /* stop training once the window is recorded */
 } trace_t;
 
@@ -518,10 +518,12 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
       else
         sgd_step(hp, P, theta, grad, &o, prec);
       if (trace && gstep >= trace->step_begin && gstep < trace->step_end) {
-        double* rec = trace->out + (gstep - trace->step_begin) * (1 + 2 * P);
+        double* rec = trace->out + (gstep - trace->step_begin) * (1 + 4 * P);
         rec[0] = loss;
         memcpy(rec + 1, grad, sizeof(double) * (size_t)P);
         memcpy(rec + 1 + P, theta, sizeof(double) * (size_t)P);
+        memcpy(rec + 1 + 2 * P, m, sizeof(double) * (size_t)P);
+        memcpy(rec + 1 + 3 * P, v, sizeof(double) * (size_t)P);
         if (trace->stop_after && gstep + 1 == trace->step_end) done = 1;
       }
     }

@@ -178,15 +178,16 @@ def opt_step(hp, theta, g, m, v, t, prec=0):
 def train_one(X, y, n_classes, fold_idx, hp, fold, dtype=0, prec=0, step_begin=0, step_end=0, stop_after=False):
     """Train one (suggestion, fold) model.
 
-    Returns dict(theta, scores, loss[T], grad[T,P], theta_after[T,P]) with
-    T = step_end - step_begin recorded steps.
+    Returns dict(theta, scores, loss[T], grad[T,P], theta_after[T,P],
+    m_after[T,P], v_after[T,P]) with T = step_end - step_begin recorded steps
+    (m = first moment or SGD velocity, v = second moment).
     """
     X, y = _xy(X, y, n_classes, dtype)
     fold_idx = np.ascontiguousarray(fold_idx, dtype=np.int32)
     h = make_hparams([hp])
     P = param_count(X.shape[1], n_classes, hp)
     T = max(step_end - step_begin, 0)
-    trace = np.full((T, 1 + 2 * P), np.nan, dtype=np.float64) if T else None
+    trace = np.full((T, 1 + 4 * P), np.nan, dtype=np.float64) if T else None
     theta = np.zeros(P, dtype=np.float64)
     sc = np.zeros(2, dtype=np.float64)
     rc = lib().oracle_train_one(_p(X), _p(y), C.c_int64(X.shape[0]), C.c_int32(X.shape[1]), C.c_int32(n_classes),
@@ -198,7 +199,9 @@ def train_one(X, y, n_classes, fold_idx, hp, fold, dtype=0, prec=0, step_begin=0
     if T:
         out["loss"] = trace[:, 0].copy()
         out["grad"] = trace[:, 1:1 + P].copy()
-        out["theta_after"] = trace[:, 1 + P:].copy()
+        out["theta_after"] = trace[:, 1 + P:1 + 2 * P].copy()
+        out["m_after"] = trace[:, 1 + 2 * P:1 + 3 * P].copy()
+        out["v_after"] = trace[:, 1 + 3 * P:].copy()
     return out
 
 

@@ -1,0 +1,56 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bb():
+    from paper_2012_04201_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_lib()
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bbo_mlp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bbo_mlp_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(bb):
+    syms = declared_symbols()
+    assert len(syms) >= 8
+    L = bb.lib()
+    for s in syms:
+        assert hasattr(L, s), s
+    assert sorted(bb.EXPORTS) == syms
+
+
+def test_hparams_struct_layout(bb):
+    assert C.sizeof(bb.HParams) == 72
+    assert bb.HParams.seed.offset == 64 and bb.HParams.lr.offset == 36
+
+
+def test_argument_validation_without_gpu(bb):
+    L = bb.lib()
+    hp = bb.make_hparams([{"hidden": [8, 9]}])
+    assert bb.bbo_mlp_param_count(4, 3, {"hidden": [8, 9]}) == 4 * 8 + 8 + 8 * 9 + 9 + 9 * 3 + 3
+    assert bb.bbo_mlp_param_count(4, 0, {"hidden": []}) == 5
+    out = C.c_size_t(0)
+    rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(0), C.c_int32(3), C.c_int32(5), hp, C.c_int32(1),
+                                   C.c_int32(0), C.byref(out))
+    assert rc == bb.INVALID_ARG and b"d < 1" in L.bbo_mlp_last_error()
+    rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(4), C.c_int32(1), C.c_int32(5), hp, C.c_int32(1),
+                                   C.c_int32(0), C.byref(out))
+    assert rc == bb.INVALID_ARG
+    bad = bb.make_hparams([{"hidden": [100000]}])
+    rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(4), C.c_int32(3), C.c_int32(5), bad, C.c_int32(1),
+                                   C.c_int32(0), C.byref(out))
+    assert rc == bb.UNSUPPORTED
+    assert L.bbo_mlp_param_count(C.c_int32(4), C.c_int32(1), hp) < 0

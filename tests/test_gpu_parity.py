@@ -1,0 +1,323 @@
+"""GPU parity tests: the HIP library (through its C ABI) against the CPU oracle
+on the same seeded inputs.
+
+Bars: integer work (fold lists, minibatch rows, initial-weight bits) is
+bit-exact; per-step gradients and weights match to 1e-4 relative (norm-wise,
+fp32) or 2e-2 (bf16 operands); final cross-validation scores match to 1e-3
+absolute."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2012_04201_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+REL_F32, REL_BF16, ABS_SCORE = 1e-4, 2e-2, 1e-3
+
+
+@pytest.fixture(scope="module")
+def bb():
+    from paper_2012_04201_amd import binding
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    binding.lib()
+    return binding
+
+
+def relerr(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
+
+
+def layer_slices(d, hidden, c_out):
+    dims = [d] + list(hidden) + [c_out]
+    out, off = [], 0
+    for l in range(len(dims) - 1):
+        nw = dims[l] * dims[l + 1]
+        out.append(("W%d" % l, slice(off, off + nw)))
+        off += nw
+        out.append(("b%d" % l, slice(off, off + dims[l + 1])))
+        off += dims[l + 1]
+    return out
+
+
+# ------------------------------------------------------------- integers ----
+
+@pytest.mark.parametrize("n,K", [(0, 5), (1, 5), (150, 5), (569, 5), (1797, 5), (20000, 5), (1000, 3), (777, 1)])
+def test_fold_lists_bit_exact(bb, oracle, n, K):
+    rng = np.random.default_rng(n + K)
+    fold = rng.integers(-1, K, size=n).astype(np.int32) if n else np.zeros(0, dtype=np.int32)
+    ft = torch.from_numpy(fold).cuda()
+    tr, va, cnt = bb.bbo_mlp_fold_lists(ft, K)
+    torch.cuda.synchronize()
+    tr, va, cnt = tr.cpu().numpy(), va.cpu().numpy(), cnt.cpu().numpy()
+    for f in range(K):
+        otr, ova = oracle.fold_lists(fold, f)
+        assert cnt[f, 0] == len(otr) and cnt[f, 1] == len(ova)
+        assert np.array_equal(tr[f, :len(otr)], otr)
+        assert np.array_equal(va[f, :len(ova)], ova)
+
+
+@pytest.mark.parametrize("n,bs", [(150, 0), (103, 16), (569, 57), (1797, 256), (20000, 256), (37, 1), (64, 64)])
+def test_minibatch_rows_bit_exact(bb, oracle, n, bs):
+    fold = inputs.make_folds(n, 5, n)
+    ft = torch.from_numpy(fold).cuda()
+    tr, va, cnt = bb.bbo_mlp_fold_lists(ft, 5)
+    hp = {"hidden": [4], "batch_size": bs, "seed": 0xDEADBEEF12345 + n}
+    for f in (0, 4):
+        n_tr = int((fold != f).sum())
+        eff = n_tr if bs <= 0 or bs > n_tr else bs
+        steps = -(-n_tr // eff)
+        for ep in (0, 3):
+            for st in sorted({0, steps // 2, steps - 1}):
+                got = bb.bbo_mlp_minibatch_rows(tr, cnt, n, hp, f, ep, st).cpu().numpy()
+                want = oracle.minibatch_rows(fold, hp, f, ep, st)
+                assert np.array_equal(got, want), (f, ep, st)
+
+
+@pytest.mark.parametrize("d,hidden,c", [(4, [8], 3), (64, [200], 10), (13, [57], 0), (30, [], 2), (128, [256, 128], 10),
+                                        (5, [3, 4, 5, 6], 7)])
+def test_init_params_bit_exact(bb, oracle, d, hidden, c):
+    hp = {"hidden": hidden, "seed": 987654321012345678}
+    for fold in (0, 3):
+        got = bb.bbo_mlp_init_params(d, c, hp, fold).cpu().numpy()
+        want = oracle.init_params(d, c, hp, fold).astype(np.float32)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+# ------------------------------------------------------- per-step trace ----
+
+def small_problem(seed, n, d, n_classes, bf16=False):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(n, d)).astype(np.float32)
+    if n_classes >= 2:
+        W = rng.normal(size=(d, n_classes))
+        y = (X @ W + 0.5 * rng.normal(size=(n, n_classes))).argmax(1).astype(np.int32)
+    else:
+        y = (X @ rng.normal(size=d) / np.sqrt(d) + 0.1 * rng.normal(size=n)).astype(np.float32)
+    fold = inputs.make_folds(n, 5, seed)
+    cfg = {"X": inputs.to_bf16_bits(X).reshape(n, d) if bf16 else X, "y": y, "n_classes": n_classes,
+           "dtype": 1 if bf16 else 0, "fold_idx": fold, "n_folds": 5}
+    return cfg
+
+
+TRACE_CASES = [
+    # n, d, classes, hidden, solver, nesterov, batch, alpha
+    (150, 4, 3, [20], "adam", False, 0, 0.01),
+    (300, 64, 10, [77], "adam", False, 50, 0.3),
+    (203, 13, 0, [50], "sgd", True, 16, 0.1),
+    (203, 13, 0, [33], "sgd", False, 37, 0.0),
+    (400, 30, 2, [129], "adam", False, 100, 1.0),
+    (120, 7, 4, [], "adam", False, 32, 0.05),
+    (260, 20, 5, [40, 24], "adam", False, 64, 0.02),
+    (180, 9, 0, [17, 18, 19], "sgd", True, 48, 0.01),
+    (90, 3, 3, [1], "adam", False, 5, 0.0),
+]
+
+
+@pytest.mark.parametrize("n,d,c,hidden,solver,nesterov,bs,alpha", TRACE_CASES)
+def test_per_step_gradients_and_weights_fp32(bb, oracle, n, d, c, hidden, solver, nesterov, bs, alpha):
+    cfg = small_problem(n + d, n, d, c)
+    hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "batch_size": bs, "alpha": alpha, "lr": 0.01,
+          "momentum": 0.9, "epochs": 6, "seed": 31337 + n}
+    other = dict(hp, hidden=[5] * len(hidden), seed=1)
+    X, y, ft = bb.to_device(cfg)
+    f = 2
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    T = min(24, 6 * -(-n_tr // (bs if 0 < bs <= n_tr else n_tr)))
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [other, hp], 0, want_per_fold=True,
+                                                trace=(1, f, 0, T))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, step_begin=0, step_end=T)
+    g, th, ls = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy(), tr["loss"].cpu().numpy()
+    assert np.all(np.isfinite(g)) and np.all(np.isfinite(th))
+    c_out = c if c >= 2 else 1
+    for t in range(T):
+        assert abs(ls[t] - ref["loss"][t]) <= 1e-5 * max(1.0, abs(ref["loss"][t])), t
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_F32, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_F32, (t, name, "theta")
+    # the traced model's fold score and the untraced entry point agree with the oracle
+    assert abs(pf[1, f, 0].item() - ref["scores"][0]) < ABS_SCORE
+    s2, st2 = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [other, hp], 0)
+    torch.cuda.synchronize()
+    assert torch.equal(s2, scores) and torch.equal(st2, status)
+
+
+def forced_steps(bb, oracle, cfg, hp, f, dtype, steps, T):
+    """Single steps started from the oracle's own state (parameters and
+    moments after step t-1), so that the drift of a free run is not charged to
+    the step's arithmetic.  Yields (t, gpu_grad, gpu_theta, ref_grad, ref_theta)."""
+    c = cfg["n_classes"]
+    X, y, ft = bb.to_device(cfg)
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=T)
+    for t in steps:
+        assert 1 <= t < T
+        state = np.concatenate([ref["theta_after"][t - 1], ref["m_after"][t - 1], ref["v_after"][t - 1]])
+        st = torch.from_numpy(state.astype(np.float32)).cuda()
+        out = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], dtype, trace=(0, f, t, t + 1, st))
+        torch.cuda.synchronize()
+        tr = out[-1]
+        yield t, tr["grad"][0].cpu().numpy(), tr["theta_after"][0].cpu().numpy(), ref["grad"][t], ref["theta_after"][t]
+
+
+@pytest.mark.parametrize("n,d,c,hidden,solver,nesterov,bs,alpha", TRACE_CASES[1:5] + TRACE_CASES[6:8])
+def test_single_steps_from_oracle_state_fp32(bb, oracle, n, d, c, hidden, solver, nesterov, bs, alpha):
+    cfg = small_problem(n + d, n, d, c)
+    hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "batch_size": bs, "alpha": alpha, "lr": 0.01,
+          "momentum": 0.9, "epochs": 30, "seed": 31337 + n}
+    n_tr = int((cfg["fold_idx"] != 3).sum())
+    spe = -(-n_tr // bs)
+    T = min(30 * spe, 60)
+    c_out = c if c >= 2 else 1
+    for t, g, th, rg, rth in forced_steps(bb, oracle, cfg, hp, 3, 0, [1, spe - 1, spe, T // 2, T - 1], T):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[sl], rg[sl]) < REL_F32, (t, name, "grad")
+            assert relerr(th[sl], rth[sl]) < REL_F32, (t, name, "theta")
+
+
+@pytest.mark.parametrize("n,d,c,hidden,bs", [(600, 128, 10, [128, 160], 256), (300, 40, 3, [70], 100),
+                                             (500, 128, 10, [256, 256], 256), (200, 33, 0, [45, 31], 64)])
+def test_per_step_gradients_and_weights_bf16(bb, oracle, n, d, c, hidden, bs):
+    cfg = small_problem(n + d, n, d, c, bf16=True)
+    hp = {"hidden": hidden, "solver": "adam", "batch_size": bs, "alpha": 0.01, "lr": 0.002, "epochs": 6,
+          "seed": 4242 + n}
+    X, y, ft = bb.to_device(cfg)
+    f, T = 1, 12
+    c_out = c if c >= 2 else 1
+    # the first steps of a free run from the shared initial weights
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 1, want_per_fold=True, trace=(0, f, 0, 3))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=1, step_begin=0, step_end=3)
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    for t in range(3):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_BF16, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (t, name, "theta")
+    assert abs(pf[0, f, 0].item() - ref["scores"][0]) < ABS_SCORE
+    # later steps, each started from the oracle's state
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [1, 4, 7, 11], T):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_BF16, (t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_BF16, (t, name, "theta")
+
+
+# ----------------------------------------------------------- final scores ----
+
+def explained_flips(acc_gpu, acc_ref, n_va):
+    """Accuracy moves by 1/n_va per flipped prediction; allow the flips a 1e-3
+    score tolerance on the logits can produce (at most one row per fold)."""
+    return abs(acc_gpu - acc_ref) <= 1.0 / n_va + 1e-6
+
+
+@pytest.mark.parametrize("idx,kw", [
+    (0, {}),                                  # tiny classification, full size
+    (1, {"B": 4, "epochs": 12}),              # digits-shaped, full rows, fewer epochs
+    (2, {"B": 8, "epochs": 40}),              # regression / SGD-Nesterov
+    (3, {"B": 24, "epochs": 20}),             # many-studies shape, a slice of the suggestions
+    (4, {"B": 2, "epochs": 2, "n": 3000}),    # bf16 two-hidden-layer shape, fewer rows
+])
+def test_final_cv_scores_match_oracle(bb, oracle, idx, kw):
+    cfg = inputs.make_config(idx, **kw)
+    X, y, ft = bb.to_device(cfg)
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, cfg["hparams"], dt, want_per_fold=True)
+    torch.cuda.synchronize()
+    scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, cfg["hparams"], dtype=dt)
+    # The same runs without any fp32 rounding give each suggestion's own sensitivity to rounding
+    # ("noise").  Below a tenth of the bar the run is stable and held to 1e-3.  A run that amplifies
+    # rounding noise up to the size of the bar (bf16 operands do: one flipped rounding moves an
+    # activation by 0.4 %) is held to the bar widened by twice its own noise; beyond that (large
+    # learning rates) trajectories are chaotic and only finiteness is compared.
+    rs64, _, rpf64 = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, cfg["hparams"], dtype=dt, prec=1)
+    n_va = len(cfg["y"]) // K
+    n_strict = n_wide = 0
+    for b in range(len(cfg["hparams"])):
+        if rst[b] != 0:
+            assert status[b] == 1 and not np.isfinite(scores[b, 0])
+            continue
+        noise = np.abs(rpf[b, :, 0] - rpf64[b, :, 0]).max() if np.all(np.isfinite(rpf64[b])) else np.inf
+        if noise >= ABS_SCORE:
+            continue
+        tol = ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
+        assert status[b] == 0, b
+        assert abs(scores[b, 0] - rs[b, 0]) < tol, (b, scores[b], rs[b], noise)
+        assert np.abs(pf[b, :, 0] - rpf[b, :, 0]).max() < 2 * tol, (b, pf[b], rpf[b], noise)
+        if c >= 2 and noise < ABS_SCORE / 10:
+            for f in range(K):
+                assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (b, f)
+        n_strict += noise < ABS_SCORE / 10
+        n_wide += noise >= ABS_SCORE / 10
+    if dt == 0:
+        assert n_strict >= max(1, len(cfg["hparams"]) // 2)
+    else:
+        assert n_strict + n_wide >= 1
+
+
+def test_batch_composition_invariance_and_determinism(bb):
+    cfg = inputs.make_config(3, B=16, epochs=5)
+    X, y, ft = bb.to_device(cfg)
+    hps = cfg["hparams"]
+    s1, _ = bb.bbo_mlp_cv_eval(X, y, 2, ft, 5, hps, 0)
+    s2, _ = bb.bbo_mlp_cv_eval(X, y, 2, ft, 5, hps, 0)
+    order = [7, 3, 3, 15, 0]
+    s3, _ = bb.bbo_mlp_cv_eval(X, y, 2, ft, 5, [hps[i] for i in order], 0)
+    torch.cuda.synchronize()
+    assert torch.equal(s1, s2)
+    assert torch.equal(s3, s1[order])
+
+
+def test_edge_cases(bb, oracle):
+    cfg = small_problem(5, 60, 6, 3)
+    X, y, ft = bb.to_device(cfg)
+    base = {"hidden": [8], "batch_size": 16, "lr": 0.01, "epochs": 2, "seed": 3}
+    # B == 0
+    s, st = bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, [], 0)
+    assert s.shape[0] == 0
+    # epochs == 0 scores the initial weights; batch larger than the fold; batch of one row
+    hps = [dict(base, epochs=0), dict(base, batch_size=10**6), dict(base, batch_size=1, epochs=1), dict(base, hidden=[])]
+    s, st = bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, hps, 0)
+    torch.cuda.synchronize()
+    rs, rst, _ = oracle.cv_eval(cfg["X"], cfg["y"], 3, cfg["fold_idx"], 5, hps)
+    assert np.allclose(s.cpu().numpy()[:, 0], rs[:, 0], atol=ABS_SCORE)
+    # a fold with no held rows gives a non-finite score and status 1; rows with fold < 0 are unused
+    fold2 = cfg["fold_idx"].copy()
+    fold2[fold2 == 4] = -1
+    ft2 = torch.from_numpy(fold2).cuda()
+    s, st = bb.bbo_mlp_cv_eval(X, y, 3, ft2, 5, [base], 0)
+    s4, st4, pf4 = bb.bbo_mlp_cv_eval(X, y, 3, ft2, 4, [base], 0, want_per_fold=True)
+    torch.cuda.synchronize()
+    assert st.item() == 1 and not np.isfinite(s[0, 0].item())
+    rs4, _, rpf4 = oracle.cv_eval(cfg["X"], cfg["y"], 3, fold2, 4, [base])
+    assert st4.item() == 0 and abs(s4[0, 0].item() - rs4[0, 0]) < ABS_SCORE
+    # a divergent run flags itself and leaves its neighbour alone
+    reg = small_problem(6, 80, 5, 0)
+    Xr, yr, fr = bb.to_device(reg)
+    bad = {"hidden": [8], "solver": "sgd", "momentum": 0.99, "nesterov": True, "lr": 50.0, "batch_size": 8,
+           "epochs": 60, "seed": 1}
+    good = dict(bad, lr=0.01, momentum=0.5)
+    s, st = bb.bbo_mlp_cv_eval(Xr, yr, 0, fr, 5, [bad, good], 0)
+    torch.cuda.synchronize()
+    rs, rst, _ = oracle.cv_eval(reg["X"], reg["y"], 0, reg["fold_idx"], 5, [bad, good])
+    assert st.cpu().tolist() == [1, 0] and rst.tolist() == [1, 0]
+    assert abs(s[1, 0].item() - rs[1, 0]) < ABS_SCORE
+
+
+def test_error_codes(bb):
+    cfg = small_problem(5, 60, 6, 3)
+    X, y, ft = bb.to_device(cfg)
+    hp = {"hidden": [8], "epochs": 1}
+    with pytest.raises(bb.BboError) as e:
+        bb.bbo_mlp_cv_eval(X, y, 1, ft, 5, [hp], 0)
+    assert e.value.code == bb.INVALID_ARG
+    with pytest.raises(bb.BboError) as e:
+        bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, [dict(hp, hidden=[5000])], 0)
+    assert e.value.code == bb.UNSUPPORTED
+    with pytest.raises(bb.BboError) as e:
+        bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, [hp], 0, workspace=bb.alloc_workspace(256, X.device))
+    assert e.value.code == bb.WORKSPACE_TOO_SMALL
+    # the library still works after the failures
+    s, st = bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, [hp], 0)
+    torch.cuda.synchronize()
+    assert np.isfinite(s[0, 0].item())
