@@ -53,9 +53,10 @@ def lib():
     """Load the shared library (built by paper_2012_04201_amd/build.py)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("BBO_MLP_LIB", LIB_PATH)  # override: an alternative build of the same ABI
+        if not os.path.exists(path):
             raise ImportError("libbbo_mlp.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
-        L = C.CDLL(LIB_PATH)
+        L = C.CDLL(path)
         L.bbo_mlp_last_error.restype = C.c_char_p
         L.bbo_mlp_param_count.restype = C.c_int64
         _lib = L

@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -34,149 +35,10 @@
 
 #include "../../include/bbo_mlp.h"
 
+#include "common.h"
+#include "train_tiled_bf16.h"
+
 namespace {
-
-constexpr int MAXL = BBO_MAX_HIDDEN + 1;  // weight layers
-constexpr int NTHREADS = 256;
-constexpr uint64_t GOLDEN = 0x9E3779B97F4A7C15ull;
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-
-// ---------------------------------------------------------------------------
-// Counter-based random numbers: SplitMix64 output mixer over (key, counter).
-// ---------------------------------------------------------------------------
-__host__ __device__ inline uint64_t mix64(uint64_t z) {
-  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-  return z ^ (z >> 31);
-}
-__host__ __device__ inline uint64_t key_fold(uint64_t h, uint64_t v) { return mix64(h + (v + 1) * GOLDEN); }
-__host__ __device__ inline uint64_t key_model(uint64_t seed, int fold) {
-  return key_fold(key_fold(seed, 0x4D4C50ull), (uint64_t)fold);
-}
-__host__ __device__ inline uint64_t key_epoch(uint64_t kmodel, int epoch) {
-  return key_fold(key_fold(kmodel, 1), (uint64_t)epoch);
-}
-
-// Position p of an epoch -> index into the fold's training list: 4-round
-// balanced Feistel permutation on an even number of bits, cycle-walked into
-// [0, n).
-__device__ inline uint32_t perm_index(uint64_t key, uint32_t n, uint32_t p) {
-  if (n <= 1) return 0;
-  int bits = 32 - __builtin_clz(n - 1);
-  bits += bits & 1;
-  if (bits < 2) bits = 2;
-  const int hb = bits >> 1;
-  const uint32_t mask = (1u << hb) - 1;
-  uint32_t x = p;
-  do {
-    uint32_t Lh = x >> hb, Rh = x & mask;
-#pragma unroll
-    for (uint32_t r = 0; r < 4; r++) {
-      uint32_t F = (uint32_t)key_fold(key, ((uint64_t)r << 32) | Rh) & mask;
-      uint32_t t = Lh ^ F;
-      Lh = Rh;
-      Rh = t;
-    }
-    x = (Lh << hb) | Rh;
-  } while (x >= n);
-  return x;
-}
-
-// ---------------------------------------------------------------------------
-// Item description and per-item memory layout
-// ---------------------------------------------------------------------------
-struct ItemDesc {
-  uint64_t seed;
-  int32_t b, fold, L, solver, nesterov, batch_size, epochs, rows_cap;
-  float lr, alpha, momentum, beta1, beta2, eps;
-  int32_t dims[MAXL + 1];
-  float bound[MAXL];
-};
-
-__host__ __device__ inline int rup(int x, int m) { return (x + m - 1) / m * m; }
-
-struct Layout {
-  int32_t L, rows;
-  int32_t dims[MAXL + 1];
-  int32_t ld[MAXL + 1];    // row length of W_l ([out][ld]): roundup(dims+1, kstep)
-  int32_t kp[MAXL + 1];    // dims rounded up to the K step
-  int32_t p16[MAXL + 1];   // dims rounded up to 16
-  int32_t p16a[MAXL + 1];  // dims+1 rounded up to 16
-  int32_t cw[MAXL], cb[MAXL];  // offsets in the packed W[in][out], b[out] order
-  int32_t P;
-  uint64_t w[MAXL], m[MAXL], v[MAXL], oi[MAXL], io[MAXL];
-  uint64_t A[MAXL], AT[MAXL], D[MAXL + 1], DT[MAXL + 1], Z, rowlist, total;
-};
-
-// Byte offsets of everything one item keeps in its slot.  Used by the host to
-// size slots and by the device to address them.
-__host__ __device__ inline void make_layout(Layout& y, const int32_t* dims, int L, int rows, int kstep,
-                                            int opsz) {
-  y.L = L;
-  y.rows = rows;
-  int c = 0;
-  for (int l = 0; l <= L; l++) {
-    y.dims[l] = dims[l];
-    y.ld[l] = rup(dims[l] + 1, kstep);
-    y.kp[l] = rup(dims[l], kstep);
-    y.p16[l] = rup(dims[l], 16);
-    y.p16a[l] = rup(dims[l] + 1, 16);
-  }
-  for (int l = 0; l < L; l++) {
-    y.cw[l] = c;
-    c += dims[l] * dims[l + 1];
-    y.cb[l] = c;
-    c += dims[l + 1];
-  }
-  y.P = c;
-  uint64_t off = 0;
-  auto take = [&](uint64_t bytes) {
-    uint64_t o = off;
-    off += (bytes + 255) & ~(uint64_t)255;
-    return o;
-  };
-  for (int l = 0; l < L; l++) {
-    uint64_t wn = (uint64_t)y.p16[l + 1] * y.ld[l];
-    y.w[l] = take(wn * 4);
-    y.m[l] = take(wn * 4);
-    y.v[l] = take(wn * 4);
-    y.oi[l] = opsz == 4 ? y.w[l] : take(wn * opsz);
-    y.io[l] = l >= 1 ? take((uint64_t)y.p16[l] * y.kp[l + 1] * opsz) : 0;
-    y.A[l] = take((uint64_t)rows * y.kp[l] * opsz);
-    y.AT[l] = take((uint64_t)y.p16a[l] * rows * opsz);
-  }
-  y.D[0] = y.DT[0] = 0;
-  for (int l = 1; l <= L; l++) {
-    y.D[l] = take((uint64_t)rows * y.kp[l] * opsz);
-    y.DT[l] = take((uint64_t)y.p16[l] * rows * opsz);
-  }
-  y.Z = take((uint64_t)rows * y.p16[L] * 4);
-  y.rowlist = take((uint64_t)rows * 4);
-  y.total = off;
-}
-
-struct TrainParams {
-  const void* X;
-  const void* y;
-  const int32_t* train_idx;
-  const int32_t* val_idx;
-  const int32_t* counts;
-  const ItemDesc* items;
-  int32_t* queue;
-  float* item_out;  // [B*K][2]
-  char* slots;
-  uint64_t slot_bytes;
-  int64_t n;
-  int32_t d, n_classes, n_folds, n_items;
-  // trace
-  int32_t trace_item;  // b*K+fold or -1
-  int64_t step_begin, step_end;
-  float* trace_out;
-  const float* state_in;  // optional [3P]: parameters, m, v of the traced item before step_begin
-};
 
 // ---------------------------------------------------------------------------
 // Operand types
@@ -266,17 +128,6 @@ __device__ inline void wg_gemm(const OpT* A, int lda, const OpT* B, int ldb, int
     wg_gemm_blk<OpT, 2, 2>(A, lda, B, ldb, Mt, Nt, K, epi);
 }
 
-__device__ inline double block_sum(double v, double* red) {
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  __syncthreads();
-  if (lane == 0) red[wave] = v;
-  __syncthreads();
-  double t = 0.0;
-  for (int w = 0; w < nw; w++) t += red[w];
-  return t;
-}
-
 // Per-row loss on the outputs z[0..c): returns the row's loss (cross-entropy,
 // or squared error) and whether the prediction is correct; optionally writes
 // the output delta (p - onehot)/m or (z - y)/m.
@@ -353,7 +204,6 @@ __global__ __launch_bounds__(NTHREADS) void k_fold_lists(const int32_t* __restri
   }
 }
 
-__device__ inline int eff_batch(int bs, int n_tr) { return (bs <= 0 || bs > n_tr) ? n_tr : bs; }
 
 // ---------------------------------------------------------------------------
 // The training / scoring kernel: persistent workgroups, one item at a time.
@@ -713,7 +563,7 @@ __global__ __launch_bounds__(NTHREADS) void k_train(const TrainParams P) {
     const int item = s_item;
     if (item >= P.n_items) break;
     if (threadIdx.x == 0) {
-      desc = P.items[item];
+      desc = ((const ItemDesc*)P.items)[item];
       make_layout(lay, desc.dims, desc.L, desc.rows_cap, Op<OpT>::KSTEP, (int)sizeof(OpT));
     }
     __syncthreads();
@@ -838,6 +688,8 @@ struct Plan {
   std::vector<ItemDesc> items;  // sorted, most expensive first
   uint64_t slot_bytes = 0;
   int n_slots = 0;
+  bool tiled = false;     // every item fits the LDS-tiled bf16 kernel
+  uint32_t lds_bytes = 0; // dynamic LDS of that kernel
   // workspace byte offsets
   uint64_t o_items = 0, o_queue = 0, o_out = 0, o_train = 0, o_val = 0, o_counts = 0, o_slots = 0, total = 0;
 };
@@ -859,9 +711,28 @@ int device_slots(int dtype, int* out) {
   return BBO_OK;
 }
 
+int device_cus(int* out) {
+  static thread_local int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  }
+  *out = cus;
+  return BBO_OK;
+}
+
+bool force_generic() {
+  const char* e = getenv("BBO_MLP_FORCE_GENERIC");
+  return e && e[0] == '1';
+}
+
 int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_mlp_hparams* hp, int B,
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
+  bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic();
+  uint64_t tslot = 0;
+  uint32_t tlds = 0;
   pl.items.clear();
   pl.items.reserve((size_t)B * n_folds);
   std::vector<double> cost;
@@ -896,6 +767,15 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     Layout y;
     make_layout(y, it.dims, it.L, it.rows_cap, kstep, opsz);
     slot = std::max<uint64_t>(slot, y.total);
+    if (tiled && tiled_eligible(it.dims, it.L)) {
+      TLay ty;
+      make_tlay(ty, it.dims, it.L);
+      tslot = std::max<uint64_t>(tslot, ty.total);
+      tlds = std::max<uint32_t>(tlds, ty.lds_total);
+      if (ty.lds_total > TB_LDS_LIMIT) tiled = false;
+    } else {
+      tiled = false;
+    }
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
@@ -912,8 +792,11 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   pl.items.swap(sorted);
 
   int max_slots = 0;
-  int rc = device_slots(dtype, &max_slots);
+  int rc = tiled ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
   if (rc) return rc;
+  pl.tiled = tiled;
+  pl.lds_bytes = tlds;
+  if (tiled) slot = tslot;
   pl.slot_bytes = (slot + 255) & ~(uint64_t)255;
   pl.n_slots = (int)std::min<size_t>(pl.items.size(), (size_t)max_slots);
   uint64_t off = 0;
@@ -923,7 +806,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     return o;
   };
   const uint64_t nn = (uint64_t)std::max<int64_t>(n, 1);
-  pl.o_items = take(sizeof(ItemDesc) * std::max<size_t>(pl.items.size(), 1));
+  pl.o_items = take((tiled ? sizeof(TItem) : sizeof(ItemDesc)) * std::max<size_t>(pl.items.size(), 1));
   pl.o_queue = take(256);
   pl.o_out = take(8ull * std::max<size_t>(pl.items.size(), 1));
   pl.o_train = take(4ull * nn * n_folds);
@@ -944,8 +827,7 @@ struct Staging {
 };
 thread_local Staging g_stage;
 
-int stage_items(const std::vector<ItemDesc>& items, void* dst, hipStream_t s) {
-  const size_t bytes = items.size() * sizeof(ItemDesc);
+int stage_items(const void* src, size_t bytes, void* dst, hipStream_t s) {
   if (!g_stage.ev) HIP_TRY(hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming));
   if (g_stage.pending) {
     HIP_TRY(hipEventSynchronize(g_stage.ev));
@@ -958,7 +840,7 @@ int stage_items(const std::vector<ItemDesc>& items, void* dst, hipStream_t s) {
     HIP_TRY(hipHostMalloc(&g_stage.ptr, bytes, hipHostMallocDefault));
     g_stage.cap = bytes;
   }
-  memcpy(g_stage.ptr, items.data(), bytes);
+  memcpy(g_stage.ptr, src, bytes);
   HIP_TRY(hipMemcpyAsync(dst, g_stage.ptr, bytes, hipMemcpyHostToDevice, s));
   HIP_TRY(hipEventRecord(g_stage.ev, s));
   g_stage.pending = true;
@@ -1003,7 +885,16 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   if (workspace_bytes < pl.total) return fail(BBO_WORKSPACE_TOO_SMALL, "workspace too small");
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  rc = stage_items(pl.items, ws + pl.o_items, s);
+  if (pl.tiled) {
+    std::vector<TItem> ti(pl.items.size());
+    for (size_t i = 0; i < ti.size(); i++) {
+      ti[i].d = pl.items[i];
+      make_tlay(ti[i].y, pl.items[i].dims, pl.items[i].L);
+    }
+    rc = stage_items(ti.data(), ti.size() * sizeof(TItem), ws + pl.o_items, s);
+  } else {
+    rc = stage_items(pl.items.data(), pl.items.size() * sizeof(ItemDesc), ws + pl.o_items, s);
+  }
   if (rc) return rc;
 
   TrainParams P;
@@ -1013,7 +904,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   P.train_idx = (const int32_t*)(ws + pl.o_train);
   P.val_idx = (const int32_t*)(ws + pl.o_val);
   P.counts = (const int32_t*)(ws + pl.o_counts);
-  P.items = (const ItemDesc*)(ws + pl.o_items);
+  P.items = ws + pl.o_items;
   P.queue = (int32_t*)(ws + pl.o_queue);
   P.item_out = (float*)(ws + pl.o_out);
   P.slots = ws + pl.o_slots;
@@ -1032,7 +923,11 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   hipLaunchKernelGGL(k_fold_lists, dim3(n_folds), dim3(NTHREADS), 0, s, fold_idx, n, (int32_t*)(ws + pl.o_train),
                      (int32_t*)(ws + pl.o_val), (int32_t*)(ws + pl.o_counts), P.queue);
   HIP_TRY(hipGetLastError());
-  if (dtype == BBO_F32)
+  if (pl.tiled) {
+    HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)pl.lds_bytes));
+    hipLaunchKernelGGL(k_train_tiled, dim3(pl.n_slots), dim3(TB_THREADS), pl.lds_bytes, s, P);
+  } else if (dtype == BBO_F32)
     hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
   else
     hipLaunchKernelGGL(k_train<__bf16>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
