@@ -37,6 +37,7 @@
 
 #include "common.h"
 #include "train_tiled_bf16.h"
+#include "train_small_f32.h"
 
 namespace {
 
@@ -689,7 +690,8 @@ struct Plan {
   uint64_t slot_bytes = 0;
   int n_slots = 0;
   bool tiled = false;     // every item fits the LDS-tiled bf16 kernel
-  uint32_t lds_bytes = 0; // dynamic LDS of that kernel
+  bool small = false;     // every item fits the LDS-resident fp32 kernel
+  uint32_t lds_bytes = 0; // dynamic LDS of the chosen kernel
   // workspace byte offsets
   uint64_t o_items = 0, o_queue = 0, o_out = 0, o_train = 0, o_val = 0, o_counts = 0, o_slots = 0, total = 0;
 };
@@ -731,8 +733,9 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
   bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic();
+  bool small = dtype == BBO_F32 && B > 0 && !force_generic();
   uint64_t tslot = 0;
-  uint32_t tlds = 0;
+  uint32_t tlds = 0, slds = 0;
   pl.items.clear();
   pl.items.reserve((size_t)B * n_folds);
   std::vector<double> cost;
@@ -776,6 +779,14 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     } else {
       tiled = false;
     }
+    if (small && small_eligible(it.dims, it.L)) {
+      SLay sy;
+      make_slay(sy, it.dims);
+      slds = std::max<uint32_t>(slds, sy.lds_total);
+      if (sy.lds_total > SM_LDS_LIMIT) small = false;
+    } else {
+      small = false;
+    }
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
@@ -792,11 +803,14 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   pl.items.swap(sorted);
 
   int max_slots = 0;
-  int rc = tiled ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
+  int rc = (tiled || small) ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
   if (rc) return rc;
+  if (small) max_slots *= std::min<int>(2, std::max<int>(1, (int)((160u * 1024u) / (slds + 1024u))));
   pl.tiled = tiled;
-  pl.lds_bytes = tlds;
+  pl.small = small;
+  pl.lds_bytes = tiled ? tlds : slds;
   if (tiled) slot = tslot;
+  if (small) slot = 256;  // the model lives in LDS; no per-slot global memory
   pl.slot_bytes = (slot + 255) & ~(uint64_t)255;
   pl.n_slots = (int)std::min<size_t>(pl.items.size(), (size_t)max_slots);
   uint64_t off = 0;
@@ -806,7 +820,8 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     return o;
   };
   const uint64_t nn = (uint64_t)std::max<int64_t>(n, 1);
-  pl.o_items = take((tiled ? sizeof(TItem) : sizeof(ItemDesc)) * std::max<size_t>(pl.items.size(), 1));
+  pl.o_items = take((tiled ? sizeof(TItem) : small ? sizeof(SItem) : sizeof(ItemDesc)) *
+                    std::max<size_t>(pl.items.size(), 1));
   pl.o_queue = take(256);
   pl.o_out = take(8ull * std::max<size_t>(pl.items.size(), 1));
   pl.o_train = take(4ull * nn * n_folds);
@@ -892,6 +907,13 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
       make_tlay(ti[i].y, pl.items[i].dims, pl.items[i].L);
     }
     rc = stage_items(ti.data(), ti.size() * sizeof(TItem), ws + pl.o_items, s);
+  } else if (pl.small) {
+    std::vector<SItem> si(pl.items.size());
+    for (size_t i = 0; i < si.size(); i++) {
+      si[i].d = pl.items[i];
+      make_slay(si[i].y, pl.items[i].dims);
+    }
+    rc = stage_items(si.data(), si.size() * sizeof(SItem), ws + pl.o_items, s);
   } else {
     rc = stage_items(pl.items.data(), pl.items.size() * sizeof(ItemDesc), ws + pl.o_items, s);
   }
@@ -927,6 +949,10 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)pl.lds_bytes));
     hipLaunchKernelGGL(k_train_tiled, dim3(pl.n_slots), dim3(TB_THREADS), pl.lds_bytes, s, P);
+  } else if (pl.small) {
+    HIP_TRY(hipFuncSetAttribute((const void*)k_train_small, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)pl.lds_bytes));
+    hipLaunchKernelGGL(k_train_small, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
   } else if (dtype == BBO_F32)
     hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
   else

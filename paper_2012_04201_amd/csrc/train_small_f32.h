@@ -1,6 +1,6 @@
 // LDS-resident training / scoring kernel for small fp32 models with one hidden
 // layer (the "many concurrent studies" shape: up to 63 inputs, hidden width up
-// to 256, up to 4 outputs).
+// to 240, up to 4 outputs).
 //
 // One workgroup (4 waves) trains one model, and the model never leaves the
 // chip: weights and both optimizer moments of the two layers stay in LDS for
@@ -41,7 +41,7 @@ struct SItem {
 };
 
 __host__ __device__ inline bool small_eligible(const int32_t* dims, int L) {
-  return L == 2 && dims[0] <= 63 && dims[1] <= 256 && dims[2] <= 4;
+  return L == 2 && dims[0] <= 63 && dims[1] <= 240 && dims[2] <= 4;  // thread HP (<= 240) owns the output bias
 }
 
 __host__ __device__ inline void make_slay(SLay& y, const int32_t* dims) {
@@ -512,7 +512,7 @@ struct Small {
   }
 };
 
-__global__ __launch_bounds__(SM_THREADS) void k_train_small(const TrainParams P) {
+__global__ __launch_bounds__(SM_THREADS, 2) void k_train_small(const TrainParams P) {
   extern __shared__ __align__(16) char smem[];
   __shared__ int s_item;
   __shared__ double red[SM_THREADS / 64];
