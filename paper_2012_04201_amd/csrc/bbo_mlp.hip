@@ -805,7 +805,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   int max_slots = 0;
   int rc = (tiled || small) ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
   if (rc) return rc;
-  if (small) max_slots *= std::min<int>(2, std::max<int>(1, (int)((160u * 1024u) / (slds + 1024u))));
+  if (small) max_slots *= 2;  // the kernel's LDS footprint is capped at half a CU's LDS
   pl.tiled = tiled;
   pl.small = small;
   pl.lds_bytes = tiled ? tlds : slds;
@@ -950,9 +950,16 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
                                 (int)pl.lds_bytes));
     hipLaunchKernelGGL(k_train_tiled, dim3(pl.n_slots), dim3(TB_THREADS), pl.lds_bytes, s, P);
   } else if (pl.small) {
-    HIP_TRY(hipFuncSetAttribute((const void*)k_train_small, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)pl.lds_bytes));
-    hipLaunchKernelGGL(k_train_small, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
+    const int kt = d + 1 <= 16 ? 1 : (d + 1 <= 32 ? 2 : 4);
+    const void* fn = kt == 1 ? (const void*)k_train_small<1>
+                             : (kt == 2 ? (const void*)k_train_small<2> : (const void*)k_train_small<4>);
+    HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
+    if (kt == 1)
+      hipLaunchKernelGGL(k_train_small<1>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
+    else if (kt == 2)
+      hipLaunchKernelGGL(k_train_small<2>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
+    else
+      hipLaunchKernelGGL(k_train_small<4>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
   } else if (dtype == BBO_F32)
     hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
   else

@@ -609,7 +609,7 @@ struct Tiled {
     return block_sum(s, red);
   }
 
-  __device__ void run() const {
+  __device__ __forceinline__ void run() const {
     const int f = it.fold, L = y.L;
     const int n_tr = P.counts[2 * f], n_va = P.counts[2 * f + 1];
     const int32_t* tr = P.train_idx + (int64_t)f * P.n;
