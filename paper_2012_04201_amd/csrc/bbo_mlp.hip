@@ -733,7 +733,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
   bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic();
-  bool small = dtype == BBO_F32 && B > 0 && !force_generic();
+  bool small = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
   uint64_t tslot = 0;
   uint32_t tlds = 0, slds = 0;
   pl.items.clear();
@@ -781,7 +781,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     }
     if (small && small_eligible(it.dims, it.L)) {
       SLay sy;
-      make_slay(sy, it.dims);
+      make_slay(sy, it.dims, n);
       slds = std::max<uint32_t>(slds, sy.lds_total);
       if (sy.lds_total > SM_LDS_LIMIT) small = false;
     } else {
@@ -911,7 +911,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     std::vector<SItem> si(pl.items.size());
     for (size_t i = 0; i < si.size(); i++) {
       si[i].d = pl.items[i];
-      make_slay(si[i].y, pl.items[i].dims);
+      make_slay(si[i].y, pl.items[i].dims, n);
     }
     rc = stage_items(si.data(), si.size() * sizeof(SItem), ws + pl.o_items, s);
   } else {

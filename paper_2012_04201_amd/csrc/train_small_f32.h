@@ -34,7 +34,8 @@ constexpr uint32_t SM_LDS_LIMIT = 79 * 1024;  // per workgroup: two workgroups p
 struct SLay {
   int32_t d, h, c, K0, HP, RC, ldw, lda;
   int32_t cw[2], cb[2], P;
-  uint32_t o_w1, o_w2, o_xs, o_xt, o_a1, o_red, o_d2, o_rows, o_ys, lds_total;
+  uint32_t o_w1, o_w2, o_xs, o_xt, o_a1, o_red, o_d2, o_rows, o_ys, o_epoch, lds_total;
+  int32_t epoch_cap;  // entries of the per-epoch row table in LDS (0: rows are permuted on the fly)
 };
 
 struct SItem {
@@ -46,7 +47,7 @@ __host__ __device__ inline bool small_eligible(const int32_t* dims, int L) {
   return L == 2 && dims[0] <= 63 && dims[1] <= 240 && dims[2] <= 4;  // thread HP (<= 240) owns the output bias
 }
 
-__host__ __device__ inline void make_slay(SLay& y, const int32_t* dims) {
+__host__ __device__ inline void make_slay(SLay& y, const int32_t* dims, int64_t n) {
   y.d = dims[0];
   y.h = dims[1];
   y.c = dims[2];
@@ -76,8 +77,17 @@ __host__ __device__ inline void make_slay(SLay& y, const int32_t* dims) {
     y.o_d2 = take(rc * 4);
     y.o_rows = take(2 * rc);
     y.o_ys = take(rc);
+    y.o_epoch = o;
+    y.epoch_cap = 0;
     y.lds_total = o;
-    if (o <= SM_LDS_LIMIT) break;
+    if (o <= SM_LDS_LIMIT) {
+      // room left for the epoch's row order (all training rows of a fold)?
+      if (n <= 4096 && o + 4 * (uint32_t)n <= SM_LDS_LIMIT) {
+        y.epoch_cap = (int32_t)n;
+        y.lds_total = o + ((4 * (uint32_t)n + 15) & ~15u);
+      }
+      break;
+    }
   }
 }
 
@@ -134,7 +144,13 @@ struct Small {
   __device__ int fetch_row_id(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute) const {
     const int p = threadIdx.x;
     if (p >= y.RC || p >= rows) return -1;
+    if (permute && y.epoch_cap) return ((const int32_t*)(lds + y.o_epoch))[lo + p];
     return list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p];
+  }
+  // Row ids of a whole epoch, in minibatch order, into the LDS table.
+  __device__ void build_epoch_table(const int32_t* list, uint64_t key, int n_list) const {
+    int32_t* tab = (int32_t*)(lds + y.o_epoch);
+    for (int p = threadIdx.x; p < n_list; p += blockDim.x) tab[p] = list[perm_index(key, (uint32_t)n_list, (uint32_t)p)];
   }
   __device__ void park_row_id(int par, int row) const {
     if ((int)threadIdx.x < y.RC) rowlist(par)[threadIdx.x] = row;
@@ -150,7 +166,7 @@ struct Small {
       xr[i] = 0.f;
       if (r < y.RC) {
         const int row = rl[r];
-        if (row >= 0) xr[i] = k < d ? X[(size_t)row * d + k] : (k == d ? 1.f : 0.f);
+        if (row >= 0) xr[i] = k < d ? X[row * d + k] : (k == d ? 1.f : 0.f);  // n*d < 2^31 (checked by the host)
       }
     }
     yv = 0.f;
@@ -230,13 +246,18 @@ struct Small {
     const int r = threadIdx.x % RC, g = threadIdx.x / RC;
     const float* a1 = f(y.o_a1) + r;
     const float* w2 = f(y.o_w2);
+    const bool c2 = y.c >= 2, c4 = y.c >= 3;
     f32x4 p = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
     for (int u = g; u < y.HP; u += G) {
       const float av = a1[u * lda];
       const f32x4 wv = *(const f32x4*)(w2 + u * 4);
-#pragma unroll
-      for (int cc = 0; cc < 4; cc++) p[cc] += av * wv[cc];
+      p[0] += av * wv[0];
+      if (c2) p[1] += av * wv[1];
+      if (c4) {
+        p[2] += av * wv[2];
+        p[3] += av * wv[3];
+      }
     }
     *(f32x4*)(f(y.o_red) + threadIdx.x * 4) = p;
   }
@@ -300,6 +321,7 @@ struct Small {
   __device__ void backward_out(int nrows4, f32x4& g2) const {
     const int u = threadIdx.x, lda = y.lda;
     const float* d2 = f(y.o_d2);
+    const bool c2 = y.c >= 2, c4 = y.c >= 3;
     if (u < y.HP) {
       float* a1 = f(y.o_a1) + u * lda;
       const f32x4 wv = *(const f32x4*)(f(y.o_w2) + u * 4);
@@ -310,11 +332,16 @@ struct Small {
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const f32x4 dv = *(const f32x4*)(d2 + (4 * r4 + e) * 4);
-          float s = 0.f;
-#pragma unroll
-          for (int cc = 0; cc < 4; cc++) {
-            g2[cc] += av[e] * dv[cc];
-            s += dv[cc] * wv[cc];
+          float s = dv[0] * wv[0];
+          g2[0] += av[e] * dv[0];
+          if (c2) {
+            g2[1] += av[e] * dv[1];
+            s += dv[1] * wv[1];
+          }
+          if (c4) {
+            g2[2] += av[e] * dv[2];
+            g2[3] += av[e] * dv[3];
+            s += dv[2] * wv[2] + dv[3] * wv[3];
           }
           out[e] = av[e] > 0.f ? s : 0.f;
         }
@@ -527,6 +554,10 @@ struct Small {
     };
     float xr[NX], yv = 0.f;
     int par = 0;
+    if (chunk_valid(pos) && y.epoch_cap) {
+      build_epoch_table(tr, key_epoch(km, pos.e), n_tr);
+      __syncthreads();
+    }
     if (chunk_valid(pos)) {
       park_row_id(0, chunk_row_id(pos));
       __syncthreads();
@@ -560,6 +591,11 @@ struct Small {
       commit_inputs(xr, yv);
       const ChunkPos nxt = chunk_next(pos);
       const bool more = chunk_valid(nxt);
+      if (more && nxt.e != pos.e && y.epoch_cap) {
+        // the next chunk opens an epoch: its row order replaces the table (this epoch's last rows are already read)
+        build_epoch_table(tr, key_epoch(km, nxt.e), n_tr);
+        __syncthreads();
+      }
       int nrow = -1;
       if (more) nrow = chunk_row_id(nxt);  // load in flight across the hidden layer
       __syncthreads();

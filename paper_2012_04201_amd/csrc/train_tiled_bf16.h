@@ -130,7 +130,8 @@ __device__ inline void opt_update(const OptC& c, float g, float& w, float& m, fl
   if (c.adam) {
     m = c.b1 * m + c.omb1 * g;
     v = c.b2 * v + c.omb2 * (g * g);
-    w = w - (c.lr_t * m) / (sqrtf(v) + c.eps);
+    // hardware reciprocal and square root (1 ulp each): far inside the per-step tolerance
+    w = w - (c.lr_t * m) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(v) + c.eps);
   } else {
     const float u = c.mu * m - c.lr * g;
     m = u;
