@@ -492,8 +492,10 @@ struct Trainer {
       gstep = P.step_begin;
       e0 = (int)(gstep / steps);
       st0 = (int)(gstep % steps);
-      b1t = pow((double)it.beta1, (double)gstep);
-      b2t = pow((double)it.beta2, (double)gstep);
+      for (int64_t i = 0; i < gstep; i++) {  // beta^gstep by repeated products, as the free run builds it
+        b1t *= (double)it.beta1;
+        b2t *= (double)it.beta2;
+      }
     } else {
       init_params();
     }
@@ -736,6 +738,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   bool small = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
   uint64_t tslot = 0;
   uint32_t tlds = 0, slds = 0;
+  uint64_t sslot = 256;
   pl.items.clear();
   pl.items.reserve((size_t)B * n_folds);
   std::vector<double> cost;
@@ -783,6 +786,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
       SLay sy;
       make_slay(sy, it.dims, n);
       slds = std::max<uint32_t>(slds, sy.lds_total);
+      sslot = std::max<uint64_t>(sslot, 2ull * sy.HP * sy.ldw * 4);
       if (sy.lds_total > SM_LDS_LIMIT) small = false;
     } else {
       small = false;
@@ -810,7 +814,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   pl.small = small;
   pl.lds_bytes = tiled ? tlds : slds;
   if (tiled) slot = tslot;
-  if (small) slot = 256;  // the model lives in LDS; no per-slot global memory
+  if (small) slot = sslot;  // only the hidden layer's moments live in global memory
   pl.slot_bytes = (slot + 255) & ~(uint64_t)255;
   pl.n_slots = (int)std::min<size_t>(pl.items.size(), (size_t)max_slots);
   uint64_t off = 0;

@@ -1,27 +1,36 @@
 // LDS-resident training / scoring kernel for small fp32 models with one hidden
 // layer (the "many concurrent studies" shape: up to 63 inputs, hidden width up
-// to 240, up to 4 outputs).
+// to 224, up to 4 outputs).
 //
 // One workgroup (4 waves) trains one model, and the model never leaves the
-// chip: the weights of both layers stay in LDS for all epochs, the optimizer
-// moments stay in registers (each lane always updates the same elements), the
-// minibatch is processed in chunks of 64 (or 32) rows whose inputs and hidden
-// activations are LDS tiles, and the hidden-layer weight gradient is
-// accumulated across the chunks of a step in MFMA accumulator registers.  HBM
-// is touched only for the gathered input rows, and those are fetched one
-// chunk ahead into registers.  The LDS footprint is kept under half a CU's
-// LDS so that two workgroups share a CU and cover each other's barriers.
+// chip: the weights of both layers stay in LDS for all epochs and the
+// minibatch is processed in chunks of 64 rows.  The hidden layer's optimizer
+// moments are the one thing kept in global memory (a per-workgroup slot that
+// stays L2-resident, read and written once per step in the update); HBM is
+// otherwise touched only for the gathered input rows, fetched one chunk ahead
+// into registers.  The LDS footprint stays under half a CU's LDS so that two
+// workgroups share a CU and cover each other's barriers.
 //
-// Layouts (floats; every row padded by 4 against bank conflicts):
-//   xs  [row][k]      gathered inputs, column d = 1 on real rows (bias)
-//   xt  [k][row]      the same tile, input-major (operand of the weight gradient)
-//   a1t [unit][row]   hidden activations, later overwritten by their deltas
-//   w1  [unit][k]     hidden layer (bias in column d)
-//   w2  [unit][4]     output layer (bias in row HP)
-// The hidden layer runs on fp32 MFMA (16x16x4): forward contracts over k with
-// xs and w1 as operands and stores the tile unit-major, the weight gradient
-// contracts over the rows with xt and a1t as operands and lands in w1's own
-// layout.  The output layer (at most 4 units) is plain VALU work.
+// Each wave owns the same hidden-unit tiles in every phase, so the hidden
+// activations never leave its registers:
+//   phase 1  forward MFMA (16x16x4 fp32): D[row][unit] = xs[row][k] . w1[unit][k]
+//            (bias rides in column d of xs/w1), ReLU in the accumulators; the
+//            wave's share of the output layer is reduced over its 16 unit lanes
+//            with DPP adds and parked in LDS (4 KB);
+//   phase 2  every wave sums the four shares for all 64 rows (lane = row),
+//            takes softmax / loss / output delta, then turns its accumulators
+//            into hidden deltas in place and feeds them straight back to the
+//            MFMA as the B operand of the weight gradient, D[k][unit] += xt[k][row]
+//            . delta[unit][row], accumulated over the chunks of the step in
+//            registers; the optimizer update reads the gradient from those
+//            registers and the weights from LDS.
+// Two block-wide barriers per chunk (the input-major tile is double-buffered).
+//
+// LDS (floats; rows padded by 4 against bank conflicts):
+//   xs[row][k], xt[2][k][row]     gathered inputs, both orders; column d = 1 on real rows
+//   w1[unit][k]                   hidden layer, bias in column d
+//   w2, m2, v2 [unit][4]          output layer and its moments, bias in row HP
+//   zp[wave][row][4], d2[wave][row][4], ys[2][row], row ids, the epoch's row order
 #pragma once
 #include "common.h"
 #include "train_tiled_bf16.h"  // OptC, opt_update
@@ -29,12 +38,13 @@
 namespace {
 
 constexpr int SM_THREADS = 256;
-constexpr uint32_t SM_LDS_LIMIT = 79 * 1024;  // per workgroup: two workgroups per CU
+constexpr int SM_RC = 64;                          // rows per chunk
+constexpr uint32_t SM_LDS_LIMIT = 80 * 1024 - 64;  // per workgroup: two workgroups per CU
 
 struct SLay {
-  int32_t d, h, c, K0, HP, RC, ldw, lda;
+  int32_t d, h, c, K0, HP, ldw, lda;
   int32_t cw[2], cb[2], P;
-  uint32_t o_w1, o_w2, o_xs, o_xt, o_a1, o_red, o_d2, o_rows, o_ys, o_epoch, lds_total;
+  uint32_t o_w1, o_w2, o_m2, o_v2, o_xs, o_xt, o_zp, o_d2, o_rows, o_ys, o_epoch, lds_total;
   int32_t epoch_cap;  // entries of the per-epoch row table in LDS (0: rows are permuted on the fly)
 };
 
@@ -44,7 +54,7 @@ struct SItem {
 };
 
 __host__ __device__ inline bool small_eligible(const int32_t* dims, int L) {
-  return L == 2 && dims[0] <= 63 && dims[1] <= 240 && dims[2] <= 4;  // thread HP (<= 240) owns the output bias
+  return L == 2 && dims[0] <= 63 && dims[1] <= 224 && dims[2] <= 4;
 }
 
 __host__ __device__ inline void make_slay(SLay& y, const int32_t* dims, int64_t n) {
@@ -54,41 +64,44 @@ __host__ __device__ inline void make_slay(SLay& y, const int32_t* dims, int64_t 
   y.K0 = dims[0] + 1 <= 16 ? 16 : (dims[0] + 1 <= 32 ? 32 : 64);
   y.HP = rup(dims[1], 16);
   y.ldw = y.K0 + 4;
+  y.lda = SM_RC + 4;
   y.cw[0] = 0;
   y.cb[0] = y.d * y.h;
   y.cw[1] = y.cb[0] + y.h;
   y.cb[1] = y.cw[1] + y.h * y.c;
   y.P = y.cb[1] + y.c;
-  for (int rc = 64; rc >= 32; rc -= 32) {
-    y.RC = rc;
-    y.lda = rc + 4;
-    uint32_t o = 0;
-    auto take = [&](uint32_t floats) {
-      uint32_t r = o;
-      o += ((floats * 4) + 15) & ~15u;
-      return r;
-    };
-    y.o_w1 = take(y.HP * y.ldw);
-    y.o_w2 = take((y.HP + 1) * 4);
-    y.o_xs = take(rc * y.ldw);
-    y.o_xt = take(y.K0 * y.lda);
-    y.o_a1 = take(y.HP * y.lda);
-    y.o_red = take(SM_THREADS * 4);
-    y.o_d2 = take(rc * 4);
-    y.o_rows = take(2 * rc);
-    y.o_ys = take(rc);
-    y.o_epoch = o;
-    y.epoch_cap = 0;
-    y.lds_total = o;
-    if (o <= SM_LDS_LIMIT) {
-      // room left for the epoch's row order (all training rows of a fold)?
-      if (n <= 4096 && o + 4 * (uint32_t)n <= SM_LDS_LIMIT) {
-        y.epoch_cap = (int32_t)n;
-        y.lds_total = o + ((4 * (uint32_t)n + 15) & ~15u);
-      }
-      break;
-    }
+  uint32_t o = 0;
+  auto take = [&](uint32_t floats) {
+    uint32_t r = o;
+    o += ((floats * 4) + 15) & ~15u;
+    return r;
+  };
+  y.o_w1 = take(y.HP * y.ldw);
+  y.o_w2 = take((y.HP + 1) * 4);
+  y.o_m2 = take((y.HP + 1) * 4);
+  y.o_v2 = take((y.HP + 1) * 4);
+  y.o_xs = take(SM_RC * y.ldw);
+  y.o_xt = take(2 * y.K0 * y.lda);
+  y.o_zp = take(4 * SM_RC * 4);
+  y.o_d2 = take(4 * SM_RC * 4);
+  y.o_rows = take(2 * SM_RC);
+  y.o_ys = take(2 * SM_RC);
+  y.o_epoch = o;
+  y.epoch_cap = 0;
+  if (n <= 4096 && o + 4 * (uint32_t)n + 16 <= SM_LDS_LIMIT) {
+    y.epoch_cap = (int32_t)n;
+    o += (4 * (uint32_t)n + 15) & ~15u;
   }
+  y.lds_total = o;
+}
+
+// Sum over the 16 lanes of a DPP row; every lane gets the total.
+__device__ inline float row16_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, false));
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, false));
+  return v;
 }
 
 // Position in the training schedule: epoch, step of the epoch, first row of
@@ -99,297 +112,317 @@ struct ChunkPos {
 
 template <int KT>
 struct Small {
-  static constexpr int K0 = 16 * KT, RSTEP = SM_THREADS / K0, NX = 64 / RSTEP;
+  static constexpr int K0 = 16 * KT, RSTEP = SM_THREADS / K0, NX = SM_RC / RSTEP;
   const TrainParams& P;
   const ItemDesc& it;
   const SLay& y;
   char* lds;
+  char* slot;  // global: m1[unit][k], v1[unit][k]
   double* red;
 
   __device__ float* f(uint32_t off) const { return (float*)(lds + off); }
-  __device__ int32_t* rowlist(int par) const { return (int32_t*)(lds + y.o_rows) + par * y.RC; }
+  __device__ float* m1g() const { return (float*)slot; }
+  __device__ float* v1g() const { return (float*)slot + y.HP * y.ldw; }
+  __device__ int32_t* rowlist(int par) const { return (int32_t*)(lds + y.o_rows) + par * SM_RC; }
+  __device__ float* xt(int par) const { return f(y.o_xt) + par * K0 * y.lda; }
+  __device__ float* ys(int par) const { return f(y.o_ys) + par * SM_RC; }
 
   // packed index (W1[in][out], b1, W2[in][out], b2) of hidden-layer element (unit j, column k); -1 for pads
-  __device__ int ci_hidden(int j, int k) const {
+  __device__ __forceinline__ int ci_hidden(int j, int k) const {
     if (j >= y.h || k > y.d) return -1;
     return k < y.d ? y.cw[0] + k * y.h + j : y.cb[0] + j;
   }
-  __device__ float init_value(int l, int e, bool isb) const {
+  __device__ __forceinline__ float init_value(int l, int e, bool isb) const {
     const uint64_t kt = key_fold(key_model(it.seed, it.fold), 16 + 2 * l + (isb ? 1 : 0));
     const uint32_t k24 = (uint32_t)(key_fold(kt, (uint64_t)e) >> 40);
     return it.bound[l] * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
   }
 
-  // Weights into LDS, from the initial draw or from a packed state.
-  __device__ void put_weights(const float* st) const {
+  // Weights (and the output layer's moments) into LDS, from the initial draw or from a packed state.
+  __device__ __forceinline__ void put_weights(const float* st) const {
     const int d = y.d, h = y.h, c = y.c;
     float* w1 = f(y.o_w1);
     float* w2 = f(y.o_w2);
     for (int ci = threadIdx.x; ci < y.P; ci += blockDim.x) {
-      if (ci < y.cb[0]) {
-        w1[(ci % h) * y.ldw + ci / h] = st ? st[ci] : init_value(0, ci, false);
-      } else if (ci < y.cw[1]) {
-        w1[(ci - y.cb[0]) * y.ldw + d] = st ? st[ci] : init_value(0, ci - y.cb[0], true);
-      } else if (ci < y.cb[1]) {
-        const int e = ci - y.cw[1];
-        w2[(e / c) * 4 + e % c] = st ? st[ci] : init_value(1, e, false);
+      if (ci < y.cw[1]) {
+        const bool isb = ci >= y.cb[0];
+        const int o = isb ? (ci - y.cb[0]) * y.ldw + d : (ci % h) * y.ldw + ci / h;
+        w1[o] = st ? st[ci] : init_value(0, isb ? ci - y.cb[0] : ci, isb);
+        if (st) {
+          m1g()[o] = st[y.P + ci];
+          v1g()[o] = st[2 * y.P + ci];
+        }
       } else {
-        w2[y.HP * 4 + (ci - y.cb[1])] = st ? st[ci] : init_value(1, ci - y.cb[1], true);
+        const bool isb = ci >= y.cb[1];
+        const int e = isb ? ci - y.cb[1] : ci - y.cw[1];
+        const int o = isb ? y.HP * 4 + e : (e / c) * 4 + e % c;
+        w2[o] = st ? st[ci] : init_value(1, e, isb);
+        if (st) {
+          f(y.o_m2)[o] = st[y.P + ci];
+          f(y.o_v2)[o] = st[2 * y.P + ci];
+        }
       }
     }
   }
 
   // ---- input staging, one chunk ahead ---------------------------------------
   // (1) row ids of a chunk: the load is issued here, the value parked in LDS later
-  __device__ int fetch_row_id(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute) const {
+  __device__ __forceinline__ int fetch_row_id(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute) const {
     const int p = threadIdx.x;
-    if (p >= y.RC || p >= rows) return -1;
+    if (p >= SM_RC || p >= rows) return -1;
     if (permute && y.epoch_cap) return ((const int32_t*)(lds + y.o_epoch))[lo + p];
     return list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p];
   }
   // Row ids of a whole epoch, in minibatch order, into the LDS table.
-  __device__ void build_epoch_table(const int32_t* list, uint64_t key, int n_list) const {
+  __device__ __forceinline__ void build_epoch_table(const int32_t* list, uint64_t key, int n_list) const {
     int32_t* tab = (int32_t*)(lds + y.o_epoch);
     for (int p = threadIdx.x; p < n_list; p += blockDim.x) tab[p] = list[perm_index(key, (uint32_t)n_list, (uint32_t)p)];
   }
-  __device__ void park_row_id(int par, int row) const {
-    if ((int)threadIdx.x < y.RC) rowlist(par)[threadIdx.x] = row;
+  __device__ __forceinline__ void park_row_id(int par, int row) const {
+    if ((int)threadIdx.x < SM_RC) rowlist(par)[threadIdx.x] = row;
   }
   // (2) the chunk's input values (and label) into registers
-  __device__ void fetch_inputs(int par, float (&xr)[NX], float& yv) const {
+  __device__ __forceinline__ void fetch_inputs(int par, float (&xr)[NX], float& yv) const {
     const int32_t* rl = rowlist(par);
     const float* X = (const float*)P.X;
     const int k = threadIdx.x % K0, r0 = threadIdx.x / K0, d = y.d;
 #pragma unroll
     for (int i = 0; i < NX; i++) {
-      const int r = r0 + i * RSTEP;
+      const int row = rl[r0 + i * RSTEP];
       xr[i] = 0.f;
-      if (r < y.RC) {
-        const int row = rl[r];
-        if (row >= 0) xr[i] = k < d ? X[row * d + k] : (k == d ? 1.f : 0.f);  // n*d < 2^31 (checked by the host)
-      }
+      if (row >= 0) xr[i] = k < d ? X[row * d + k] : (k == d ? 1.f : 0.f);  // n*d < 2^31 (checked by the host)
     }
     yv = 0.f;
-    if ((int)threadIdx.x < y.RC) {
+    if ((int)threadIdx.x < SM_RC) {
       const int row = rl[threadIdx.x];
       if (row >= 0) yv = P.n_classes >= 2 ? __int_as_float(((const int32_t*)P.y)[row]) : ((const float*)P.y)[row];
     }
   }
-  // (3) registers -> the LDS tiles
-  __device__ void commit_inputs(const float (&xr)[NX], float yv) const {
-    float* xs = f(y.o_xs);
-    float* xt = f(y.o_xt);
+  // (3) registers -> the LDS tiles (the input-major tile and the labels of parity par)
+  __device__ __forceinline__ void commit_inputs(int par, const float (&xr)[NX], float yv) const {
+    float* s = f(y.o_xs);
+    float* t = xt(par);
     const int k = threadIdx.x % K0, r0 = threadIdx.x / K0;
 #pragma unroll
     for (int i = 0; i < NX; i++) {
       const int r = r0 + i * RSTEP;
-      if (r < y.RC) {
-        xs[r * y.ldw + k] = xr[i];
-        xt[k * y.lda + r] = xr[i];
-      }
+      s[r * y.ldw + k] = xr[i];
+      t[k * y.lda + r] = xr[i];
     }
-    if ((int)threadIdx.x < y.RC) f(y.o_ys)[threadIdx.x] = yv;
+    if ((int)threadIdx.x < SM_RC) ys(par)[threadIdx.x] = yv;
   }
 
-  // a1t[unit][row] = relu(sum_k xs[row][k] * w1[unit][k])   (bias rides in column d)
-  // Two row tiles at a time, to keep the accumulator footprint small.
-  __device__ void forward_hidden(int nrt) const {
+  // ---- phase 1: hidden layer forward; the wave's share of the outputs -> zp ----
+  __device__ __forceinline__ void forward(int nrt, f32x4 (&acc)[4][4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int nut = y.HP / 16, ldw = y.ldw, lda = y.lda;
-    const float* xs = f(y.o_xs);
+    const int nut = y.HP / 16, ldw = y.ldw;
+    const float* s = f(y.o_xs);
     const float* w1 = f(y.o_w1);
-    float* a1 = f(y.o_a1);
-    for (int r0 = 0; r0 < nrt; r0 += 2) {
-      f32x4 acc[4][2];
+    const bool c2 = y.c >= 2, c4 = y.c >= 3;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) acc[i][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KT; kk++) {
+      f32x4 a[4], b[4];
+#pragma unroll
+      for (int r = 0; r < 4; r++)
+        if (r < nrt) a[r] = *(const f32x4*)(s + (r * 16 + li) * ldw + kk * 16 + 4 * q);
 #pragma unroll
       for (int i = 0; i < 4; i++)
+        if (w + 4 * i < nut) b[i] = *(const f32x4*)(w1 + ((w + 4 * i) * 16 + li) * ldw + kk * 16 + 4 * q);
 #pragma unroll
-        for (int r = 0; r < 2; r++) acc[i][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < 4; i++)
+        if (w + 4 * i < nut) {
 #pragma unroll
-      for (int kk = 0; kk < KT; kk++) {
-        f32x4 a[2], b[4];
-#pragma unroll
-        for (int r = 0; r < 2; r++) a[r] = *(const f32x4*)(xs + ((r0 + r) * 16 + li) * ldw + kk * 16 + 4 * q);
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-          if (w + 4 * i < nut) b[i] = *(const f32x4*)(w1 + ((w + 4 * i) * 16 + li) * ldw + kk * 16 + 4 * q);
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-          if (w + 4 * i < nut) {
-#pragma unroll
-            for (int r = 0; r < 2; r++) {
+          for (int r = 0; r < 4; r++)
+            if (r < nrt) {
 #pragma unroll
               for (int e = 0; e < 4; e++)
                 acc[i][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e], b[i][e], acc[i][r], 0, 0, 0);
             }
-          }
-      }
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-        if (w + 4 * i < nut) {
-#pragma unroll
-          for (int r = 0; r < 2; r++) {
-            f32x4 v = acc[i][r];
-#pragma unroll
-            for (int e = 0; e < 4; e++) v[e] = fmaxf(v[e], 0.f);
-            *(f32x4*)(a1 + ((w + 4 * i) * 16 + li) * lda + (r0 + r) * 16 + 4 * q) = v;
-          }
         }
     }
-    __syncthreads();
-  }
-
-  // Output layer: partial dot products of thread (row r, group g) over the units
-  // g, g+G, ...; the caller synchronises before finish_out.
-  __device__ void forward_out_partial() const {
-    const int RC = y.RC, G = SM_THREADS / RC, lda = y.lda;
-    const int r = threadIdx.x % RC, g = threadIdx.x / RC;
-    const float* a1 = f(y.o_a1) + r;
-    const float* w2 = f(y.o_w2);
-    const bool c2 = y.c >= 2, c4 = y.c >= 3;
-    f32x4 p = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int u = g; u < y.HP; u += G) {
-      const float av = a1[u * lda];
-      const f32x4 wv = *(const f32x4*)(w2 + u * 4);
-      p[0] += av * wv[0];
-      if (c2) p[1] += av * wv[1];
-      if (c4) {
-        p[2] += av * wv[2];
-        p[3] += av * wv[3];
-      }
-    }
-    *(f32x4*)(f(y.o_red) + threadIdx.x * 4) = p;
-  }
-
-  // Loss and output delta (TRAIN) or validation statistics of the chunk's rows.
-  template <bool TRAIN>
-  __device__ void finish_out(int rows, float inv_mb, double& lsum, double& hits) const {
-    const int RC = y.RC, G = SM_THREADS / RC, c = y.c;
-    const int r = threadIdx.x;
-    if (r < RC) {
-      const float* redf = f(y.o_red);
-      const f32x4 b2 = *(const f32x4*)(f(y.o_w2) + y.HP * 4);
-      float z[4] = {b2[0], b2[1], b2[2], b2[3]};
-#pragma unroll 4
-      for (int gg = 0; gg < G; gg++) {
-        const f32x4 pv = *(const f32x4*)(redf + (gg * RC + r) * 4);
+    // ReLU, and the output layer restricted to this wave's units: lane (unit li, rows 4q..4q+3)
+    f32x4 w2r[4];
 #pragma unroll
-        for (int cc = 0; cc < 4; cc++) z[cc] += pv[cc];
-      }
-      const float yv = f(y.o_ys)[r];
-      float dl[4] = {0.f, 0.f, 0.f, 0.f};
-      if (r < rows) {
-        if (P.n_classes >= 2) {
-          const int yr = __float_as_int(yv);
-          float mx = z[0], zy = z[0];
-          int best = 0;
+    for (int i = 0; i < 4; i++)
+      w2r[i] = w + 4 * i < nut ? *(const f32x4*)(f(y.o_w2) + ((w + 4 * i) * 16 + li) * 4) : f32x4{0.f, 0.f, 0.f, 0.f};
+    float* zp = f(y.o_zp) + w * SM_RC * 4;
 #pragma unroll
-          for (int cc = 1; cc < 4; cc++)
-            if (cc < c) {
-              if (z[cc] > mx) {
-                mx = z[cc];
-                best = cc;
+    for (int r = 0; r < 4; r++)
+      if (r < nrt) {
+        f32x4 pz[4];  // [row 4q+e][output]
+#pragma unroll
+        for (int e = 0; e < 4; e++) pz[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+          if (w + 4 * i < nut) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const float av = fmaxf(acc[i][r][e], 0.f);
+              acc[i][r][e] = av;
+              pz[e][0] += av * w2r[i][0];
+              if (c2) pz[e][1] += av * w2r[i][1];
+              if (c4) {
+                pz[e][2] += av * w2r[i][2];
+                pz[e][3] += av * w2r[i][3];
               }
-              zy = cc == yr ? z[cc] : zy;
             }
-          float se = 0.f;
-#pragma unroll
-          for (int cc = 0; cc < 4; cc++)
-            if (cc < c) se += expf(z[cc] - mx);
-          const float lse = mx + logf(se);
-          lsum += (double)(lse - zy);
-          hits += best == yr;
-          if (TRAIN) {
-#pragma unroll
-            for (int cc = 0; cc < 4; cc++)
-              if (cc < c) dl[cc] = (expf(z[cc] - lse) - (cc == yr ? 1.f : 0.f)) * inv_mb;
           }
-        } else {
-          const float e0 = z[0] - yv;
-          lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
-          if (TRAIN) dl[0] = e0 * inv_mb;
-        }
-      }
-      if (TRAIN) *(f32x4*)(f(y.o_d2) + r * 4) = f32x4{dl[0], dl[1], dl[2], dl[3]};
-    }
-  }
-
-  // Output-layer gradient (accumulated in g2 over the chunks of the step) and
-  // the hidden delta written over the activations.  Thread u owns hidden unit u;
-  // thread HP owns the output bias.
-  __device__ void backward_out(int nrows4, f32x4& g2) const {
-    const int u = threadIdx.x, lda = y.lda;
-    const float* d2 = f(y.o_d2);
-    const bool c2 = y.c >= 2, c4 = y.c >= 3;
-    if (u < y.HP) {
-      float* a1 = f(y.o_a1) + u * lda;
-      const f32x4 wv = *(const f32x4*)(f(y.o_w2) + u * 4);
-#pragma unroll 2
-      for (int r4 = 0; r4 < nrows4; r4++) {
-        const f32x4 av = *(const f32x4*)(a1 + 4 * r4);
-        f32x4 out;
 #pragma unroll
         for (int e = 0; e < 4; e++) {
-          const f32x4 dv = *(const f32x4*)(d2 + (4 * r4 + e) * 4);
-          float s = dv[0] * wv[0];
-          g2[0] += av[e] * dv[0];
-          if (c2) {
-            g2[1] += av[e] * dv[1];
-            s += dv[1] * wv[1];
-          }
+          pz[e][0] = row16_sum(pz[e][0]);
+          if (c2) pz[e][1] = row16_sum(pz[e][1]);
           if (c4) {
-            g2[2] += av[e] * dv[2];
-            g2[3] += av[e] * dv[3];
-            s += dv[2] * wv[2] + dv[3] * wv[3];
+            pz[e][2] = row16_sum(pz[e][2]);
+            pz[e][3] = row16_sum(pz[e][3]);
           }
-          out[e] = av[e] > 0.f ? s : 0.f;
         }
-        *(f32x4*)(a1 + 4 * r4) = out;
-      }
-    } else if (u == y.HP) {
-      for (int r = 0; r < 4 * nrows4; r++) {
-        const f32x4 dv = *(const f32x4*)(d2 + r * 4);
+        if (li == 0) {
 #pragma unroll
-        for (int cc = 0; cc < 4; cc++) g2[cc] += dv[cc];
+          for (int e = 0; e < 4; e++) *(f32x4*)(zp + (r * 16 + 4 * q + e) * 4) = pz[e];
+        }
       }
-    }
-    __syncthreads();
   }
 
-  // accg[unit tile][k tile] += sum_rows xt[k][row] * a1t[unit][row]
-  __device__ void wgrad_hidden(int nrt, f32x4 (&accg)[4][KT]) const {
+  // ---- phase 2a: outputs, loss and output delta of all 64 rows (lane = row), per wave ----
+  template <bool TRAIN>
+  __device__ __forceinline__ void outputs(int par, int rows, float inv_mb, double& lsum, double& hits, f32x4& gb2) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = y.c;
+    const float* zp = f(y.o_zp);
+    const f32x4 b2 = *(const f32x4*)(f(y.o_w2) + y.HP * 4);
+    float z0 = b2[0], z1 = b2[1], z2 = b2[2], z3 = b2[3];
+#pragma unroll
+    for (int ww = 0; ww < 4; ww++) {
+      const f32x4 pv = *(const f32x4*)(zp + (ww * SM_RC + lane) * 4);
+      z0 += pv[0];
+      z1 += pv[1];
+      z2 += pv[2];
+      z3 += pv[3];
+    }
+    const float z[4] = {z0, z1, z2, z3};
+    const float yv = ys(par)[lane];
+    f32x4 dl = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (lane < rows) {
+      double l = 0.0;
+      int hit = 0;
+      if (P.n_classes >= 2) {
+        const int yr = __float_as_int(yv);
+        float mx = z[0], zy = z[0];
+        int best = 0;
+#pragma unroll
+        for (int cc = 1; cc < 4; cc++)
+          if (cc < c) {
+            if (z[cc] > mx) {
+              mx = z[cc];
+              best = cc;
+            }
+            zy = cc == yr ? z[cc] : zy;
+          }
+        float se = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < 4; cc++)
+          if (cc < c) se += expf(z[cc] - mx);
+        const float lse = mx + logf(se);
+        l = (double)(lse - zy);
+        hit = best == yr;
+        if (TRAIN) {
+#pragma unroll
+          for (int cc = 0; cc < 4; cc++)
+            if (cc < c) dl[cc] = (expf(z[cc] - lse) - (cc == yr ? 1.f : 0.f)) * inv_mb;
+        }
+      } else {
+        const float e0 = z[0] - yv;
+        l = TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+        if (TRAIN) dl[0] = e0 * inv_mb;
+      }
+      if (w == 0) {  // every wave computes the same values; one of them keeps the statistics
+        lsum += l;
+        hits += hit;
+      }
+    }
+    if (TRAIN) {
+      *(f32x4*)(f(y.o_d2) + (w * SM_RC + lane) * 4) = dl;
+      if (w == 0) {
+#pragma unroll
+        for (int cc = 0; cc < 4; cc++) gb2[cc] += dl[cc];
+      }
+      // the wave reads back what its other lanes wrote: LDS executes a wave's accesses in order
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+  }
+
+  // ---- phase 2b: hidden deltas in the accumulators, output-layer gradient, hidden weight gradient ----
+  __device__ __forceinline__ void backward(int par, int nrt, f32x4 (&acc)[4][4], f32x4 (&accg)[4][KT], f32x4 (&g2p)[4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, lda = y.lda;
-    const float* xt = f(y.o_xt);
-    const float* a1 = f(y.o_a1);
-    for (int rt = 0; rt < nrt; rt++) {
-      f32x4 a[KT], b[4];
+    const float* t = xt(par);
+    const float* d2 = f(y.o_d2) + w * SM_RC * 4;
+    const bool c2 = y.c >= 2, c4 = y.c >= 3;
+    f32x4 w2r[4];
 #pragma unroll
-      for (int m = 0; m < KT; m++) a[m] = *(const f32x4*)(xt + (m * 16 + li) * lda + rt * 16 + 4 * q);
+    for (int i = 0; i < 4; i++)
+      w2r[i] = w + 4 * i < nut ? *(const f32x4*)(f(y.o_w2) + ((w + 4 * i) * 16 + li) * 4) : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < 4; i++)
-        if (w + 4 * i < nut) b[i] = *(const f32x4*)(a1 + ((w + 4 * i) * 16 + li) * lda + rt * 16 + 4 * q);
+    for (int r = 0; r < 4; r++)
+      if (r < nrt) {
+        f32x4 dv[4], a[KT];
 #pragma unroll
-      for (int i = 0; i < 4; i++)
-        if (w + 4 * i < nut) {
+        for (int e = 0; e < 4; e++) dv[e] = *(const f32x4*)(d2 + (r * 16 + 4 * q + e) * 4);
 #pragma unroll
-          for (int m = 0; m < KT; m++) {
+        for (int m = 0; m < KT; m++) a[m] = *(const f32x4*)(t + (m * 16 + li) * lda + r * 16 + 4 * q);
 #pragma unroll
-            for (int e = 0; e < 4; e++)
-              accg[i][m] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m][e], b[i][e], accg[i][m], 0, 0, 0);
+        for (int i = 0; i < 4; i++)
+          if (w + 4 * i < nut) {
+            f32x4 dh;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const float av = acc[i][r][e];
+              float s = dv[e][0] * w2r[i][0];
+              g2p[i][0] += av * dv[e][0];
+              if (c2) {
+                s += dv[e][1] * w2r[i][1];
+                g2p[i][1] += av * dv[e][1];
+              }
+              if (c4) {
+                s += dv[e][2] * w2r[i][2] + dv[e][3] * w2r[i][3];
+                g2p[i][2] += av * dv[e][2];
+                g2p[i][3] += av * dv[e][3];
+              }
+              dh[e] = av > 0.f ? s : 0.f;
+            }
+#pragma unroll
+            for (int m = 0; m < KT; m++) {
+#pragma unroll
+              for (int e = 0; e < 4; e++)
+                accg[i][m] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m][e], dh[e], accg[i][m], 0, 0, 0);
+            }
           }
-        }
-    }
-    __syncthreads();
+      }
   }
 
-  // Optimizer step on both layers: gradients and moments in registers, weights in LDS.
-  __device__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&m1r)[4][KT], f32x4 (&v1r)[4][KT],
-                         const f32x4& g2, f32x4& m2r, f32x4& v2r, float* rec) const {
+  // ---- optimizer step: gradients (and hidden moments) in registers, weights in LDS ----
+  __device__ __forceinline__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&g2p)[4], f32x4 gb2, float* rec) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h, c = y.c;
     float* w1 = f(y.o_w1);
+    float* m1 = m1g();
+    float* v1 = v1g();
+    // all moment loads of the wave first, so that their latency overlaps
+    f32x4 m1r[4][KT], v1r[4][KT];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int m = 0; m < KT; m++) {
+        const int j = (w + 4 * i) * 16 + li, k0 = m * 16 + 4 * q;
+        m1r[i][m] = v1r[i][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (w + 4 * i < nut && j < h && k0 <= d) {
+          m1r[i][m] = *(const f32x4*)(m1 + j * ldw + k0);
+          if (oc.adam) v1r[i][m] = *(const f32x4*)(v1 + j * ldw + k0);
+        }
+      }
 #pragma unroll
     for (int i = 0; i < 4; i++)
       if (w + 4 * i < nut) {
@@ -418,35 +451,65 @@ struct Small {
               }
             }
             *(f32x4*)(w1 + o) = wv;
+            *(f32x4*)(m1 + o) = m1r[i][m];
+            if (oc.adam) *(f32x4*)(v1 + o) = v1r[i][m];
           }
         }
       }
-    const int u = threadIdx.x;
-    if (u < h || u == y.HP) {
-      const bool isb = u == y.HP;
-      float* w2 = f(y.o_w2) + u * 4;
-      f32x4 wv = *(const f32x4*)w2;
+    // output layer: finish the sums over the rows held by the four lane groups, lane group 0 updates
 #pragma unroll
-      for (int cc = 0; cc < 4; cc++)
-        if (cc < c) {
-          float wr = wv[cc], mr = m2r[cc], vr = v2r[cc];
-          const float gg = isb ? g2[cc] : g2[cc] + oc.am * wr;
-          opt_update(oc, gg, wr, mr, vr);
-          if (rec) {
-            const int ci = isb ? y.cb[1] + cc : y.cw[1] + u * c + cc;
-            rec[1 + ci] = gg;
-            rec[1 + y.P + ci] = wr;
-          }
-          wv[cc] = wr;
-          m2r[cc] = mr;
-          v2r[cc] = vr;
-        }
-      *(f32x4*)w2 = wv;
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int cc = 0; cc < 4; cc++) {
+        float v = g2p[i][cc];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        g2p[i][cc] = v;
+      }
+    if (w == 0) {
+#pragma unroll
+      for (int cc = 0; cc < 4; cc++) {
+        float v = gb2[cc];
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s);
+        gb2[cc] = v;
+      }
     }
-    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 5; i++) {
+      // i < 4: unit (w+4i)*16+li by lane group 0; i == 4: the bias row by lane 0 of wave 0
+      const bool isb = i == 4;
+      const int u = isb ? y.HP : (w + 4 * (i & 3)) * 16 + li;
+      const bool mine = isb ? (w == 0 && lane == 0) : (q == 0 && u < h);
+      if (mine) {
+        const f32x4 g = isb ? gb2 : g2p[i & 3];
+        float* w2 = f(y.o_w2) + u * 4;
+        float* m2 = f(y.o_m2) + u * 4;
+        float* v2 = f(y.o_v2) + u * 4;
+        f32x4 wv = *(const f32x4*)w2, mv = *(const f32x4*)m2, vv = *(const f32x4*)v2;
+#pragma unroll
+        for (int cc = 0; cc < 4; cc++)
+          if (cc < c) {
+            float wr = wv[cc], mr = mv[cc], vr = vv[cc];
+            const float gg = isb ? g[cc] : g[cc] + oc.am * wr;
+            opt_update(oc, gg, wr, mr, vr);
+            if (rec) {
+              const int ci = isb ? y.cb[1] + cc : y.cw[1] + u * c + cc;
+              rec[1 + ci] = gg;
+              rec[1 + y.P + ci] = wr;
+            }
+            wv[cc] = wr;
+            mv[cc] = mr;
+            vv[cc] = vr;
+          }
+        *(f32x4*)w2 = wv;
+        *(f32x4*)m2 = mv;
+        *(f32x4*)v2 = vv;
+      }
+    }
   }
 
-  __device__ double penalty_sum() const {
+  __device__ __forceinline__ double penalty_sum() const {
     double s = 0.0;
     const float* w1 = f(y.o_w1);
     const float* w2 = f(y.o_w2);
@@ -470,55 +533,33 @@ struct Small {
     const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f_);
     const bool traced = P.trace_item == it.b * P.n_folds + f_;
-    const int RC = y.RC;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
 
-    // zero the weights (pads must be zero), then the initial or given parameters
+    // zero the weights and output-layer moments (pads must be zero), then the initial or given parameters
     {
       uint4* z = (uint4*)lds;
       const uint32_t n16 = y.o_xs / 16;
       for (uint32_t i = threadIdx.x; i < n16; i += blockDim.x) z[i] = uint4{0, 0, 0, 0};
     }
     __syncthreads();
-    f32x4 m1r[4][KT], v1r[4][KT], m2r = f32x4{0.f, 0.f, 0.f, 0.f}, v2r = m2r;
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-#pragma unroll
-      for (int m = 0; m < KT; m++) m1r[i][m] = v1r[i][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+      uint4* z = (uint4*)slot;
+      const uint32_t n16 = 2 * y.HP * y.ldw * 4 / 16;
+      for (uint32_t i = threadIdx.x; i < n16; i += blockDim.x) z[i] = uint4{0, 0, 0, 0};
+    }
     double b1t = 1.0, b2t = 1.0;
     int64_t gstep = 0;
     ChunkPos pos = {0, 0, 0};
     const bool resume = traced && P.state_in && steps > 0;
     if (resume) {
-      const float* st = P.state_in;
       gstep = P.step_begin;
       pos.e = (int)(gstep / steps);
       pos.st = (int)(gstep % steps);
-      b1t = pow((double)it.beta1, (double)gstep);
-      b2t = pow((double)it.beta2, (double)gstep);
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int m = 0; m < KT; m++)
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int ci = ci_hidden((w + 4 * i) * 16 + li, m * 16 + 4 * q + e);
-            if (ci >= 0) {
-              m1r[i][m][e] = st[y.P + ci];
-              v1r[i][m][e] = st[2 * y.P + ci];
-            }
-          }
-      const int u = threadIdx.x;
-      if (u < y.h || u == y.HP) {
-#pragma unroll
-        for (int cc = 0; cc < 4; cc++)
-          if (cc < y.c) {
-            const int ci = u == y.HP ? y.cb[1] + cc : y.cw[1] + u * y.c + cc;
-            m2r[cc] = st[y.P + ci];
-            v2r[cc] = st[2 * y.P + ci];
-          }
+      for (int64_t i = 0; i < gstep; i++) {  // beta^gstep by repeated products, as the free run builds it
+        b1t *= (double)it.beta1;
+        b2t *= (double)it.beta2;
       }
     }
+    __syncthreads();  // zeroed moments before a resumed state overwrites them
     put_weights(resume ? P.state_in : nullptr);
     __syncthreads();
 
@@ -536,10 +577,10 @@ struct Small {
 
     // ---- training: the chunks of all steps of all epochs, inputs fetched one chunk ahead ----
     auto chunk_valid = [&](const ChunkPos& p) { return steps > 0 && p.e < it.epochs; };
-    auto chunk_rows = [&](const ChunkPos& p) { return min(RC, min(bs, n_tr - p.st * bs) - p.c0); };
+    auto chunk_rows = [&](const ChunkPos& p) { return min(SM_RC, min(bs, n_tr - p.st * bs) - p.c0); };
     auto chunk_next = [&](ChunkPos p) {
       const int mb = min(bs, n_tr - p.st * bs);
-      p.c0 += RC;
+      p.c0 += SM_RC;
       if (p.c0 >= mb) {
         p.c0 = 0;
         if (++p.st >= steps) {
@@ -554,17 +595,17 @@ struct Small {
     };
     float xr[NX], yv = 0.f;
     int par = 0;
-    if (chunk_valid(pos) && y.epoch_cap) {
-      build_epoch_table(tr, key_epoch(km, pos.e), n_tr);
-      __syncthreads();
-    }
     if (chunk_valid(pos)) {
+      if (y.epoch_cap) {
+        build_epoch_table(tr, key_epoch(km, pos.e), n_tr);
+        __syncthreads();
+      }
       park_row_id(0, chunk_row_id(pos));
       __syncthreads();
       fetch_inputs(0, xr, yv);
     }
-    f32x4 accg[4][KT];
-    f32x4 g2 = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[4][4], accg[4][KT], g2p[4];
+    f32x4 gb2 = f32x4{0.f, 0.f, 0.f, 0.f};
     double lsum = 0.0, hits = 0.0, pen = 0.0;
     float* rec = nullptr;
     while (chunk_valid(pos)) {
@@ -580,15 +621,20 @@ struct Small {
         rec = nullptr;
         if (traced && gstep >= P.step_begin && gstep < P.step_end)
           rec = P.trace_out + (gstep - P.step_begin) * (1 + 2 * (int64_t)y.P);
-        if (rec) pen = penalty_sum();
+        if (rec) {
+          __syncthreads();  // the previous step's update, by every wave
+          pen = penalty_sum();
+        }
         lsum = 0.0;
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 4; i++) {
+          g2p[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int m = 0; m < KT; m++) accg[i][m] = f32x4{0.f, 0.f, 0.f, 0.f};
-        g2 = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        gb2 = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-      commit_inputs(xr, yv);
+      commit_inputs(par, xr, yv);
       const ChunkPos nxt = chunk_next(pos);
       const bool more = chunk_valid(nxt);
       if (more && nxt.e != pos.e && y.epoch_cap) {
@@ -597,19 +643,17 @@ struct Small {
         __syncthreads();
       }
       int nrow = -1;
-      if (more) nrow = chunk_row_id(nxt);  // load in flight across the hidden layer
-      __syncthreads();
-      forward_hidden(nrt);
+      if (more) nrow = chunk_row_id(nxt);  // load in flight across the forward phase
+      __syncthreads();                     // inputs of this chunk (and last step's weights) visible
+      forward(nrt, acc);
       if (more) park_row_id(par ^ 1, nrow);
-      forward_out_partial();
-      __syncthreads();
-      if (more) fetch_inputs(par ^ 1, xr, yv);  // in flight across the backward phases
-      finish_out<true>(rows, 1.f / (float)mb, lsum, hits);
-      __syncthreads();
-      backward_out(4 * nrt, g2);
-      wgrad_hidden(nrt, accg);
+      __syncthreads();  // all four shares of the outputs, and the next chunk's row ids, visible
+      if (more) fetch_inputs(par ^ 1, xr, yv);  // in flight across the backward phase
+      outputs<true>(par, rows, 1.f / (float)mb, lsum, hits, gb2);
+      backward(par, nrt, acc, accg, g2p);
       if (nxt.c0 == 0) {  // that was the last chunk of the step
-        update(oc, accg, m1r, v1r, g2, m2r, v2r, rec);
+        __syncthreads();  // every wave is past its reads of the output bias
+        update(oc, accg, g2p, gb2, rec);
         if (rec) {
           const double data = block_sum(lsum, red) / (double)mb;
           if (threadIdx.x == 0) rec[0] = (float)(data + 0.5 * (double)it.alpha * pen / (double)mb);
@@ -619,21 +663,21 @@ struct Small {
       pos = nxt;
       par ^= 1;
     }
+    __syncthreads();
 
     // ---- validation score on the held rows ----
     lsum = 0.0;
     hits = 0.0;
-    for (int off = 0; off < n_va; off += RC) {
-      const int rows = min(RC, n_va - off);
+    for (int off = 0; off < n_va; off += SM_RC) {
+      const int rows = min(SM_RC, n_va - off);
       park_row_id(0, fetch_row_id(va, 0, n_va, off, rows, false));
       __syncthreads();
       fetch_inputs(0, xr, yv);
-      commit_inputs(xr, yv);
+      commit_inputs(0, xr, yv);
       __syncthreads();
-      forward_hidden((rows + 15) / 16);
-      forward_out_partial();
+      forward((rows + 15) / 16, acc);
       __syncthreads();
-      finish_out<false>(rows, 0.f, lsum, hits);
+      outputs<false>(0, rows, 0.f, lsum, hits, gb2);
       __syncthreads();
     }
     lsum = block_sum(lsum, red);
@@ -658,7 +702,7 @@ __global__ __launch_bounds__(SM_THREADS, 2) void k_train_small(const TrainParams
     const int item = __builtin_amdgcn_readfirstlane(s_item);
     if (item >= P.n_items) break;
     const SItem* __restrict__ si = (const SItem*)P.items + item;
-    Small<KT> T{P, si->d, si->y, smem, red};
+    Small<KT> T{P, si->d, si->y, smem, P.slots + (uint64_t)blockIdx.x * P.slot_bytes, red};
     T.run();
   }
 }

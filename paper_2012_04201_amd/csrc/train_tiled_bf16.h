@@ -172,11 +172,11 @@ struct Tiled {
   __device__ float* fp(uint64_t off) const { return (float*)(slot + off); }
   __device__ __bf16* bp(uint64_t off) const { return (__bf16*)(slot + off); }
   __device__ char* buf(int level) const { return lds + y.lds_buf[level & 1]; }
-  __device__ int stride(int level) const { return y.S[level & 1]; }
+  __device__ __forceinline__ int stride(int level) const { return y.S[level & 1]; }
   __device__ int32_t* rowlist() const { return (int32_t*)(lds + y.lds_rows); }
 
   // ---- parameters -------------------------------------------------------
-  __device__ void store_param(int l, int k, int j, bool isb, float val, int par) const {
+  __device__ __forceinline__ void store_param(int l, int k, int j, bool isb, float val, int par) const {
     const int ldw = y.UP[l] + TB_PAD;
     if (isb) {
       fp(y.w[l])[(size_t)j * ldw + y.UP[l]] = val;
@@ -188,7 +188,7 @@ struct Tiled {
     }
   }
 
-  __device__ void init_params() const {
+  __device__ __forceinline__ void init_params() const {
     const uint64_t km = key_model(it.seed, it.fold);
     for (int l = 0; l < y.L; l++) {
       const int fi = y.U[l], fo = y.U[l + 1];
@@ -204,7 +204,7 @@ struct Tiled {
     }
   }
 
-  __device__ void load_state(const float* st, int par) const {
+  __device__ __forceinline__ void load_state(const float* st, int par) const {
     for (int l = 0; l < y.L; l++) {
       const int fi = y.U[l], fo = y.U[l + 1], ldw = y.UP[l] + TB_PAD;
       for (int i = threadIdx.x; i < fi * fo + fo; i += blockDim.x) {
@@ -222,7 +222,7 @@ struct Tiled {
   // ---- chunk staging -----------------------------------------------------
   // Row list of the chunk, the gathered input rows into the level-0 buffer,
   // and that buffer's pad columns.
-  __device__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute,
+  __device__ __forceinline__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute,
                              bool want_list) const {
     int32_t* rl = rowlist();
     if (want_list) {
@@ -244,7 +244,7 @@ struct Tiled {
   }
 
   // Pad columns of a level's buffer: column UP is 1 on real rows, the rest 0.
-  __device__ void write_pad(int level) const {
+  __device__ __forceinline__ void write_pad(int level) const {
     const int32_t* rl = rowlist();
     char* b = buf(level);
     const int S = stride(level), up = y.UP[level];
@@ -259,7 +259,7 @@ struct Tiled {
   // D[unit][row] = sum_k A[unit][k] * B[row][k]; A: global bf16 [units][lda],
   // B: LDS rows.  Wave w owns unit tiles w, w+NW, ... and all row blocks.
   template <int KS, bool FULL, typename Epi>
-  __device__ void gemm_units_t(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int nt, int njb_,
+  __device__ __forceinline__ void gemm_units_t(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int nt, int njb_,
                                int K, Epi epi) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const int njb = FULL ? 8 : njb_;  // a full chunk has all eight row blocks: no guards in the inner loops
@@ -313,7 +313,7 @@ struct Tiled {
   }
 
   template <int KS, typename Epi>
-  __device__ void gemm_units(const __bf16* A, int lda, const char* Bl, int ldb, int nt, int njb, int K,
+  __device__ __forceinline__ void gemm_units(const __bf16* A, int lda, const char* Bl, int ldb, int nt, int njb, int K,
                              Epi epi) const {
     if (njb == 8)
       gemm_units_t<KS, true>(A, lda, Bl, ldb, nt, njb, K, epi);
@@ -324,7 +324,7 @@ struct Tiled {
   // Output layer: one tile of (up to 16) output units; wave w owns row block w
   // (and w+NW).  epi(acc, jb): lane holds outputs 4q..4q+3 of row jb*16+li.
   template <typename Epi>
-  __device__ void gemm_out(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int njb, int K,
+  __device__ __forceinline__ void gemm_out(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int njb, int K,
                            Epi epi) const {
     constexpr int JPW = (8 + TB_WAVES - 1) / TB_WAVES;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
@@ -353,7 +353,7 @@ struct Tiled {
   // tile will need before the tile's operand reads and MFMAs; epi(acc, i0, j,
   // slot) consumes them afterwards.
   template <typename Pre, typename Epi>
-  __device__ void gemm_rows(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB, Pre pre,
+  __device__ __forceinline__ void gemm_rows(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB, Pre pre,
                             Epi epi) const {
     if (KB == 4)
       gemm_rows_t<true>(Al, lda, Mt, Bl, ldb, Nt, KB, pre, epi);
@@ -362,7 +362,7 @@ struct Tiled {
   }
 
   template <bool FULL, typename Pre, typename Epi>
-  __device__ void gemm_rows_t(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB_, Pre pre,
+  __device__ __forceinline__ void gemm_rows_t(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB_, Pre pre,
                               Epi epi) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const int KB = FULL ? 4 : KB_;
@@ -406,7 +406,7 @@ struct Tiled {
 
   // ---- phases ---------------------------------------------------------------
   // Hidden layer l: level l -> level l+1 (ReLU), all in LDS.
-  __device__ void forward_hidden(int l, int njb) const {
+  __device__ __forceinline__ void forward_hidden(int l, int njb) const {
     const float* bias = fp(y.bias[l]);
     char* out = buf(l + 1);
     const int So = stride(l + 1);
@@ -426,7 +426,7 @@ struct Tiled {
   // lane's share of the summed data loss.  Otherwise accumulates the validation
   // loss and hit count of the chunk's real rows.
   template <bool TRAIN>
-  __device__ void forward_out(int njb, int rows, float inv_mb, double& lsum, double& hits) const {
+  __device__ __forceinline__ void forward_out(int njb, int rows, float inv_mb, double& lsum, double& hits) const {
     const int l = y.L - 1, c = y.U[y.L];
     const float* bias = fp(y.bias[l]);
     const int32_t* rl = rowlist();
@@ -498,7 +498,7 @@ struct Tiled {
 
   // Delta of level l (1 <= l < L) from the delta of level l+1, masked by and
   // written over the level-l activations.
-  __device__ void backward_data(int l, int njb, int par) const {
+  __device__ __forceinline__ void backward_data(int l, int njb, int par) const {
     char* a = buf(l);
     const int Sa = stride(l);
     auto epi = [&](const f32x4& acc, int u0, int row) {
@@ -523,7 +523,7 @@ struct Tiled {
   // bf16 [out][in] copy, the [in][out] copy of the next step's parity and the
   // compact bias are refreshed.  The state loads are issued before the MFMAs
   // of the tile they belong to.
-  __device__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next, float* rec) const {
+  __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next, float* rec) const {
     float* W = fp(y.w[l]);
     float* Mo = fp(y.m[l]);
     float* Vo = fp(y.v[l]);
@@ -597,7 +597,7 @@ struct Tiled {
     __syncthreads();
   }
 
-  __device__ double penalty_sum() const {
+  __device__ __forceinline__ double penalty_sum() const {
     double s = 0.0;
     for (int l = 0; l < y.L; l++) {
       const float* W = fp(y.w[l]);
@@ -634,8 +634,10 @@ struct Tiled {
       load_state(P.state_in, (int)(gstep & 1));
       e0 = (int)(gstep / steps);
       st0 = (int)(gstep % steps);
-      b1t = pow((double)it.beta1, (double)gstep);
-      b2t = pow((double)it.beta2, (double)gstep);
+      for (int64_t i = 0; i < gstep; i++) {  // beta^gstep by repeated products, as the free run builds it
+        b1t *= (double)it.beta1;
+        b2t *= (double)it.beta2;
+      }
     } else {
       init_params();
     }
