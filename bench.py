@@ -6,8 +6,10 @@ A "step" is one full evaluation call (fold lists, training of every
 synthetic workload already resident in HBM.  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+    python bench.py --copy-probe BYTES     # plain device copy, to calibrate HBM counters
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -18,11 +20,65 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+KERNEL_SOURCES = ["bbo_mlp.hip", "common.h", "train_tiled_bf16.h", "train_small_f32.h"]
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def kernel_source_hash():
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2012_04201_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch from the committed rocprofv3 counter runs; None when
+    there is no record for this workload or the kernel sources changed since."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None
+    rec = {}
+    for line in open(TRAFFIC_FILE):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=", 1)
+            rec[k.strip()] = v.strip()
+    if rec.get(workload + ".source_hash") != kernel_source_hash():
+        return None
+    try:
+        return float(rec[workload + ".bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def algorithmic_bytes(cfg):
+    """HBM bytes one launch must move when the optimizer state does not fit on chip:
+    every step reads and writes the fp32 weights and both moments (24 B per
+    parameter; 16 B for SGD) and reads the minibatch's input rows; validation reads
+    its rows once."""
+    import numpy as np
+    fold = cfg["fold_idx"]
+    K = cfg["n_folds"]
+    d = cfg["X"].shape[1]
+    xb = 2 if cfg["dtype"] else 4
+    c_out = cfg["n_classes"] if cfg["n_classes"] >= 2 else 1
+    total = 0.0
+    for f in range(K):
+        n_va = int((fold == f).sum())
+        n_tr = int((fold >= 0).sum()) - n_va
+        for h in cfg["hparams"]:
+            dims = [d] + list(h["hidden"]) + [c_out]
+            P = sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(len(dims) - 1))
+            bs = h["batch_size"] if 0 < h["batch_size"] <= n_tr else n_tr
+            steps = -(-n_tr // bs) if n_tr else 0
+            per_param = 24 if h.get("solver", "adam") == "adam" else 16
+            total += h["epochs"] * (steps * per_param * P + n_tr * d * xb) + n_va * d * xb
+    return total
 
 
 def cpu_baseline(cfg, seconds_hint=20.0):
     """The oracle as it stands, timed on this machine's cores on a bounded sample."""
-    import numpy as np
     from oracle import mlp_cv_oracle as O
     from paper_2012_04201_amd import inputs
     cores = len(os.sched_getaffinity(0))
@@ -43,29 +99,12 @@ def cpu_baseline(cfg, seconds_hint=20.0):
             "sample": "first %d suggestions x %d folds x %d epoch(s) of the same workload, %.1f s" % (n_sugg, K, epochs, dt)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
-    ap.add_argument("--suggestions", type=int, default=0, help="debug: evaluate only the first B suggestions")
-    ap.add_argument("--epochs", type=int, default=0, help="debug: override the epoch count")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this evaluator runs on one GPU (items are independent; a multi-GPU run would only "
-                 "split the work list); use --gpus 1")
-
+def run_workload(idx, steps, warmup, suggestions=0, epochs=0):
     import torch
     from paper_2012_04201_amd import binding, inputs
-
-    idx = int(args.workload[3])
-    cfg = inputs.make_config(idx, B=args.suggestions or None, epochs=args.epochs or None)
-    reduced = bool(args.suggestions or args.epochs)
+    cfg = inputs.make_config(idx, B=suggestions or None, epochs=epochs or None)
     flops, model_epochs = inputs.workload_flops(cfg)
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     X, y, ft = binding.to_device(cfg, dev)
     K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
     hps = cfg["hparams"]
@@ -76,11 +115,13 @@ def main():
     def step():
         return binding.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, workspace=ws, stream=stream, hp_arr=hp_arr)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    # events are recorded on the stream the kernels are launched on
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # Events are recorded on the stream the kernels are launched on.  One call launches the fold-list
+    # kernel, the training kernel and the fold-mean kernel; the first and last take tens of microseconds
+    # (see profiles/), so the bracket is the training kernel's duration to better than 0.1 %.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
     for a, b in ev:
         a.record(stream)
@@ -88,30 +129,80 @@ def main():
         b.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kern_ms = [a.elapsed_time(b) for a, b in ev]
-    avg_kernel_s = sum(kern_ms) / len(kern_ms) / 1e3
-    ms_per_step = wall / args.steps * 1e3
-    n_bad = int(status.sum().item())
-
+    kern_s = sum(a.elapsed_time(b) for a, b in ev) / len(ev) / 1e3
+    per_step = wall / steps
     dname = "bf16" if dt else "f32"
-    tflops = flops / (wall / args.steps) / 1e12
-    achieved = flops / avg_kernel_s / 1e12
-    out = {
-        "metric": "MLP models x epochs/sec for batched CV eval",
-        "value": model_epochs / (wall / args.steps),
-        "unit": "model-epochs/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dname, "data": "synthetic",
+    kernel = "k_train_tiled" if dt else ("k_train_small" if idx in (0, 2, 3) else "k_train")
+    tflops = flops / per_step / 1e12
+    abytes = algorithmic_bytes(cfg)
+    traffic = measured_traffic(cfg["name"])
+    mfma = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_TFLOPS[dname], "unit": "TFLOP/s",
+            "frac": flops / kern_s / 1e12 / PEAK_TFLOPS[dname], "traffic": traffic, "kernel": kernel,
+            "kernel_ms": kern_s * 1e3}
+    hbm = {"bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "frac": abytes / kern_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic, "kernel": kernel,
+           "kernel_ms": kern_s * 1e3, "algorithmic_bytes": abytes}
+    res = {
+        "value": model_epochs / per_step, "ms_per_step": per_step * 1e3, "dtype": dname,
         "config": {"workload": cfg["name"], "mlps": len(hps) * K, "suggestions": len(hps), "folds": K,
                    "rows": int(len(cfg["y"])), "features": int(X.shape[1]), "classes": c,
-                   "epochs": hps[0]["epochs"], "reduced": reduced},
+                   "epochs": hps[0]["epochs"], "reduced": bool(suggestions or epochs)},
         "tflops": tflops, "pct_mfma_peak": 100.0 * tflops / PEAK_TFLOPS[dname],
-        "nonfinite_suggestions": n_bad,
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dname], "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_TFLOPS[dname], "traffic": None,
-                     "kernel": "k_train", "kernel_ms": avg_kernel_s * 1e3},
+        "nonfinite_suggestions": int(status.sum().item()),
     }
+    return cfg, res, mfma, hbm
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--suggestions", type=int, default=0, help="debug: evaluate only the first B suggestions")
+    ap.add_argument("--epochs", type=int, default=0, help="debug: override the epoch count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the extra cfg3 measurement")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device-to-device copy of BYTES (HBM counter calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this evaluator runs on one GPU (items are independent; a multi-GPU run would only "
+                 "split the work list); use --gpus 1")
+
+    import torch
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        a = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda:0")
+        b = torch.ones(args.copy_probe, dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        for _ in range(3):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "copies": 3}))
+        return
+
+    idx = int(args.workload[3])
+    cfg, res, mfma, hbm = run_workload(idx, args.steps, args.warmup, args.suggestions, args.epochs)
+    # cfg4 cannot keep its optimizer state on chip (0.9 MB of fp32 state per model, 256 models in flight):
+    # the training kernel is bound by streaming that state, so its roofline is HBM; the MFMA view is kept too.
+    # The small fp32 models live in LDS and are bound by MFMA issue and latency.
+    out = {
+        "metric": "MLP models x epochs/sec for batched CV eval",
+        "value": res["value"], "unit": "model-epochs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
+        "tflops": res["tflops"], "pct_mfma_peak": res["pct_mfma_peak"],
+        "nonfinite_suggestions": res["nonfinite_suggestions"],
+        "roofline": hbm if idx == 4 else mfma,
+        "roofline_mfma": mfma,
+    }
+    if idx == 4 and not args.no_secondary and not (args.suggestions or args.epochs):
+        _, r3, m3, _ = run_workload(3, 3, 1)
+        out["secondary"] = {"config": r3["config"], "value": r3["value"], "unit": "model-epochs/s",
+                            "ms_per_step": r3["ms_per_step"], "dtype": r3["dtype"], "tflops": r3["tflops"],
+                            "roofline": m3}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
