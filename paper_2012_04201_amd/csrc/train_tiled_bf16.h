@@ -2,29 +2,36 @@
 // layers (the "scale-up" shape: up to 256 inputs, hidden widths up to 256, up
 // to 16 outputs).
 //
-// One workgroup (8 waves) trains one model.  A minibatch is processed in
-// chunks of 128 rows whose activations live entirely in LDS:
-//   buf[0]: level 0 (gathered inputs), later level 2 and its delta
-//   buf[1]: level 1 and its delta
-//   dbuf  : output-layer delta
-// each row-major [row][unit] with 16 pad columns, the first of which is 1 on
-// real rows (it turns the weight-gradient GEMM into weight + bias gradient).
+// One workgroup (8 waves) trains one model, one model per CU.  A minibatch of
+// up to 256 rows is processed at once; its activations live in ONE row-major
+// LDS buffer buf[row][unit] (16 pad columns per row, the first of which is 1
+// on real rows: it turns the weight-gradient GEMM into weight + bias
+// gradient), which every layer overwrites in place:
 //
-// Forward / data-gradient GEMMs are output-stationary with the weight matrix
-// as the MFMA A operand (16-byte rows straight from global/L2, each wave owns
-// a slice of the output units and so streams only that slice of the weights) and the
-// LDS activations as the B operand; results go back to LDS as 8-byte stores,
-// deltas overwrite the activations they are masked by.  Weight-gradient GEMMs
-// contract over the rows: both operands come from the row-major LDS buffers
-// through the transposing LDS read (ds_read_b64_tr_b16), which hands each
-// lane the four row-consecutive values of its own unit.  The optimizer update
-// runs in the weight-gradient epilogue on the accumulator registers: it reads
-// and writes the fp32 master weights and moments once per step and emits the
-// two bf16 operand copies ([out][in] for forward, [in][out] for backward, the
-// latter double-buffered because the backward GEMM of the same step still
-// needs the old weights).  With more than one chunk per step the partial
-// gradients of the earlier chunks pass through an fp32 scratch in global
-// memory.
+//   forward / data gradient  ("row phases"): wave w owns rows 32w..32w+31.  It
+//     loads its rows of the current level into registers as MFMA B operands,
+//     streams the bf16 weight tiles from global memory as A operands
+//     (D[unit][row] = W[unit][k] . act[row][k]) and writes the next level over
+//     its own rows as 8-byte stores.  ReLU masks are kept as bits in registers,
+//     so a delta can overwrite the activation it is masked by even after that
+//     activation is gone.  No barrier between the layers of a pass.
+//   weight gradient ("unit phases"): contraction over the rows.  The delta
+//     operand comes from the LDS buffer through the transposing LDS read
+//     (ds_read_b64_tr_b16).  The activation operand comes the same way for the
+//     last hidden level; lower levels were overwritten by then, so each wave
+//     spills the transpose of its rows to global memory before it overwrites
+//     them (tile-blocked, read back as 16-byte operand vectors).
+//   The optimizer runs in the weight-gradient epilogue on the accumulator
+//   registers: fp32 master weights and moments are read and written once per
+//   step and the two bf16 operand copies ([out][in] for forward, [in][out] for
+//   backward; the latter double-buffered by step parity, because the backward
+//   pass of the same step still needs the old weights) are refreshed.
+//
+// Every global array is stored in the order its wave-level accesses touch it
+// (tile-blocked), so each load or store instruction of a wave covers 1 KB of
+// contiguous memory: state tiles [out tile][in tile][lane][4], operand tiles
+// [unit tile][k block][unit][32 k].  Batches above 256 rows are processed in
+// chunks whose partial gradients pass through an fp32 scratch.
 #pragma once
 #include <type_traits>
 
@@ -37,24 +44,23 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TB_ROWS = 128;  // rows per chunk
+constexpr int TB_ROWS = 256;  // rows per chunk
 constexpr int TB_PAD = 16;    // pad columns per LDS row
 constexpr int TB_MAXL = 3;    // weight layers
 constexpr int TB_MAXU = 256;  // padded units per level
-constexpr int TB_WAVES = 8;                   // waves per workgroup (2 per SIMD)
+constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns rows 32w..32w+31 in the row phases
 constexpr int TB_THREADS = 64 * TB_WAVES;
-constexpr int TB_TPN = 16 / TB_WAVES > 1 ? 2 : 1;  // out tiles per wave in the rows-contracting GEMM
-constexpr int TB_TPW = (16 + TB_WAVES - 1) / TB_WAVES;  // unit tiles per wave in the unit-split GEMMs
-constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 2048;  // dynamic LDS available to the kernel
+constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 1024;  // dynamic LDS available to the kernel
 
 struct TLay {
   int32_t L;
   int32_t U[TB_MAXL + 1];   // units per level: inputs, hidden..., outputs
   int32_t UP[TB_MAXL + 1];  // padded to 32 (levels < L) or 16 (outputs)
-  int32_t S[2];             // LDS row strides in elements
+  int32_t S;                // LDS row stride in elements
   int32_t cw[TB_MAXL], cb[TB_MAXL], P;
-  uint32_t lds_buf[2], lds_delta, lds_rows, lds_total;
-  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL], io[TB_MAXL][2], bias[TB_MAXL], total;
+  uint32_t lds_buf, lds_delta, lds_rows, lds_tr, lds_total;
+  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL], io[TB_MAXL][2], bias[TB_MAXL],
+      T[TB_MAXL], total;
 };
 
 __host__ __device__ inline bool tiled_eligible(const int32_t* dims, int L) {
@@ -67,11 +73,11 @@ __host__ __device__ inline bool tiled_eligible(const int32_t* dims, int L) {
 
 __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
   y.L = L;
-  y.S[0] = y.S[1] = 0;
+  y.S = 0;
   for (int u = 0; u <= L; u++) {
     y.U[u] = dims[u];
     y.UP[u] = u < L ? rup(dims[u], 32) : 16;
-    if (u < L && y.UP[u] + TB_PAD > y.S[u & 1]) y.S[u & 1] = y.UP[u] + TB_PAD;
+    if (u < L && y.UP[u] + TB_PAD > y.S) y.S = y.UP[u] + TB_PAD;
   }
   int c = 0;
   for (int l = 0; l < L; l++) {
@@ -82,14 +88,14 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
   }
   y.P = c;
   uint32_t lo = 0;
-  y.lds_buf[0] = lo;
-  lo += TB_ROWS * y.S[0] * 2;
-  y.lds_buf[1] = lo;
-  lo += TB_ROWS * y.S[1] * 2;
+  y.lds_buf = lo;
+  lo += TB_ROWS * y.S * 2;
   y.lds_delta = lo;
   lo += TB_ROWS * 16 * 2;
   y.lds_rows = lo;
   lo += TB_ROWS * 4;
+  y.lds_tr = lo;  // a 16 x 16 bf16 patch per wave
+  lo += TB_WAVES * 512;
   y.lds_total = lo;
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
@@ -98,7 +104,7 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
     return o;
   };
   for (int l = 0; l < L; l++) {
-    const uint64_t wn = (uint64_t)y.UP[l + 1] * (y.UP[l] + TB_PAD);
+    const uint64_t wn = (uint64_t)(y.UP[l + 1] / 16) * (y.UP[l] / 16 + 1) * 256;
     y.w[l] = take(wn * 4);
     y.m[l] = take(wn * 4);
     y.v[l] = take(wn * 4);
@@ -110,6 +116,8 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
       y.io[l][1] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
     }
     y.bias[l] = take((uint64_t)y.UP[l + 1] * 4);
+    // transposed spill of level l: needed by the weight gradient of every layer but the last
+    y.T[l] = l <= L - 2 ? take((uint64_t)(y.UP[l] + 16) * TB_ROWS * 2) : 0;
   }
   y.total = off;
 }
@@ -147,7 +155,8 @@ __device__ inline s16x4 lds_read_tr(const char* p) {
 }
 
 // Operand of a rows-contracting MFMA for the 16 units starting at u0 and the
-// 32 rows starting at r0 of a row-major LDS buffer with row stride ld.
+// 32 rows starting at r0 of a row-major LDS buffer with row stride ld: lane
+// (li, q) gets rows r0+8q..r0+8q+7 of unit u0+li.
 __device__ inline bf16x8 lds_operand_tr(const char* base, int ld, int r0, int u0, int li, int q) {
   const char* p = base + ((size_t)(r0 + 8 * q + (li >> 2)) * ld + u0 + 4 * (li & 3)) * 2;
   union {
@@ -169,22 +178,39 @@ struct Tiled {
   char* lds;
   double* red;
 
-  __device__ float* fp(uint64_t off) const { return (float*)(slot + off); }
-  __device__ __bf16* bp(uint64_t off) const { return (__bf16*)(slot + off); }
-  __device__ char* buf(int level) const { return lds + y.lds_buf[level & 1]; }
-  __device__ __forceinline__ int stride(int level) const { return y.S[level & 1]; }
-  __device__ int32_t* rowlist() const { return (int32_t*)(lds + y.lds_rows); }
+  __device__ __forceinline__ float* fp(uint64_t off) const { return (float*)(slot + off); }
+  __device__ __forceinline__ __bf16* bp(uint64_t off) const { return (__bf16*)(slot + off); }
+  __device__ __forceinline__ char* buf() const { return lds + y.lds_buf; }
+  __device__ __forceinline__ char* dbuf() const { return lds + y.lds_delta; }
+  __device__ __forceinline__ int32_t* rowlist() const { return (int32_t*)(lds + y.lds_rows); }
+
+  // ---- blocked indices ------------------------------------------------------
+  // state element (in unit k, out unit j) of layer l; the bias is in unit k = UP[l]
+  __device__ __forceinline__ size_t sidx(int l, int k, int j) const {
+    const int mta = y.UP[l] / 16 + 1;
+    return ((size_t)(j >> 4) * mta + (k >> 4)) * 256 + ((((k & 15) >> 2) << 4) + (j & 15)) * 4 + (k & 3);
+  }
+  // forward operand copy: 16 x 16 tiles [out tile][in tile][out unit][in unit]
+  __device__ __forceinline__ size_t oidx(int l, int j, int k) const {
+    return (((size_t)(j >> 4) * (y.UP[l] / 16) + (k >> 4)) * 16 + (j & 15)) * 16 + (k & 15);
+  }
+  // backward operand copy: 16 x 16 tiles [in tile][out tile][in unit][out unit]
+  __device__ __forceinline__ size_t iidx(int l, int i, int j) const {
+    return (((size_t)(i >> 4) * (y.UP[l + 1] / 16) + (j >> 4)) * 16 + (i & 15)) * 16 + (j & 15);
+  }
+  // Lane's share of a weight operand (unit li of a tile row, 8 contraction units from 8q) inside the 1 KB
+  // that two neighbouring 16 x 16 tiles of an operand copy take.
+  __device__ __forceinline__ static int opnd_lane(int li, int q) { return (q >> 1) * 256 + li * 16 + 8 * (q & 1); }
 
   // ---- parameters -------------------------------------------------------
   __device__ __forceinline__ void store_param(int l, int k, int j, bool isb, float val, int par) const {
-    const int ldw = y.UP[l] + TB_PAD;
     if (isb) {
-      fp(y.w[l])[(size_t)j * ldw + y.UP[l]] = val;
+      fp(y.w[l])[sidx(l, y.UP[l], j)] = val;
       fp(y.bias[l])[j] = val;
     } else {
-      fp(y.w[l])[(size_t)j * ldw + k] = val;
-      bp(y.oi[l])[(size_t)j * y.UP[l] + k] = (__bf16)val;
-      if (l >= 1) bp(y.io[l][par])[(size_t)k * y.UP[l + 1] + j] = (__bf16)val;
+      fp(y.w[l])[sidx(l, k, j)] = val;
+      bp(y.oi[l])[oidx(l, j, k)] = (__bf16)val;
+      if (l >= 1) bp(y.io[l][par])[iidx(l, k, j)] = (__bf16)val;
     }
   }
 
@@ -206,324 +232,296 @@ struct Tiled {
 
   __device__ __forceinline__ void load_state(const float* st, int par) const {
     for (int l = 0; l < y.L; l++) {
-      const int fi = y.U[l], fo = y.U[l + 1], ldw = y.UP[l] + TB_PAD;
+      const int fi = y.U[l], fo = y.U[l + 1];
       for (int i = threadIdx.x; i < fi * fo + fo; i += blockDim.x) {
         const bool isb = i >= fi * fo;
         const int e = isb ? i - fi * fo : i;
         const int k = isb ? y.UP[l] : e / fo, j = isb ? e : e % fo;
         const int ci = (isb ? y.cb[l] : y.cw[l]) + e;
         store_param(l, k, j, isb, st[ci], par);
-        fp(y.m[l])[(size_t)j * ldw + k] = st[y.P + ci];
-        fp(y.v[l])[(size_t)j * ldw + k] = st[2 * y.P + ci];
+        fp(y.m[l])[sidx(l, k, j)] = st[y.P + ci];
+        fp(y.v[l])[sidx(l, k, j)] = st[2 * y.P + ci];
       }
     }
   }
 
-  // ---- chunk staging -----------------------------------------------------
-  // Row list of the chunk, the gathered input rows into the level-0 buffer,
-  // and that buffer's pad columns.
-  __device__ __forceinline__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute,
-                             bool want_list) const {
+  // ---- staging --------------------------------------------------------------
+  // Row list of the chunk and the gathered input rows (with their pad columns) into the buffer.
+  __device__ __forceinline__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows,
+                                             bool permute) const {
     int32_t* rl = rowlist();
-    if (want_list) {
-      for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x)
-        rl[p] = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
-      __syncthreads();
-    }
-    const int d = y.U[0], up0 = y.UP[0], S0 = stride(0), vpr = up0 / 8;
-    char* b0 = buf(0);
+    for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x)
+      rl[p] = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
+    __syncthreads();
+    const int d = y.U[0], up0 = y.UP[0], S = y.S, vpr = up0 / 8 + 2;  // data vectors + two pad vectors per row
+    char* b0 = buf();
     const __bf16* X = (const __bf16*)P.X;
     for (int idx = threadIdx.x; idx < TB_ROWS * vpr; idx += blockDim.x) {
       const int r = idx / vpr, vv = idx - r * vpr;
       const int row = rl[r];
       uint4 val = uint4{0, 0, 0, 0};
-      if (row >= 0 && vv * 8 < d) val = *(const uint4*)(X + (size_t)row * d + vv * 8);
-      *(uint4*)(b0 + ((size_t)r * S0 + vv * 8) * 2) = val;
+      if (row >= 0) {
+        if (vv * 8 < d)
+          val = *(const uint4*)(X + (size_t)row * d + vv * 8);
+        else if (vv * 8 == up0)
+          val.x = 0x3F80u;  // bf16 1.0 in column UP[0]
+      }
+      *(uint4*)(b0 + ((size_t)r * S + vv * 8) * 2) = val;
     }
-    write_pad(0);
+    __syncthreads();
   }
 
-  // Pad columns of a level's buffer: column UP is 1 on real rows, the rest 0.
+  // Transpose of the wave's rows of level l (units 0..UP[l]+15) to global, tile-blocked [unit tile][row block][unit][32 rows].
+  __device__ __forceinline__ void spill_transposed(int l) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    __bf16* T = bp(y.T[l]);
+    const int mta = y.UP[l] / 16 + 1;
+    for (int mt = 0; mt < mta; mt++) {
+      const bf16x8 v = lds_operand_tr(buf(), y.S, 32 * w, mt * 16, li, q);
+      *(bf16x8*)(T + (((size_t)mt * 8 + w) * 16 + li) * 32 + q * 8) = v;
+    }
+  }
+
+  // ---- hidden layers, forward and data gradient: wave w owns units 32w..32w+31 of the level it produces ----
+  // acc[ub][jb] = sum_k A[(2w+ub)*16 + .][k] * level[16jb + .][k] over the row tiles jb < njb; the weights A
+  // (tile-blocked in global) are read once per workgroup, the level comes from the buffer.  The lane ends up
+  // with units (2w+ub)*16+4q..+3 of row 16jb+li.  The results stay in registers until every wave has read the
+  // level, then overwrite it.
+  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int njb,
+                                                 f32x4 (&acc)[2][16]) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    // weight operands of the wave's two unit tiles, fetched two k blocks ahead of their use
+    const __bf16* A0 = A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
+    const __bf16* A1 = A0 + (size_t)kbn * 512;
+    const int k1 = min(1, kbn - 1);
+    bf16x8 a0 = *(const bf16x8*)A0, a1 = *(const bf16x8*)A1;
+    bf16x8 n0 = *(const bf16x8*)(A0 + k1 * 512), n1 = *(const bf16x8*)(A1 + k1 * 512);
+    const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2;
+    const size_t tile_bytes = (size_t)16 * y.S * 2;
+#pragma unroll
+    for (int jb = 0; jb < 16; jb++) {
+      acc[0][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc[1][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    auto sweep = [&](auto full) {
+      constexpr bool FULL = decltype(full)::value;
+#pragma unroll 1
+      for (int kb = 0; kb < kbn; kb++) {
+        const int k2 = min(kb + 2, kbn - 1);
+        const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * 512), m1 = *(const bf16x8*)(A1 + k2 * 512);
+#pragma unroll
+        for (int jb = 0; jb < 16; jb++)
+          if (FULL || jb < njb) {
+            const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes);
+            acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][jb], 0, 0, 0);
+            acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][jb], 0, 0, 0);
+          }
+        a0 = n0;
+        a1 = n1;
+        n0 = m0;
+        n1 = m1;
+        bp += 64;
+      }
+    };
+    if (njb == 16)
+      sweep(std::true_type());
+    else
+      sweep(std::false_type());
+  }
+
+  // Pad columns of a level: column UP is 1 on real rows, the rest 0.
   __device__ __forceinline__ void write_pad(int level) const {
-    const int32_t* rl = rowlist();
-    char* b = buf(level);
-    const int S = stride(level), up = y.UP[level];
-    for (int r = threadIdx.x; r < TB_ROWS; r += blockDim.x) {
-      uint4 one = uint4{rl[r] >= 0 ? 0x3F80u : 0u, 0, 0, 0};  // bf16 1.0 in the low half
-      *(uint4*)(b + ((size_t)r * S + up) * 2) = one;
-      *(uint4*)(b + ((size_t)r * S + up + 8) * 2) = uint4{0, 0, 0, 0};
+    if (threadIdx.x < TB_ROWS) {
+      const int r = threadIdx.x;
+      char* p = buf() + ((size_t)r * y.S + y.UP[level]) * 2;
+      *(uint4*)p = uint4{rowlist()[r] >= 0 ? 0x3F80u : 0u, 0, 0, 0};
+      *(uint4*)(p + 16) = uint4{0, 0, 0, 0};
     }
   }
 
-  // ---- GEMMs --------------------------------------------------------------
-  // D[unit][row] = sum_k A[unit][k] * B[row][k]; A: global bf16 [units][lda],
-  // B: LDS rows.  Wave w owns unit tiles w, w+NW, ... and all row blocks.
-  template <int KS, bool FULL, typename Epi>
-  __device__ __forceinline__ void gemm_units_t(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int nt, int njb_,
-                               int K, Epi epi) const {
+  // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
+  // (bit 4*(16*ub + jb) + r).  Called by all waves.
+  __device__ __forceinline__ void forward_hidden(int l, int njb, uint32_t (&bits)[4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int njb = FULL ? 8 : njb_;  // a full chunk has all eight row blocks: no guards in the inner loops
-    if (w >= nt) return;
-    f32x4 acc[TB_TPW][8];
+    const bool active = 32 * w < y.UP[l + 1];
+    f32x4 acc[2][16];
+    if (active)
+      gemm_unitsplit(bp(y.oi[l]), y.UP[l] / 32, njb, acc);
+    __syncthreads();
+    if (active) {
+      const float* bias = fp(y.bias[l]);
+      char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2;
+      const size_t tile_bytes = (size_t)16 * y.S * 2;
 #pragma unroll
-    for (int i = 0; i < TB_TPW; i++)
+      for (int i = 0; i < 4; i++) bits[i] = 0;
 #pragma unroll
-      for (int j = 0; j < 8; j++) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (KS == 32) {
-      for (int k0 = 0; k0 < K; k0 += 32) {
-        bf16x8 a[TB_TPW], b[8];
+      for (int ub = 0; ub < 2; ub++) {
+        const f32x4 bv = *(const f32x4*)(bias + 32 * w + 16 * ub + 4 * q);
 #pragma unroll
-        for (int i = 0; i < TB_TPW; i++)
-          if (w + TB_WAVES * i < nt)
-            a[i] = *(const bf16x8*)(A + (size_t)((w + TB_WAVES * i) * 16 + li) * lda + k0 + q * 8);
+        for (int jb = 0; jb < 16; jb++)
+          if (jb < njb) {
+            bf16x4 pk;
+            uint32_t nib = 0;
 #pragma unroll
-        for (int j = 0; j < 8; j++)
-          if (j < njb) b[j] = *(const bf16x8*)(Bl + ((size_t)(j * 16 + li) * ldb + k0 + q * 8) * 2);
-#pragma unroll
-        for (int i = 0; i < TB_TPW; i++)
-          if (w + TB_WAVES * i < nt) {
-#pragma unroll
-            for (int j = 0; j < 8; j++)
-              if (j < njb) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            for (int r = 0; r < 4; r++) {
+              pk[r] = (__bf16)fmaxf(acc[ub][jb][r] + bv[r], 0.f);
+              nib |= ((float)pk[r] > 0.f ? 1u : 0u) << r;
+            }
+            *(bf16x4*)(b + jb * tile_bytes + ub * 32) = pk;
+            bits[ub * 2 + (jb >> 3)] |= nib << ((jb & 7) * 4);
           }
       }
-    } else {  // K == 16: one MFMA of depth 16
-      bf16x4 a[TB_TPW], b[8];
-#pragma unroll
-      for (int i = 0; i < TB_TPW; i++)
-        if (w + TB_WAVES * i < nt) a[i] = *(const bf16x4*)(A + (size_t)((w + TB_WAVES * i) * 16 + li) * lda + q * 4);
-#pragma unroll
-      for (int j = 0; j < 8; j++)
-        if (j < njb) b[j] = *(const bf16x4*)(Bl + ((size_t)(j * 16 + li) * ldb + q * 4) * 2);
-#pragma unroll
-      for (int i = 0; i < TB_TPW; i++)
-        if (w + TB_WAVES * i < nt) {
-#pragma unroll
-          for (int j = 0; j < 8; j++)
-            if (j < njb) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
     }
-#pragma unroll
-    for (int i = 0; i < TB_TPW; i++)
-      if (w + TB_WAVES * i < nt) {
-#pragma unroll
-        for (int j = 0; j < 8; j++)
-          if (j < njb) epi(acc[i][j], (w + TB_WAVES * i) * 16 + 4 * q, j * 16 + li);
-      }
-  }
-
-  template <int KS, typename Epi>
-  __device__ __forceinline__ void gemm_units(const __bf16* A, int lda, const char* Bl, int ldb, int nt, int njb, int K,
-                             Epi epi) const {
-    if (njb == 8)
-      gemm_units_t<KS, true>(A, lda, Bl, ldb, nt, njb, K, epi);
-    else
-      gemm_units_t<KS, false>(A, lda, Bl, ldb, nt, njb, K, epi);
-  }
-
-  // Output layer: one tile of (up to 16) output units; wave w owns row block w
-  // (and w+NW).  epi(acc, jb): lane holds outputs 4q..4q+3 of row jb*16+li.
-  template <typename Epi>
-  __device__ __forceinline__ void gemm_out(const __bf16* __restrict__ A, int lda, const char* Bl, int ldb, int njb, int K,
-                           Epi epi) const {
-    constexpr int JPW = (8 + TB_WAVES - 1) / TB_WAVES;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    if (w >= njb) return;
-    f32x4 acc[JPW];
-#pragma unroll
-    for (int j = 0; j < JPW; j++) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < K; k0 += 32) {
-      const bf16x8 a = *(const bf16x8*)(A + (size_t)li * lda + k0 + q * 8);
-#pragma unroll
-      for (int j = 0; j < JPW; j++)
-        if (w + TB_WAVES * j < njb) {
-          const bf16x8 b = *(const bf16x8*)(Bl + ((size_t)((w + TB_WAVES * j) * 16 + li) * ldb + k0 + q * 8) * 2);
-          acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[j], 0, 0, 0);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < JPW; j++)
-      if (w + TB_WAVES * j < njb) epi(acc[j], w + TB_WAVES * j);
-  }
-
-  // D[in][out] = sum_rows A[row][in] * B[row][out], both operands from LDS
-  // through the transposing read.  The waves form a WM x WN grid: a wave keeps
-  // the B operands of its (at most two) out tiles in registers and walks the
-  // in tiles wm, wm+WM, ...   pre(i0, j, slot) starts the loads the epilogue of a
-  // tile will need before the tile's operand reads and MFMAs; epi(acc, i0, j,
-  // slot) consumes them afterwards.
-  template <typename Pre, typename Epi>
-  __device__ __forceinline__ void gemm_rows(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB, Pre pre,
-                            Epi epi) const {
-    if (KB == 4)
-      gemm_rows_t<true>(Al, lda, Mt, Bl, ldb, Nt, KB, pre, epi);
-    else
-      gemm_rows_t<false>(Al, lda, Mt, Bl, ldb, Nt, KB, pre, epi);
-  }
-
-  template <bool FULL, typename Pre, typename Epi>
-  __device__ __forceinline__ void gemm_rows_t(const char* Al, int lda, int Mt, const char* Bl, int ldb, int Nt, int KB_, Pre pre,
-                              Epi epi) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int KB = FULL ? 4 : KB_;
-    const int WN = (Nt + TB_TPN - 1) / TB_TPN, WM = TB_WAVES / WN;
-    const int wn = w % WN, wm = w / WN;
-    if (wm >= WM) return;
-    bf16x8 bop[TB_TPN][4];
-    int ntile[TB_TPN];
-#pragma unroll
-    for (int i = 0; i < TB_TPN; i++) {
-      ntile[i] = wn + WN * i;
-      if (ntile[i] < Nt) {
-#pragma unroll
-        for (int kb = 0; kb < 4; kb++)
-          if (kb < KB) bop[i][kb] = lds_operand_tr(Bl, ldb, kb * 32, ntile[i] * 16, li, q);
-      }
-    }
-    for (int mt = wm; mt < Mt; mt += WM) {
-#pragma unroll
-      for (int i = 0; i < TB_TPN; i++)
-        if (ntile[i] < Nt) pre(mt * 16 + 4 * q, ntile[i] * 16 + li, i);
-      bf16x8 a[4];
-#pragma unroll
-      for (int kb = 0; kb < 4; kb++)
-        if (kb < KB) a[kb] = lds_operand_tr(Al, lda, kb * 32, mt * 16, li, q);
-      f32x4 acc[TB_TPN];
-#pragma unroll
-      for (int i = 0; i < TB_TPN; i++) {
-        acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ntile[i] < Nt) {
-#pragma unroll
-          for (int kb = 0; kb < 4; kb++)
-            if (kb < KB) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], bop[i][kb], acc[i], 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < TB_TPN; i++)
-        if (ntile[i] < Nt) epi(acc[i], mt * 16 + 4 * q, ntile[i] * 16 + li, i);
-    }
-  }
-
-  // ---- phases ---------------------------------------------------------------
-  // Hidden layer l: level l -> level l+1 (ReLU), all in LDS.
-  __device__ __forceinline__ void forward_hidden(int l, int njb) const {
-    const float* bias = fp(y.bias[l]);
-    char* out = buf(l + 1);
-    const int So = stride(l + 1);
     write_pad(l + 1);
-    gemm_units<32>(bp(y.oi[l]), y.UP[l], buf(l), stride(l), y.UP[l + 1] / 16, njb, y.UP[l],
-                   [&](const f32x4& acc, int u0, int row) {
-                     const f32x4 b = *(const f32x4*)(bias + u0);
-                     bf16x4 pk;
-#pragma unroll
-                     for (int r = 0; r < 4; r++) pk[r] = (__bf16)fmaxf(acc[r] + b[r], 0.f);
-                     *(bf16x4*)(out + ((size_t)row * So + u0) * 2) = pk;
-                   });
     __syncthreads();
   }
 
-  // Output layer + loss.  TRAIN: writes the output delta to dbuf and returns the
-  // lane's share of the summed data loss.  Otherwise accumulates the validation
-  // loss and hit count of the chunk's real rows.
-  template <bool TRAIN>
-  __device__ __forceinline__ void forward_out(int njb, int rows, float inv_mb, double& lsum, double& hits) const {
-    const int l = y.L - 1, c = y.U[y.L];
-    const float* bias = fp(y.bias[l]);
-    const int32_t* rl = rowlist();
-    char* db = lds + y.lds_delta;
-    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
-    const bool cls = P.n_classes >= 2;
-    gemm_out(bp(y.oi[l]), y.UP[l], buf(l), stride(l), njb, y.UP[l], [&](const f32x4& acc, int jb) {
-      const int r = jb * 16 + li;
-      const int row = rl[r];
-      const bool valid = r < rows && row >= 0;
-      const f32x4 b = *(const f32x4*)(bias + 4 * q);
-      float z[4];
-#pragma unroll
-      for (int e = 0; e < 4; e++) z[e] = acc[e] + b[e];
-      float delta[4] = {0.f, 0.f, 0.f, 0.f};
-      if (cls) {
-        const int yr = valid ? ((const int32_t*)P.y)[row] : 0;
-        float mx = -INFINITY;
-        int best = 0;
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-          if (4 * q + e >= c) z[e] = -INFINITY;
-          if (z[e] > mx) {
-            mx = z[e];
-            best = 4 * q + e;
-          }
-        }
-#pragma unroll
-        for (int s = 16; s <= 32; s <<= 1) {
-          const float omx = __shfl_xor(mx, s);
-          const int ob = __shfl_xor(best, s);
-          if (omx > mx || (omx == mx && ob < best)) {
-            mx = omx;
-            best = ob;
-          }
-        }
-        float se = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; e++) se += expf(z[e] - mx);
-        se += __shfl_xor(se, 16);
-        se += __shfl_xor(se, 32);
-        const float lse = mx + logf(se);
-        float zy = (yr >> 2) == q ? z[yr & 3] : 0.f;
-        zy += __shfl_xor(zy, 16);
-        zy += __shfl_xor(zy, 32);
-        if (valid && q == 0) {
-          lsum += (double)(lse - zy);
-          hits += best == yr;
-        }
-        if (TRAIN && valid) {
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            if (4 * q + e < c) delta[e] = (expf(z[e] - lse) - (4 * q + e == yr ? 1.f : 0.f)) * inv_mb;
-        }
-      } else {
-        const float e0 = valid ? z[0] - ((const float*)P.y)[row] : 0.f;
-        if (valid && q == 0) lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
-        if (TRAIN && q == 0) delta[0] = e0 * inv_mb;
-      }
-      if (TRAIN) {
-        bf16x4 pk;
-#pragma unroll
-        for (int e = 0; e < 4; e++) pk[e] = (__bf16)delta[e];
-        *(bf16x4*)(db + ((size_t)r * 16 + 4 * q) * 2) = pk;
-      }
-    });
-    __syncthreads();
-  }
-
-  // Delta of level l (1 <= l < L) from the delta of level l+1, masked by and
-  // written over the level-l activations.
-  __device__ __forceinline__ void backward_data(int l, int njb, int par) const {
-    char* a = buf(l);
-    const int Sa = stride(l);
-    auto epi = [&](const f32x4& acc, int u0, int row) {
-      bf16x4* p = (bf16x4*)(a + ((size_t)row * Sa + u0) * 2);
-      const bf16x4 act = *p;
+  // Delta of level l (1 <= l < L) from the delta of level l+1 (in dbuf for the output level, else in
+  // the buffer), masked by the ReLU pattern of level l, written over the buffer.  Called by all waves.
+  __device__ __forceinline__ void backward_data(int l, int par, int njb, const uint32_t (&bits)[4]) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const bool active = 32 * w < y.UP[l];
+    char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2;
+    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    auto put = [&](const f32x4& acc, int ub, int jb) {
+      const uint32_t nib = bits[ub * 2 + (jb >> 3)] >> ((jb & 7) * 4);
       bf16x4 pk;
 #pragma unroll
-      for (int r = 0; r < 4; r++) pk[r] = (__bf16)((float)act[r] > 0.f ? acc[r] : 0.f);
-      *p = pk;
+      for (int r = 0; r < 4; r++) pk[r] = (__bf16)(((nib >> r) & 1u) ? acc[r] : 0.f);
+      *(bf16x4*)(b + jb * tile_bytes + ub * 32) = pk;
     };
-    if (l + 1 == y.L)
-      gemm_units<16>(bp(y.io[l][par]), 16, lds + y.lds_delta, 16, y.UP[l] / 16, njb, 16, epi);
-    else
-      gemm_units<32>(bp(y.io[l][par]), y.UP[l + 1], buf(l + 1), stride(l + 1), y.UP[l] / 16, njb, y.UP[l + 1], epi);
+    if (l + 1 == y.L) {
+      // the 16-wide output delta sits in its own buffer: nothing is overwritten while it is read
+      if (active) {
+        const __bf16* A = bp(y.io[l][par]);
+        const char* db = dbuf() + ((size_t)li * 16 + 4 * q) * 2;
+#pragma unroll
+        for (int ub = 0; ub < 2; ub++) {
+          const bf16x4 a = *(const bf16x4*)(A + ((size_t)(2 * w + ub) * 16 + li) * 16 + 4 * q);
+#pragma unroll
+          for (int jb = 0; jb < 16; jb++)
+            if (jb < njb) {
+              const bf16x4 d = *(const bf16x4*)(db + jb * 16 * 16 * 2);
+              put(__builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, d, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0), ub, jb);
+            }
+        }
+      }
+    } else {
+      f32x4 acc[2][16];
+      if (active)
+        gemm_unitsplit(bp(y.io[l][par]), y.UP[l + 1] / 32, njb, acc);
+      __syncthreads();
+      if (active) {
+#pragma unroll
+        for (int ub = 0; ub < 2; ub++)
+#pragma unroll
+          for (int jb = 0; jb < 16; jb++)
+            if (jb < njb) put(acc[ub][jb], ub, jb);
+      }
+    }
     __syncthreads();
   }
 
-  // Weight + bias gradient of layer l over the chunk's rows.  Every chunk but
-  // the last of a step adds into the fp32 gradient scratch in global memory;
-  // the last one finishes the sum and applies the optimizer in the epilogue:
-  // master weights and moments are read and written once per step, and the
-  // bf16 [out][in] copy, the [in][out] copy of the next step's parity and the
-  // compact bias are refreshed.  The state loads are issued before the MFMAs
-  // of the tile they belong to.
-  __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next, float* rec) const {
+  // Output layer + loss over the wave's rows (wave w: rows 32w..32w+31).  TRAIN: output delta -> dbuf.
+  template <bool TRAIN>
+  __device__ __forceinline__ void forward_out(int rows, float inv_mb, double& lsum, double& hits) const {
+    const int l = y.L - 1, c = y.U[y.L];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const float* bias = fp(y.bias[l]);
+    const int32_t* rl = rowlist();
+    char* db = dbuf();
+    const bool cls = P.n_classes >= 2;
+    const __bf16* A = bp(y.oi[l]);
+    {
+      const int kbn = y.UP[l] / 32;
+      f32x4 accs[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+      const __bf16* Ap = A + opnd_lane(li, q);
+      const char* bq = buf() + ((size_t)(32 * w + li) * y.S + q * 8) * 2;
+      const size_t tile_bytes = (size_t)16 * y.S * 2;
+      bf16x8 a = *(const bf16x8*)Ap;
+#pragma unroll 1
+      for (int kb = 0; kb < kbn; kb++) {
+        const bf16x8 an = *(const bf16x8*)(Ap + min(kb + 1, kbn - 1) * 512);
+        accs[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + kb * 64), accs[0], 0, 0, 0);
+        accs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + tile_bytes + kb * 64), accs[1], 0, 0, 0);
+        a = an;
+      }
+#pragma unroll
+      for (int jb = 0; jb < 2; jb++) {
+        const f32x4 acc = accs[jb];
+        const int r = 32 * w + jb * 16 + li;
+        const int row = rl[r];
+        const bool valid = r < rows && row >= 0;
+        const f32x4 b = *(const f32x4*)(bias + 4 * q);
+        float z[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) z[e] = acc[e] + b[e];
+        float delta[4] = {0.f, 0.f, 0.f, 0.f};
+        if (cls) {
+          const int yr = valid ? ((const int32_t*)P.y)[row] : 0;
+          float mx = -INFINITY;
+          int best = 0;
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            if (4 * q + e >= c) z[e] = -INFINITY;
+            if (z[e] > mx) {
+              mx = z[e];
+              best = 4 * q + e;
+            }
+          }
+#pragma unroll
+          for (int s = 16; s <= 32; s <<= 1) {
+            const float omx = __shfl_xor(mx, s);
+            const int ob = __shfl_xor(best, s);
+            if (omx > mx || (omx == mx && ob < best)) {
+              mx = omx;
+              best = ob;
+            }
+          }
+          float se = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; e++) se += expf(z[e] - mx);
+          se += __shfl_xor(se, 16);
+          se += __shfl_xor(se, 32);
+          const float lse = mx + logf(se);
+          float zy = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; e++) zy = (4 * q + e == yr) ? z[e] : zy;
+          zy += __shfl_xor(zy, 16);
+          zy += __shfl_xor(zy, 32);
+          if (valid && q == 0) {
+            lsum += (double)(lse - zy);
+            hits += best == yr;
+          }
+          if (TRAIN && valid) {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (4 * q + e < c) delta[e] = (expf(z[e] - lse) - (4 * q + e == yr ? 1.f : 0.f)) * inv_mb;
+          }
+        } else {
+          const float e0 = valid ? z[0] - ((const float*)P.y)[row] : 0.f;
+          if (valid && q == 0) lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+          if (TRAIN && q == 0) delta[0] = e0 * inv_mb;
+        }
+        if (TRAIN) {
+          bf16x4 pk;
+#pragma unroll
+          for (int e = 0; e < 4; e++) pk[e] = (__bf16)delta[e];
+          *(bf16x4*)(db + ((size_t)r * 16 + 4 * q) * 2) = pk;
+        }
+      }
+    }
+  }
+
+  // ---- weight + bias gradient of layer l with the optimizer in the epilogue ------------------------
+  // D[in][out] = sum_rows act[row][in] * delta[row][out].  The work is cut into units of one in tile x a
+  // run of out tiles, dealt round-robin to the waves.  A wave holds the activation operand of its in tile
+  // in registers (read once from the spilled transpose, the next unit's already in flight), takes the delta
+  // operand of each out tile from the buffer, and has the optimizer state of the next tile in flight while
+  // it multiplies and updates the current one.
+  __device__ __forceinline__ void wgrad_t(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
+                                          float* rec) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     float* W = fp(y.w[l]);
     float* Mo = fp(y.m[l]);
     float* Vo = fp(y.v[l]);
@@ -531,69 +529,140 @@ struct Tiled {
     float* bias = fp(y.bias[l]);
     __bf16* oi = bp(y.oi[l]);
     __bf16* io = bp(y.io[l][par_next]);
-    const int fi = y.U[l], fo = y.U[l + 1], up = y.UP[l], ldw = up + TB_PAD, ldo = y.UP[l + 1];
+    const __bf16* T = bp(y.T[l]);
+    const int fi = y.U[l], fo = y.U[l + 1], up = y.UP[l];
+    const int Mt = up / 16 + 1, Me = (fi + 15) / 16 + 1, Ne = (fo + 15) / 16, Nt = y.UP[l + 1] / 16;
+    char* trp = lds + y.lds_tr + w * 512;
     const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
-    const bool lastlayer = l + 1 == y.L;
-    const char* Bl = lastlayer ? lds + y.lds_delta : buf(l + 1);
-    const int ldb = lastlayer ? 16 : stride(l + 1);
+    const bool lastlayer = l + 1 == y.L;  // its activation operand is still in the buffer, its delta in dbuf
+    const char* Bl = lastlayer ? dbuf() : buf();
+    const int ldb = lastlayer ? 16 : y.S;
     const bool adam = oc.adam;
-    f32x4 pg[TB_TPN], pw[TB_TPN], pm[TB_TPN], pv[TB_TPN];
-    auto live = [&](int i0, int j) { return j < fo && (i0 < fi || i0 == up); };
-    gemm_rows(
-        buf(l), stride(l), up / 16 + 1, Bl, ldb, y.UP[l + 1] / 16, KB,
-        [&](int i0, int j, int s) {
-          if (!live(i0, j)) return;
-          const size_t o = (size_t)j * ldw + i0;
-          if (!first) pg[s] = *(const f32x4*)(Gp + o);
-          if (last) {
-            pw[s] = *(const f32x4*)(W + o);
-            pm[s] = *(const f32x4*)(Mo + o);
-            if (adam) pv[s] = *(const f32x4*)(Vo + o);
-          }
-        },
-        [&](const f32x4& acc, int i0, int j, int s) {
-          if (!live(i0, j)) return;
-          const bool isb = i0 == up;
-          const size_t o = (size_t)j * ldw + i0;
-          f32x4 g = acc;
-          if (!first) {
+    // number of runs the out tiles are cut into: the one that spreads Me * NS units most evenly
+    int NS = 1, best = 1 << 30;
+    for (int ns = 1; ns <= 4 && ns <= Ne; ns++) {
+      const int c = ((Me * ns + TB_WAVES - 1) / TB_WAVES) * ((Ne + ns - 1) / ns);
+      if (c < best) {
+        best = c;
+        NS = ns;
+      }
+    }
+    const int NU = Me * NS;
+    auto unit_tiles = [&](int u, int& mt, int& nt0, int& nt1) {
+      const int me = u / NS, sg = u % NS;  // the runs of one in tile go to neighbouring waves: one fetch of its operand
+      mt = me == Me - 1 ? Mt - 1 : me;  // the last one is the bias tile
+      nt0 = sg * Ne / NS;
+      nt1 = (sg + 1) * Ne / NS;
+    };
+    auto load_a = [&](int mt, bf16x8(&a)[8]) {
 #pragma unroll
-            for (int r = 0; r < 4; r++) g[r] += pg[s][r];
-          }
-          if (!last) {
-            *(f32x4*)(Gp + o) = g;
-            return;
-          }
-          f32x4 w = pw[s], m = pm[s], v = adam ? pv[s] : f32x4{0.f, 0.f, 0.f, 0.f};
-          bf16x4 pk;
+      for (int kb = 0; kb < 8; kb++)
+        if (kb < KB)
+          a[kb] = lastlayer ? lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q)
+                            : *(const bf16x8*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+    };
+    auto load_st = [&](int mt, int nt, f32x4& sw, f32x4& sm, f32x4& sv) {
+      const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
+      sw = *(const f32x4*)(W + o);
+      sm = *(const f32x4*)(Mo + o);
+      if (adam) sv = *(const f32x4*)(Vo + o);
+    };
+    int u = w;
+    if (u >= NU) return;
+    int mt, nt0, nt1;
+    unit_tiles(u, mt, nt0, nt1);
+    bf16x8 an[8];
+    load_a(mt, an);
+    f32x4 nw = f32x4{0.f, 0.f, 0.f, 0.f}, nm = nw, nv = nw;
+    if (last) load_st(mt, nt0, nw, nm, nv);
+    while (u < NU) {
+      bf16x8 a[8];
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++) a[kb] = an[kb];
+      const int u2 = u + TB_WAVES;
+      const bool more = u2 < NU;
+      int mt2 = mt, nt02 = nt0, nt12 = nt1;
+      if (more) {
+        unit_tiles(u2, mt2, nt02, nt12);
+        load_a(mt2, an);
+      }
+      const bool isb = mt == Mt - 1;
+      for (int nt = nt0; nt < nt1; nt++) {
+        f32x4 wv = nw, mv = nm, vv = nv;
+        if (last) {  // state of the tile after this one (a repeat of this one when there is none)
+          const bool same = nt + 1 < nt1;
+          load_st(same || !more ? mt : mt2, same ? nt + 1 : (more ? nt02 : nt), nw, nm, nv);
+        }
+        const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
+        f32x4 g = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (!first) g = *(const f32x4*)(Gp + o);
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++)
+          if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
+        if (!last) {
+          *(f32x4*)(Gp + o) = g;
+          continue;
+        }
+        // the lane holds in units i0..i0+3 (or the bias in r = 0 of lane group 0), out unit j
+        const int i0 = mt * 16 + 4 * q, j = nt * 16 + li;
+        bf16x4 pk;
+        if (!isb && !rec && mt * 16 + 16 <= fi && nt * 16 + 16 <= fo) {  // no pad unit in the tile
 #pragma unroll
           for (int r = 0; r < 4; r++) {
-            const int i = i0 + r;
-            const bool on = isb ? r == 0 : i < fi;
-            float wr = w[r], mr = m[r], vr = v[r];
+            float wr = wv[r], mr = mv[r], vr = vv[r];
+            opt_update(oc, g[r] + oc.am * wr, wr, mr, vr);
+            wv[r] = wr;
+            mv[r] = mr;
+            vv[r] = vr;
+            pk[r] = (__bf16)wr;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            const int ii = i0 + r;
+            const bool on = j < fo && (isb ? (q == 0 && r == 0) : ii < fi);
+            float wr = wv[r], mr = mv[r], vr = vv[r];
             if (on) {
               const float gg = isb ? g[r] : g[r] + oc.am * wr;
               opt_update(oc, gg, wr, mr, vr);
               if (rec) {
-                const int ci = isb ? cb + j : cw + i * fo + j;
+                const int ci = isb ? cb + j : cw + ii * fo + j;
                 rec[1 + ci] = gg;
                 rec[1 + Pn + ci] = wr;
               }
-              if (!isb && l >= 1) io[(size_t)i * ldo + j] = (__bf16)wr;
             }
-            w[r] = wr;
-            m[r] = mr;
-            v[r] = vr;
+            wv[r] = wr;
+            mv[r] = mr;
+            vv[r] = vr;
             pk[r] = (__bf16)wr;
           }
-          *(f32x4*)(W + o) = w;
-          *(f32x4*)(Mo + o) = m;
-          if (adam) *(f32x4*)(Vo + o) = v;
-          if (isb)
-            bias[j] = w[0];
-          else
-            *(bf16x4*)(oi + (size_t)j * up + i0) = pk;
-        });
+        }
+        *(f32x4*)(W + o) = wv;
+        *(f32x4*)(Mo + o) = mv;
+        if (adam) *(f32x4*)(Vo + o) = vv;
+        if (isb) {
+          if (q == 0 && j < fo) bias[j] = wv[0];
+        } else {
+          // both bf16 operand copies are made of 16 x 16 tiles, so the wave writes 512 contiguous bytes each
+          *(bf16x4*)(oi + ((size_t)nt * (Mt - 1) + mt) * 256 + li * 16 + 4 * q) = pk;
+          if (l >= 1) {
+            // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
+            *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
+            const s16x4 tv = lds_read_tr(trp + ((4 * q + (li >> 2)) * 16 + 4 * (li & 3)) * 2);
+            *(s16x4*)(io + ((size_t)mt * Nt + nt) * 256 + li * 16 + 4 * q) = tv;
+          }
+        }
+      }
+      u = u2;
+      mt = mt2;
+      nt0 = nt02;
+      nt1 = nt12;
+    }
+  }
+
+  __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
+                                        float* rec) const {
+    wgrad_t(l, KB, first, last, oc, par_next, rec);
     __syncthreads();
   }
 
@@ -601,13 +670,35 @@ struct Tiled {
     double s = 0.0;
     for (int l = 0; l < y.L; l++) {
       const float* W = fp(y.w[l]);
-      const int fi = y.U[l], fo = y.U[l + 1], ldw = y.UP[l] + TB_PAD;
+      const int fi = y.U[l], fo = y.U[l + 1];
       for (int i = threadIdx.x; i < fi * fo; i += blockDim.x) {
-        const float w = W[(size_t)(i / fi) * ldw + (i % fi)];
+        const float w = W[sidx(l, i % fi, i / fi)];
         s += (double)w * (double)w;
       }
     }
     return block_sum(s, red);
+  }
+
+  // Forward pass of the chunk through all layers.  TRAIN: spills the transposes the weight gradients
+  // will need, keeps the ReLU patterns, writes the output delta.  Called by all waves.
+  template <bool TRAIN>
+  __device__ __forceinline__ void forward_all(int rows, float inv_mb, uint32_t (&bits)[2][4], double& lsum,
+                                              double& hits) const {
+    const int w = threadIdx.x >> 6;
+    const int KB = (rows + 31) / 32;  // row blocks in use; whole blocks are computed
+    for (int l = 0; l + 1 < y.L; l++) {
+      if (TRAIN && w < KB) spill_transposed(l);
+      uint32_t bl[4];
+      forward_hidden(l, 2 * KB, bl);
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        if (l & 1)
+          bits[1][i] = bl[i];
+        else
+          bits[0][i] = bl[i];
+      }
+    }
+    if (w < KB) forward_out<TRAIN>(rows, inv_mb, lsum, hits);
   }
 
   __device__ __forceinline__ void run() const {
@@ -655,6 +746,7 @@ struct Tiled {
     oc.lr = it.lr;
     oc.lr_t = it.lr;
 
+    uint32_t bits[2][4];
     for (int e = e0; e < it.epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
       for (int st = e == e0 ? st0 : 0; st < steps; st++, gstep++) {
@@ -675,18 +767,19 @@ struct Tiled {
         double lsum = 0.0, hits = 0.0;
         for (int ch = 0; ch < nch; ch++) {
           const int rows = min(TB_ROWS, mb - ch * TB_ROWS);
-          const int KB = (rows + 31) / 32, njb = 2 * KB;
-          stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true, true);
+          const int KB = (rows + 31) / 32;
+          const bool first = ch == 0, last = ch == nch - 1;
+          stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true);
+          forward_all<true>(rows, inv_mb, bits, lsum, hits);
           __syncthreads();
-          for (int l = 0; l + 1 < L; l++) forward_hidden(l, njb);
-          forward_out<true>(njb, rows, inv_mb, lsum, hits);
           for (int l = L - 1; l >= 0; l--) {
-            if (l == 0 && L == 3) {  // level 0 shared its buffer with level 2: gather the inputs again
-              stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true, false);
-              __syncthreads();
+            wgrad(l, KB, first, last, oc, par ^ 1, last ? rec : nullptr);
+            if (l >= 1) {
+              uint32_t bl[4];
+#pragma unroll
+              for (int i = 0; i < 4; i++) bl[i] = ((l - 1) & 1) ? bits[1][i] : bits[0][i];
+              backward_data(l, par, 2 * KB, bl);
             }
-            wgrad(l, KB, ch == 0, ch == nch - 1, oc, par ^ 1, rec);
-            if (l >= 1) backward_data(l, njb, par);
           }
         }
         if (rec) {
@@ -700,11 +793,9 @@ struct Tiled {
     double lsum = 0.0, hits = 0.0;
     for (int off = 0; off < n_va; off += TB_ROWS) {
       const int rows = min(TB_ROWS, n_va - off);
-      const int njb = 2 * ((rows + 31) / 32);
-      stage_rows(va, 0, n_va, off, rows, false, true);
+      stage_rows(va, 0, n_va, off, rows, false);
+      forward_all<false>(rows, 0.f, bits, lsum, hits);
       __syncthreads();
-      for (int l = 0; l + 1 < L; l++) forward_hidden(l, njb);
-      forward_out<false>(njb, rows, 0.f, lsum, hits);
     }
     lsum = block_sum(lsum, red);
     hits = block_sum(hits, red);
