@@ -45,7 +45,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TB_ROWS = 256;  // rows per chunk
-constexpr int TB_PAD = 16;    // pad columns per LDS row
+constexpr int TB_PAD = 8;     // pad elements per LDS row: consecutive rows start 4 banks apart
 constexpr int TB_MAXL = 3;    // weight layers
 constexpr int TB_MAXU = 256;  // padded units per level
 constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns rows 32w..32w+31 in the row phases
@@ -59,8 +59,8 @@ struct TLay {
   int32_t S;                // LDS row stride in elements
   int32_t cw[TB_MAXL], cb[TB_MAXL], P;
   uint32_t lds_buf, lds_delta, lds_rows, lds_tr, lds_total;
-  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL], io[TB_MAXL][2], bias[TB_MAXL],
-      T[TB_MAXL], total;
+  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL], io[TB_MAXL][2], T[TB_MAXL];
+  uint64_t bias[TB_MAXL], bm[TB_MAXL], bv[TB_MAXL], bg[TB_MAXL], total;  // bias: value, moments, partial gradient
 };
 
 __host__ __device__ inline bool tiled_eligible(const int32_t* dims, int L) {
@@ -104,7 +104,7 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
     return o;
   };
   for (int l = 0; l < L; l++) {
-    const uint64_t wn = (uint64_t)(y.UP[l + 1] / 16) * (y.UP[l] / 16 + 1) * 256;
+    const uint64_t wn = (uint64_t)y.UP[l + 1] * y.UP[l];
     y.w[l] = take(wn * 4);
     y.m[l] = take(wn * 4);
     y.v[l] = take(wn * 4);
@@ -116,8 +116,11 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
       y.io[l][1] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
     }
     y.bias[l] = take((uint64_t)y.UP[l + 1] * 4);
+    y.bm[l] = take((uint64_t)y.UP[l + 1] * 4);
+    y.bv[l] = take((uint64_t)y.UP[l + 1] * 4);
+    y.bg[l] = take((uint64_t)y.UP[l + 1] * 4);
     // transposed spill of level l: needed by the weight gradient of every layer but the last
-    y.T[l] = l <= L - 2 ? take((uint64_t)(y.UP[l] + 16) * TB_ROWS * 2) : 0;
+    y.T[l] = l <= L - 2 ? take((uint64_t)y.UP[l] * TB_ROWS * 2) : 0;
   }
   y.total = off;
 }
@@ -185,9 +188,9 @@ struct Tiled {
   __device__ __forceinline__ int32_t* rowlist() const { return (int32_t*)(lds + y.lds_rows); }
 
   // ---- blocked indices ------------------------------------------------------
-  // state element (in unit k, out unit j) of layer l; the bias is in unit k = UP[l]
+  // state element (in unit k, out unit j) of layer l
   __device__ __forceinline__ size_t sidx(int l, int k, int j) const {
-    const int mta = y.UP[l] / 16 + 1;
+    const int mta = y.UP[l] / 16;
     return ((size_t)(j >> 4) * mta + (k >> 4)) * 256 + ((((k & 15) >> 2) << 4) + (j & 15)) * 4 + (k & 3);
   }
   // forward operand copy: 16 x 16 tiles [out tile][in tile][out unit][in unit]
@@ -205,7 +208,6 @@ struct Tiled {
   // ---- parameters -------------------------------------------------------
   __device__ __forceinline__ void store_param(int l, int k, int j, bool isb, float val, int par) const {
     if (isb) {
-      fp(y.w[l])[sidx(l, y.UP[l], j)] = val;
       fp(y.bias[l])[j] = val;
     } else {
       fp(y.w[l])[sidx(l, k, j)] = val;
@@ -236,11 +238,16 @@ struct Tiled {
       for (int i = threadIdx.x; i < fi * fo + fo; i += blockDim.x) {
         const bool isb = i >= fi * fo;
         const int e = isb ? i - fi * fo : i;
-        const int k = isb ? y.UP[l] : e / fo, j = isb ? e : e % fo;
+        const int k = isb ? 0 : e / fo, j = isb ? e : e % fo;
         const int ci = (isb ? y.cb[l] : y.cw[l]) + e;
         store_param(l, k, j, isb, st[ci], par);
-        fp(y.m[l])[sidx(l, k, j)] = st[y.P + ci];
-        fp(y.v[l])[sidx(l, k, j)] = st[2 * y.P + ci];
+        if (isb) {
+          fp(y.bm[l])[j] = st[y.P + ci];
+          fp(y.bv[l])[j] = st[2 * y.P + ci];
+        } else {
+          fp(y.m[l])[sidx(l, k, j)] = st[y.P + ci];
+          fp(y.v[l])[sidx(l, k, j)] = st[2 * y.P + ci];
+        }
       }
     }
   }
@@ -253,29 +260,24 @@ struct Tiled {
     for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x)
       rl[p] = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
     __syncthreads();
-    const int d = y.U[0], up0 = y.UP[0], S = y.S, vpr = up0 / 8 + 2;  // data vectors + two pad vectors per row
+    const int d = y.U[0], up0 = y.UP[0], S = y.S, vpr = up0 / 8;  // 16-byte vectors per row
     char* b0 = buf();
     const __bf16* X = (const __bf16*)P.X;
     for (int idx = threadIdx.x; idx < TB_ROWS * vpr; idx += blockDim.x) {
       const int r = idx / vpr, vv = idx - r * vpr;
       const int row = rl[r];
       uint4 val = uint4{0, 0, 0, 0};
-      if (row >= 0) {
-        if (vv * 8 < d)
-          val = *(const uint4*)(X + (size_t)row * d + vv * 8);
-        else if (vv * 8 == up0)
-          val.x = 0x3F80u;  // bf16 1.0 in column UP[0]
-      }
+      if (row >= 0 && vv * 8 < d) val = *(const uint4*)(X + (size_t)row * d + vv * 8);
       *(uint4*)(b0 + ((size_t)r * S + vv * 8) * 2) = val;
     }
     __syncthreads();
   }
 
-  // Transpose of the wave's rows of level l (units 0..UP[l]+15) to global, tile-blocked [unit tile][row block][unit][32 rows].
+  // Transpose of the wave's rows of level l to global, tile-blocked [unit tile][row block][unit][32 rows].
   __device__ __forceinline__ void spill_transposed(int l) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     __bf16* T = bp(y.T[l]);
-    const int mta = y.UP[l] / 16 + 1;
+    const int mta = y.UP[l] / 16;
     for (int mt = 0; mt < mta; mt++) {
       const bf16x8 v = lds_operand_tr(buf(), y.S, 32 * w, mt * 16, li, q);
       *(bf16x8*)(T + (((size_t)mt * 8 + w) * 16 + li) * 32 + q * 8) = v;
@@ -329,16 +331,6 @@ struct Tiled {
       sweep(std::false_type());
   }
 
-  // Pad columns of a level: column UP is 1 on real rows, the rest 0.
-  __device__ __forceinline__ void write_pad(int level) const {
-    if (threadIdx.x < TB_ROWS) {
-      const int r = threadIdx.x;
-      char* p = buf() + ((size_t)r * y.S + y.UP[level]) * 2;
-      *(uint4*)p = uint4{rowlist()[r] >= 0 ? 0x3F80u : 0u, 0, 0, 0};
-      *(uint4*)(p + 16) = uint4{0, 0, 0, 0};
-    }
-  }
-
   // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
   // (bit 4*(16*ub + jb) + r).  Called by all waves.
   __device__ __forceinline__ void forward_hidden(int l, int njb, uint32_t (&bits)[4]) const {
@@ -372,7 +364,6 @@ struct Tiled {
           }
       }
     }
-    write_pad(l + 1);
     __syncthreads();
   }
 
@@ -438,14 +429,16 @@ struct Tiled {
       const __bf16* Ap = A + opnd_lane(li, q);
       const char* bq = buf() + ((size_t)(32 * w + li) * y.S + q * 8) * 2;
       const size_t tile_bytes = (size_t)16 * y.S * 2;
-      bf16x8 a = *(const bf16x8*)Ap;
-#pragma unroll 1
-      for (int kb = 0; kb < kbn; kb++) {
-        const bf16x8 an = *(const bf16x8*)(Ap + min(kb + 1, kbn - 1) * 512);
-        accs[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + kb * 64), accs[0], 0, 0, 0);
-        accs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + tile_bytes + kb * 64), accs[1], 0, 0, 0);
-        a = an;
-      }
+      bf16x8 a[8];
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++)
+        if (kb < kbn) a[kb] = *(const bf16x8*)(Ap + kb * 512);
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++)
+        if (kb < kbn) {
+          accs[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], *(const bf16x8*)(bq + kb * 64), accs[0], 0, 0, 0);
+          accs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], *(const bf16x8*)(bq + tile_bytes + kb * 64), accs[1], 0, 0, 0);
+        }
 #pragma unroll
       for (int jb = 0; jb < 2; jb++) {
         const f32x4 acc = accs[jb];
@@ -518,7 +511,8 @@ struct Tiled {
   // run of out tiles, dealt round-robin to the waves.  A wave holds the activation operand of its in tile
   // in registers (read once from the spilled transpose, the next unit's already in flight), takes the delta
   // operand of each out tile from the buffer, and has the optimizer state of the next tile in flight while
-  // it multiplies and updates the current one.
+  // it multiplies and updates the current one.  One more "in tile" whose operand is a row of ones gives
+  // the bias gradient (the deltas of unused rows are zero); the bias and its moments are plain arrays.
   __device__ __forceinline__ void wgrad_t(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                           float* rec) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
@@ -527,11 +521,14 @@ struct Tiled {
     float* Vo = fp(y.v[l]);
     float* Gp = fp(y.gp[l]);
     float* bias = fp(y.bias[l]);
+    float* bm = fp(y.bm[l]);
+    float* bv = fp(y.bv[l]);
+    float* bg = fp(y.bg[l]);
     __bf16* oi = bp(y.oi[l]);
     __bf16* io = bp(y.io[l][par_next]);
     const __bf16* T = bp(y.T[l]);
-    const int fi = y.U[l], fo = y.U[l + 1], up = y.UP[l];
-    const int Mt = up / 16 + 1, Me = (fi + 15) / 16 + 1, Ne = (fo + 15) / 16, Nt = y.UP[l + 1] / 16;
+    const int fi = y.U[l], fo = y.U[l + 1];
+    const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Me = (fi + 15) / 16 + 1, Ne = (fo + 15) / 16;
     char* trp = lds + y.lds_tr + w * 512;
     const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
     const bool lastlayer = l + 1 == y.L;  // its activation operand is still in the buffer, its delta in dbuf
@@ -548,24 +545,39 @@ struct Tiled {
       }
     }
     const int NU = Me * NS;
+    // unit u: in tile mt (mt == Me - 1: the bias) and out tiles nt0..nt1-1; the runs of one in tile go to
+    // neighbouring waves, which fetch its operand at the same time
     auto unit_tiles = [&](int u, int& mt, int& nt0, int& nt1) {
-      const int me = u / NS, sg = u % NS;  // the runs of one in tile go to neighbouring waves: one fetch of its operand
-      mt = me == Me - 1 ? Mt - 1 : me;  // the last one is the bias tile
+      mt = u / NS;
+      const int sg = u % NS;
       nt0 = sg * Ne / NS;
       nt1 = (sg + 1) * Ne / NS;
     };
     auto load_a = [&](int mt, bf16x8(&a)[8]) {
+      if (mt == Me - 1) {
+        const __bf16 o = (__bf16)(li == 0 ? 1.f : 0.f);
 #pragma unroll
-      for (int kb = 0; kb < 8; kb++)
-        if (kb < KB)
-          a[kb] = lastlayer ? lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q)
-                            : *(const bf16x8*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+        for (int kb = 0; kb < 8; kb++) a[kb] = bf16x8{o, o, o, o, o, o, o, o};
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++)
+          if (kb < KB)
+            a[kb] = lastlayer ? lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q)
+                              : *(const bf16x8*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+      }
     };
     auto load_st = [&](int mt, int nt, f32x4& sw, f32x4& sm, f32x4& sv) {
-      const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
-      sw = *(const f32x4*)(W + o);
-      sm = *(const f32x4*)(Mo + o);
-      if (adam) sv = *(const f32x4*)(Vo + o);
+      if (mt == Me - 1) {
+        const int j = nt * 16 + li;
+        sw[0] = bias[j];
+        sm[0] = bm[j];
+        if (adam) sv[0] = bv[j];
+      } else {
+        const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
+        sw = *(const f32x4*)(W + o);
+        sm = *(const f32x4*)(Mo + o);
+        if (adam) sv = *(const f32x4*)(Vo + o);
+      }
     };
     int u = w;
     if (u >= NU) return;
@@ -586,27 +598,51 @@ struct Tiled {
         unit_tiles(u2, mt2, nt02, nt12);
         load_a(mt2, an);
       }
-      const bool isb = mt == Mt - 1;
+      const bool isb = mt == Me - 1;
       for (int nt = nt0; nt < nt1; nt++) {
         f32x4 wv = nw, mv = nm, vv = nv;
         if (last) {  // state of the tile after this one (a repeat of this one when there is none)
           const bool same = nt + 1 < nt1;
           load_st(same || !more ? mt : mt2, same ? nt + 1 : (more ? nt02 : nt), nw, nm, nv);
         }
+        const int j = nt * 16 + li;  // the lane's out unit
         const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
         f32x4 g = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (!first) g = *(const f32x4*)(Gp + o);
+        if (!first) {
+          if (isb)
+            g[0] = bg[j];
+          else
+            g = *(const f32x4*)(Gp + o);
+        }
 #pragma unroll
         for (int kb = 0; kb < 8; kb++)
           if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
         if (!last) {
-          *(f32x4*)(Gp + o) = g;
+          if (isb) {
+            if (q == 0) bg[j] = g[0];
+          } else {
+            *(f32x4*)(Gp + o) = g;
+          }
           continue;
         }
-        // the lane holds in units i0..i0+3 (or the bias in r = 0 of lane group 0), out unit j
-        const int i0 = mt * 16 + 4 * q, j = nt * 16 + li;
+        if (isb) {  // r = 0 of lane group 0 holds the bias gradient of out unit j
+          if (q == 0 && j < fo) {
+            float wr = wv[0], mr = mv[0], vr = vv[0];
+            opt_update(oc, g[0], wr, mr, vr);
+            if (rec) {
+              rec[1 + cb + j] = g[0];
+              rec[1 + Pn + cb + j] = wr;
+            }
+            bias[j] = wr;
+            bm[j] = mr;
+            if (adam) bv[j] = vr;
+          }
+          continue;
+        }
+        // the lane holds in units i0..i0+3 of out unit j
+        const int i0 = mt * 16 + 4 * q;
         bf16x4 pk;
-        if (!isb && !rec && mt * 16 + 16 <= fi && nt * 16 + 16 <= fo) {  // no pad unit in the tile
+        if (!rec && mt * 16 + 16 <= fi && nt * 16 + 16 <= fo) {  // no pad unit in the tile
 #pragma unroll
           for (int r = 0; r < 4; r++) {
             float wr = wv[r], mr = mv[r], vr = vv[r];
@@ -620,13 +656,12 @@ struct Tiled {
 #pragma unroll
           for (int r = 0; r < 4; r++) {
             const int ii = i0 + r;
-            const bool on = j < fo && (isb ? (q == 0 && r == 0) : ii < fi);
             float wr = wv[r], mr = mv[r], vr = vv[r];
-            if (on) {
-              const float gg = isb ? g[r] : g[r] + oc.am * wr;
+            if (j < fo && ii < fi) {
+              const float gg = g[r] + oc.am * wr;
               opt_update(oc, gg, wr, mr, vr);
               if (rec) {
-                const int ci = isb ? cb + j : cw + ii * fo + j;
+                const int ci = cw + ii * fo + j;
                 rec[1 + ci] = gg;
                 rec[1 + Pn + ci] = wr;
               }
@@ -640,17 +675,13 @@ struct Tiled {
         *(f32x4*)(W + o) = wv;
         *(f32x4*)(Mo + o) = mv;
         if (adam) *(f32x4*)(Vo + o) = vv;
-        if (isb) {
-          if (q == 0 && j < fo) bias[j] = wv[0];
-        } else {
-          // both bf16 operand copies are made of 16 x 16 tiles, so the wave writes 512 contiguous bytes each
-          *(bf16x4*)(oi + ((size_t)nt * (Mt - 1) + mt) * 256 + li * 16 + 4 * q) = pk;
-          if (l >= 1) {
-            // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
-            *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
-            const s16x4 tv = lds_read_tr(trp + ((4 * q + (li >> 2)) * 16 + 4 * (li & 3)) * 2);
-            *(s16x4*)(io + ((size_t)mt * Nt + nt) * 256 + li * 16 + 4 * q) = tv;
-          }
+        // both bf16 operand copies are made of 16 x 16 tiles, so the wave writes 512 contiguous bytes each
+        *(bf16x4*)(oi + ((size_t)nt * Mt + mt) * 256 + li * 16 + 4 * q) = pk;
+        if (l >= 1) {
+          // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
+          *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
+          const s16x4 tv = lds_read_tr(trp + ((4 * q + (li >> 2)) * 16 + 4 * (li & 3)) * 2);
+          *(s16x4*)(io + ((size_t)mt * Nt + nt) * 256 + li * 16 + 4 * q) = tv;
         }
       }
       u = u2;
