@@ -4,34 +4,35 @@
 //
 // One workgroup (8 waves) trains one model, one model per CU.  A minibatch of
 // up to 256 rows is processed at once; its activations live in ONE row-major
-// LDS buffer buf[row][unit] (16 pad columns per row, the first of which is 1
-// on real rows: it turns the weight-gradient GEMM into weight + bias
-// gradient), which every layer overwrites in place:
+// LDS buffer buf[row][unit], which every layer overwrites in place:
 //
-//   forward / data gradient  ("row phases"): wave w owns rows 32w..32w+31.  It
-//     loads its rows of the current level into registers as MFMA B operands,
-//     streams the bf16 weight tiles from global memory as A operands
-//     (D[unit][row] = W[unit][k] . act[row][k]) and writes the next level over
-//     its own rows as 8-byte stores.  ReLU masks are kept as bits in registers,
-//     so a delta can overwrite the activation it is masked by even after that
-//     activation is gone.  No barrier between the layers of a pass.
-//   weight gradient ("unit phases"): contraction over the rows.  The delta
-//     operand comes from the LDS buffer through the transposing LDS read
-//     (ds_read_b64_tr_b16).  The activation operand comes the same way for the
-//     last hidden level; lower levels were overwritten by then, so each wave
-//     spills the transpose of its rows to global memory before it overwrites
-//     them (tile-blocked, read back as 16-byte operand vectors).
+//   hidden layers, forward and data gradient: wave w owns units 32w..32w+31 of
+//     the level it produces.  It streams its tiles of the bf16 weight copy from
+//     global memory as MFMA A operands (D[unit][row] = W[unit][k] . act[row][k]),
+//     takes the level from the buffer as B operands, keeps all results in
+//     registers until every wave has read the level (barrier), then writes the
+//     next level over it.  ReLU masks are kept as bits in registers, so a delta
+//     can overwrite the activation it is masked by.
+//   output layer: one wave per 32 rows; softmax, loss and output delta in the
+//     MFMA result layout; the 16-wide delta has a buffer of its own.
+//   weight gradient: contraction over the rows.  The delta operand comes from
+//     the LDS buffer through the transposing LDS read (ds_read_b64_tr_b16).  The
+//     activation operand comes the same way for the last hidden level; lower
+//     levels were overwritten by then, so each wave spills the transpose of its
+//     rows to global memory before that happens (tile-blocked, read back as
+//     16-byte operand vectors).  The bias gradient uses a row of ones as operand.
 //   The optimizer runs in the weight-gradient epilogue on the accumulator
-//   registers: fp32 master weights and moments are read and written once per
-//   step and the two bf16 operand copies ([out][in] for forward, [in][out] for
-//   backward; the latter double-buffered by step parity, because the backward
-//   pass of the same step still needs the old weights) are refreshed.
+//   registers: fp32 master weights and moments are read (one tile ahead) and
+//   written once per step and the two bf16 operand copies ([out][in] for
+//   forward, [in][out] for backward; the latter double-buffered by step parity,
+//   because the backward pass of the same step still needs the old weights) are
+//   refreshed.
 //
-// Every global array is stored in the order its wave-level accesses touch it
-// (tile-blocked), so each load or store instruction of a wave covers 1 KB of
-// contiguous memory: state tiles [out tile][in tile][lane][4], operand tiles
-// [unit tile][k block][unit][32 k].  Batches above 256 rows are processed in
-// chunks whose partial gradients pass through an fp32 scratch.
+// Every global array is stored in the order its wave-level accesses touch it:
+// fp32 state as 16 x 16 tiles [out tile][in tile][lane][4] (1 KB per access),
+// operand copies as 16 x 16 bf16 tiles (512 B per store, 1 KB per load), spills
+// as [unit tile][32-row block][unit][row].  Batches above 256 rows are processed
+// in chunks whose partial gradients pass through an fp32 scratch.
 #pragma once
 #include <type_traits>
 
