@@ -177,7 +177,9 @@ def test_single_steps_from_oracle_state_fp32(bb, oracle, n, d, c, hidden, solver
 
 
 @pytest.mark.parametrize("n,d,c,hidden,bs", [(600, 128, 10, [128, 160], 256), (300, 40, 3, [70], 100),
-                                             (500, 128, 10, [256, 256], 256), (200, 33, 0, [45, 31], 64)])
+                                             (500, 128, 10, [256, 256], 256), (200, 33, 0, [45, 31], 64),
+                                             (700, 64, 5, [96, 72], 0),      # full batch: three chunks of rows per step
+                                             (420, 256, 16, [219], 300)])    # two chunks, widest input, 16 outputs
 def test_per_step_gradients_and_weights_bf16(bb, oracle, n, d, c, hidden, bs):
     cfg = small_problem(n + d, n, d, c, bf16=True)
     hp = {"hidden": hidden, "solver": "adam", "batch_size": bs, "alpha": 0.01, "lr": 0.002, "epochs": 6,
@@ -196,7 +198,10 @@ def test_per_step_gradients_and_weights_bf16(bb, oracle, n, d, c, hidden, bs):
             assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (t, name, "theta")
     assert abs(pf[0, f, 0].item() - ref["scores"][0]) < ABS_SCORE
     # later steps, each started from the oracle's state
-    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [1, 4, 7, 11], T):
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    total = hp["epochs"] * -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(T, total)
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in [1, 4, 7, 11] if t < T], T):
         for name, sl in layer_slices(d, hidden, c_out):
             assert relerr(g1[sl], rg[sl]) < REL_BF16, (t, name, "grad")
             assert relerr(th1[sl], rth[sl]) < REL_BF16, (t, name, "theta")
@@ -223,21 +228,37 @@ def test_final_cv_scores_match_oracle(bb, oracle, idx, kw):
     K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
     scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, cfg["hparams"], dt, want_per_fold=True)
     torch.cuda.synchronize()
-    scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
-    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, cfg["hparams"], dtype=dt)
-    # The same runs without any fp32 rounding give each suggestion's own sensitivity to rounding
-    # ("noise").  Below a tenth of the bar the run is stable and held to 1e-3.  A run that amplifies
-    # rounding noise up to the size of the bar (bf16 operands do: one flipped rounding moves an
-    # activation by 0.4 %) is held to the bar widened by twice its own noise; beyond that (large
-    # learning rates) trajectories are chaotic and only finiteness is compared.
-    rs64, _, rpf64 = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, cfg["hparams"], dtype=dt, prec=1)
+    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, cfg["hparams"], scores.cpu().numpy(),
+                                                   status.cpu().numpy(), pf.cpu().numpy())
+    if dt == 0:
+        assert n_strict >= max(1, len(cfg["hparams"]) // 2)
+    else:
+        assert n_strict + n_wide >= 1
+
+
+def check_scores_against_oracle(oracle, cfg, hps, scores, status, pf):
+    """Final scores of the suggestions `hps` against the oracle.
+
+    A training run amplifies rounding differences by a factor that depends on the run (Adam with a
+    large learning rate turns the sign of a gradient element that is nearly zero into a full step).
+    The oracle measures that factor itself: the run is repeated with no fp32 rounding of the state
+    and with the learning rate moved by one fp32 ulp either way; the largest change of a fold score
+    is the run's "noise".  Below a tenth of the 1e-3 bar the run is stable and held to the bar.  Up
+    to the bar it is held to the bar widened by twice its noise.  Beyond it the trajectory is
+    chaotic and only finiteness and the status flag are compared.  Returns (stable, widened) counts."""
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    run = lambda h, **kw: oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, h, dtype=dt, **kw)
+    rs, rst, rpf = run(hps)
+    probes = [run(hps, prec=1)[2]]
+    for toward in (np.float32(1e9), np.float32(0)):
+        probes.append(run([dict(h, lr=float(np.nextafter(np.float32(h.get("lr", 1e-3)), toward))) for h in hps])[2])
     n_va = len(cfg["y"]) // K
     n_strict = n_wide = 0
-    for b in range(len(cfg["hparams"])):
+    for b in range(len(hps)):
         if rst[b] != 0:
             assert status[b] == 1 and not np.isfinite(scores[b, 0])
             continue
-        noise = np.abs(rpf[b, :, 0] - rpf64[b, :, 0]).max() if np.all(np.isfinite(rpf64[b])) else np.inf
+        noise = max(np.abs(rpf[b, :, 0] - q[b, :, 0]).max() if np.all(np.isfinite(q[b])) else np.inf for q in probes)
         if noise >= ABS_SCORE:
             continue
         tol = ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
@@ -249,10 +270,54 @@ def test_final_cv_scores_match_oracle(bb, oracle, idx, kw):
                 assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (b, f)
         n_strict += noise < ABS_SCORE / 10
         n_wide += noise >= ABS_SCORE / 10
-    if dt == 0:
-        assert n_strict >= max(1, len(cfg["hparams"]) // 2)
-    else:
-        assert n_strict + n_wide >= 1
+    return n_strict, n_wide
+
+
+def test_full_size_many_studies_launch_sampled(bb, oracle):
+    """The many-studies workload at its full size (2,048 suggestions x 5 folds, 100 epochs), launched as
+    the benchmark launches it (caller-owned workspace, prepared hyper-parameter array); a sample of
+    the suggestions is recomputed by the oracle."""
+    cfg = inputs.make_config(3)
+    hps = cfg["hparams"]
+    X, y, ft = bb.to_device(cfg)
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    hp_arr = bb.make_hparams(hps)
+    ws = bb.alloc_workspace(bb.bbo_mlp_workspace_bytes(len(cfg["y"]), X.shape[1], c, K, hps, dt, hp_arr), X.device)
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, workspace=ws, hp_arr=hp_arr, want_per_fold=True)
+    torch.cuda.synchronize()
+    scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
+    assert scores.shape == (len(hps), 2)
+    pick = [0, 1, 255, 256, 777, 1024, 1500, 2047]
+    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick])
+    assert n_strict >= 3
+    # every suggestion either finished finite or flagged itself
+    assert np.all((status == 0) == np.isfinite(scores[:, 0]))
+
+
+def test_full_size_scale_up_launch(bb, oracle):
+    """The scale-up workload at its full size (1,640 suggestions x 5 folds, 20,000 rows, 50 epochs) in the
+    benchmark's launch configuration.  A 50-epoch bf16 run of one model costs the oracle minutes, so the
+    full launch is tied to what the oracle can check: (i) a suggestion's score does not depend on the
+    launch it is part of (bit-exact against the same suggestions launched alone), and (ii) the same
+    suggestions at the full row count for one epoch match the oracle."""
+    cfg = inputs.make_config(4)
+    hps = cfg["hparams"]
+    X, y, ft = bb.to_device(cfg)
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    hp_arr = bb.make_hparams(hps)
+    ws = bb.alloc_workspace(bb.bbo_mlp_workspace_bytes(len(cfg["y"]), X.shape[1], c, K, hps, dt, hp_arr), X.device)
+    scores, status = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, workspace=ws, hp_arr=hp_arr)
+    torch.cuda.synchronize()
+    assert np.all((status.cpu().numpy() == 0) == np.isfinite(scores.cpu().numpy()[:, 0]))
+    pick = [0, 819, 1639]
+    alone, st_alone = bb.bbo_mlp_cv_eval(X, y, c, ft, K, [hps[i] for i in pick], dt)
+    torch.cuda.synchronize()
+    assert torch.equal(alone, scores[pick]) and torch.equal(st_alone, status[pick])
+    one = [dict(hps[i], epochs=1) for i in pick[:2]]
+    s1, st1, pf1 = bb.bbo_mlp_cv_eval(X, y, c, ft, K, one, dt, want_per_fold=True)
+    torch.cuda.synchronize()
+    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, one, s1.cpu().numpy(), st1.cpu().numpy(), pf1.cpu().numpy())
+    assert n_strict + n_wide >= 1
 
 
 def test_batch_composition_invariance_and_determinism(bb):
