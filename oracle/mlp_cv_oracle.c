@@ -441,14 +441,16 @@ int oracle_opt_step(const oracle_hparams* hp, int64_t P, double* theta, const do
 /* ------------------------------------------------------------------ */
 
 /* Ascending lists of the rows that train (fold_idx not in {f, negative}) and
- * validate (fold_idx == f) for fold f.  Returns counts through n_tr / n_va.
- * Either output list may be NULL to only count. */
+ * validate (fold_idx == f) for fold f.  f < 0 is the hold-out split of the
+ * generalization score (Section 6.2, Figure 2(b)): every row that belongs to a
+ * fold trains, the rows outside all folds (fold_idx < 0) are scored.  Returns
+ * counts through n_tr / n_va.  Either output list may be NULL to only count. */
 void oracle_fold_lists(const int32_t* fold_idx, int64_t n, int32_t f, int32_t* train,
                        int32_t* val, int64_t* n_tr, int64_t* n_va) {
   int64_t a = 0, b = 0;
   for (int64_t i = 0; i < n; i++) {
-    if (fold_idx[i] < 0) continue;
-    if (fold_idx[i] == f) {
+    if (fold_idx[i] < 0 && f >= 0) continue;
+    if (f >= 0 ? fold_idx[i] == f : fold_idx[i] < 0) {
       if (val) val[b] = (int32_t)i;
       b++;
     } else {
@@ -631,5 +633,45 @@ int oracle_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32
   free(lists);
   free(cnt);
   free(pf);
+  return err;
+}
+
+/* The hold-out (generalization) score of Section 6.2: each suggestion is
+ * trained once on all rows that belong to a fold and scored on the rows that
+ * belong to none (fold_idx < 0).  The model is keyed as fold -1, so it shares
+ * no random stream with the cross-validation models of the same suggestion.
+ * scores[B][2] = {nll | mse, acc | 0}; status[b] = 1 when the first score is
+ * not finite. */
+int oracle_mlp_holdout_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
+                            const int32_t* fold_idx, const oracle_hparams* hp, int32_t B,
+                            int32_t dtype, int32_t prec, float* scores, int32_t* status,
+                            int32_t n_threads) {
+  if (n < 0 || d < 1 || B < 0 || n_classes == 1 || n_classes < 0) return -1;
+  for (int b = 0; b < B; b++) {
+    net_t net;
+    if (net_build(&net, d, n_classes, &hp[b])) return -1;
+  }
+  int64_t nn = n > 0 ? n : 1;
+  int32_t* lists = (int32_t*)malloc(sizeof(int32_t) * (size_t)nn * 2);
+  int64_t n_tr, n_va;
+  oracle_fold_lists(fold_idx, n, -1, lists, lists + nn, &n_tr, &n_va);
+  data_t D = {X, y, n, d, dtype};
+  int err = 0;
+  if (n_threads < 1) n_threads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+  for (int b = 0; b < B; b++) {
+    net_t net;
+    net_build(&net, d, n_classes, &hp[b]);
+    double sc[2];
+    int rc = train_and_score(&net, &D, &hp[b], -1, lists, n_tr, lists + nn, n_va, prec, sc, NULL, NULL);
+    scores[2 * b] = (float)sc[0];
+    scores[2 * b + 1] = (float)sc[1];
+    status[b] = isfinite(scores[2 * b]) ? 0 : 1;
+    if (rc) {
+#pragma omp atomic write
+      err = rc;
+    }
+  }
+  free(lists);
   return err;
 }

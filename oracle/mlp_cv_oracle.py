@@ -223,3 +223,23 @@ def cv_eval(X, y, n_classes, fold_idx, n_folds, hps, dtype=0, prec=0, n_threads=
     if rc != 0:
         raise ValueError("oracle_mlp_cv_eval: invalid argument (%d)" % rc)
     return scores[:B], status[:B], pf[:B]
+
+
+def holdout_eval(X, y, n_classes, fold_idx, hps, dtype=0, prec=0, n_threads=None):
+    """Hold-out (generalization) scores: train on the rows of all folds, score the rows of none.
+    scores[B,2] float32, status[B] int32."""
+    X, y = _xy(X, y, n_classes, dtype)
+    fold_idx = np.ascontiguousarray(fold_idx, dtype=np.int32)
+    B = len(hps)
+    h = make_hparams(hps)
+    scores = np.zeros((max(B, 1), 2), dtype=np.float32)
+    status = np.zeros(max(B, 1), dtype=np.int32)
+    if n_threads is None:
+        n_threads = len(os.sched_getaffinity(0))
+    d = X.shape[1] if X.ndim == 2 else 1
+    rc = lib().oracle_mlp_holdout_eval(_p(X), _p(y), C.c_int64(X.shape[0]), C.c_int32(d), C.c_int32(n_classes),
+                                       _p(fold_idx), h, C.c_int32(B), C.c_int32(dtype), C.c_int32(prec),
+                                       _p(scores), _p(status), C.c_int32(n_threads))
+    if rc != 0:
+        raise ValueError("oracle_mlp_holdout_eval: invalid argument (%d)" % rc)
+    return scores[:B], status[:B]

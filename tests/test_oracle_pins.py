@@ -99,12 +99,16 @@ def test_fold_lists_partition_rows(oracle):
         tr, va = oracle.fold_lists(fold, f)
         assert np.array_equal(va, np.nonzero(fold == f)[0])
         assert np.array_equal(tr, np.nonzero((fold >= 0) & (fold != f))[0])
+    # the hold-out split (f = -1): rows of every fold train, rows of none are scored
+    tr, va = oracle.fold_lists(fold, -1)
+    assert np.array_equal(tr, np.nonzero(fold >= 0)[0]) and np.array_equal(va, np.nonzero(fold < 0)[0])
 
 
 def test_minibatches_cover_train_rows_once_per_epoch(oracle):
     fold = inputs.make_folds(103, 5, 9)
     hp = {"hidden": [3], "batch_size": 16, "seed": 77, "epochs": 2}
-    for f in (0, 3):
+    fold[[5, 50, 77]] = -1
+    for f in (0, 3, -1):
         tr, _ = oracle.fold_lists(fold, f)
         for ep in (0, 1):
             steps = -(-len(tr) // 16)
@@ -289,8 +293,8 @@ def test_adam_first_step_closed_form(oracle):
     np.testing.assert_allclose(th[big], (theta - lr * np.sign(g))[big], atol=1e-6)
 
 
-@pytest.mark.parametrize("solver,nesterov", [("adam", False), ("sgd", False), ("sgd", True)])
-def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov):
+@pytest.mark.parametrize("solver,nesterov,f", [("adam", False, 2), ("sgd", False, 2), ("sgd", True, 2), ("adam", False, -1)])
+def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov, f):
     """A few epochs of minibatch training in fp64 mode equal the same loop
     written with library autograd + library optimizer, fed the oracle's own
     minibatch rows and initial weights.  (Adam: eps is set tiny, where the two
@@ -298,9 +302,10 @@ def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov)
     n_classes = 3 if solver == "adam" else 0
     X, y = tiny_problem(6, n=50, d=4, n_classes=n_classes)
     fold = inputs.make_folds(50, 5, 1)
+    if f < 0:  # hold-out model: 40 rows in folds, 10 in none
+        fold[fold == 4] = -1
     hp = {"hidden": [7], "solver": solver, "nesterov": nesterov, "lr": 0.02, "alpha": 0.05, "momentum": 0.8,
           "batch_size": 16, "epochs": 3, "eps": 1e-30, "seed": 11}
-    f = 2
     dims = [4, 7, n_classes if n_classes >= 2 else 1]
     res = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1, step_begin=0, step_end=9)
     tt = torch.tensor(oracle.init_params(4, n_classes, hp, f), dtype=torch.float64, requires_grad=True)
@@ -432,3 +437,36 @@ def test_divergent_run_sets_status_not_error(oracle):
     s, st, _ = oracle.cv_eval(X, y, 0, fold, 5, [bad, good])
     assert st[0] == 1 and not np.isfinite(s[0, 0])
     assert st[1] == 0 and np.isfinite(s[1, 0])
+
+
+def test_holdout_score_is_the_held_rows_loss_of_the_model_trained_on_all_folds(oracle):
+    """Generalization score (Section 6.2): one model per suggestion, trained on every row that
+    belongs to a fold, scored on the rows that belong to none; checked against the held rows'
+    loss / accuracy recomputed with the library from the final weights."""
+    for n_classes in (3, 0):
+        X, y = tiny_problem(21, n=90, d=5, n_classes=n_classes)
+        fold = inputs.make_folds(90, 4, 5)
+        fold[::4] = -1
+        hps = [{"hidden": [6], "lr": 0.01, "alpha": 0.01, "batch_size": 20, "epochs": 4, "seed": 5},
+               {"hidden": [4, 3], "solver": "sgd", "lr": 0.02, "momentum": 0.5, "batch_size": 0, "epochs": 6, "seed": 6}]
+        s, st = oracle.holdout_eval(X, y, n_classes, fold, hps, prec=1)
+        assert np.all(st == 0)
+        held = np.nonzero(fold < 0)[0]
+        for b, hp in enumerate(hps):
+            one = oracle.train_one(X, y, n_classes, fold, hp, -1, prec=1)
+            assert np.allclose(one["scores"], s[b], rtol=1e-6)
+            dims = [5] + hp["hidden"] + [n_classes if n_classes >= 2 else 1]
+            tt = torch.tensor(one["theta"], dtype=torch.float64)
+            Xh = torch.tensor(X[held], dtype=torch.float64)
+            if n_classes >= 2:
+                yh = torch.tensor(y[held].astype(np.int64))
+                loss = torch_loss(tt, dims, Xh, yh, n_classes, 0.0).item()
+            else:
+                yh = torch.tensor(y[held], dtype=torch.float64)
+                loss = 2.0 * torch_loss(tt, dims, Xh, yh, n_classes, 0.0).item()  # reported mse has no 1/2
+            assert abs(loss - s[b, 0]) < 1e-6 * max(1.0, abs(loss))
+        # the hold-out model shares no stream with the cross-validation models of the suggestion
+        assert not np.array_equal(oracle.init_params(5, n_classes, hps[0], -1), oracle.init_params(5, n_classes, hps[0], 0))
+    # no held rows: non-finite score, status 1
+    s, st = oracle.holdout_eval(X, y, 0, np.zeros(90, dtype=np.int32), hps[:1])
+    assert st[0] == 1 and not np.isfinite(s[0, 0])
