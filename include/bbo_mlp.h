@@ -129,6 +129,25 @@ int bbo_mlp_cv_eval_traced(const void* X, const void* y, int64_t n, int32_t d,
                            float* trace_out, size_t trace_floats, const float* state_in);
 
 /*
+ * The hold-out (generalization) score (Section 6.2, Figure 2(b): the score of
+ * the held-out test data, which the optimizers never see).  Each suggestion is
+ * trained once on every row that belongs to a fold (fold_idx >= 0) and scored
+ * on the rows that belong to none (fold_idx < 0), with the same training and
+ * scoring arithmetic as bbo_mlp_cv_eval.  The model is keyed as fold -1: its
+ * initial weights and minibatch order are independent of the suggestion's
+ * cross-validation models.
+ *   X, y, fold_idx, hp, dtype, status, workspace, stream: as for bbo_mlp_cv_eval
+ *   scores     device, float32 [B][2] = {nll | mse, accuracy | 0} on the held
+ *              rows; NaN (status 1) when no row is held out
+ *   workspace  at least bbo_mlp_workspace_bytes(..., n_folds = 1, ...) bytes
+ * Returns BBO_OK after enqueueing, or an error code as bbo_mlp_cv_eval does.
+ */
+int bbo_mlp_holdout_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
+                         const int32_t* fold_idx, const bbo_mlp_hparams* hp, int32_t B,
+                         int32_t dtype, float* scores, int32_t* status, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * The cross-validation split as the kernels see it (Section 2: k-fold
  * cross-validation score).  For each fold f the ascending list of training
  * rows (fold_idx not in {f, negative}) and of held rows (fold_idx == f).
@@ -140,8 +159,18 @@ int bbo_mlp_fold_lists(const int32_t* fold_idx, int64_t n, int32_t n_folds, int3
                        int32_t* val_idx, int32_t* counts, void* stream);
 
 /*
+ * The hold-out split as the kernels see it (Section 6.2): the ascending list
+ * of the rows of all folds (fold_idx >= 0, training) and of the rows of none
+ * (fold_idx < 0, scored).
+ *   train_idx, val_idx  device, int32 [n]; counts device, int32 [2]
+ */
+int bbo_mlp_holdout_lists(const int32_t* fold_idx, int64_t n, int32_t* train_idx, int32_t* val_idx,
+                          int32_t* counts, void* stream);
+
+/*
  * The rows of minibatch `step` of `epoch` for suggestion hp[0] in fold `fold`,
- * from train_idx / counts as written by bbo_mlp_fold_lists.
+ * from train_idx / counts as written by bbo_mlp_fold_lists; fold = -1 is the
+ * hold-out model, with train_idx / counts from bbo_mlp_holdout_lists.
  *   rows_out  device, int32 [batch rows]; n_rows_out device int32 [1]
  */
 int bbo_mlp_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int64_t n,
@@ -149,8 +178,9 @@ int bbo_mlp_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int6
                            int32_t* rows_out, int32_t* n_rows_out, void* stream);
 
 /*
- * Initial parameters of suggestion hp[0] in fold `fold` (Glorot-uniform from
- * the counter-based generator), packed per layer as W[in][out] then b[out].
+ * Initial parameters of suggestion hp[0] in fold `fold` (-1: the hold-out
+ * model), Glorot-uniform from the counter-based generator, packed per layer as
+ * W[in][out] then b[out].
  *   theta_out  device, float32 [P]
  */
 int bbo_mlp_init_params(int32_t d, int32_t n_classes, const bbo_mlp_hparams* hp, int32_t fold,

@@ -19,7 +19,7 @@ ADAM, SGD = 0, 1
 F32, BF16 = 0, 1
 
 EXPORTS = ["bbo_mlp_workspace_bytes", "bbo_mlp_cv_eval", "bbo_mlp_cv_eval_traced", "bbo_mlp_fold_lists",
-           "bbo_mlp_minibatch_rows", "bbo_mlp_init_params", "bbo_mlp_param_count", "bbo_mlp_last_error"]
+           "bbo_mlp_holdout_eval", "bbo_mlp_holdout_lists", "bbo_mlp_minibatch_rows", "bbo_mlp_init_params", "bbo_mlp_param_count", "bbo_mlp_last_error"]
 
 
 class HParams(C.Structure):
@@ -165,6 +165,34 @@ def bbo_mlp_cv_eval(X, y, n_classes, fold_idx, n_folds, hps, dtype=F32, workspac
     if trace is not None:
         out.append({"loss": tr[:T, 0], "grad": tr[:T, 1:1 + P], "theta_after": tr[:T, 1 + P:]})
     return tuple(out)
+
+
+def bbo_mlp_holdout_eval(X, y, n_classes, fold_idx, hps, dtype=F32, workspace=None, stream=None, hp_arr=None):
+    """Hold-out scores of a list of suggestions: trained on the rows with fold_idx >= 0, scored on the
+    rows with fold_idx < 0.  Returns (scores[B,2], status[B]) device tensors."""
+    dev = X.device
+    n, d = (int(X.shape[0]), int(X.shape[1]))
+    B = len(hps)
+    h = hp_arr if hp_arr is not None else make_hparams(hps)
+    if workspace is None:
+        workspace = alloc_workspace(bbo_mlp_workspace_bytes(n, d, n_classes, 1, hps, dtype, h), dev)
+    scores = torch.empty((max(B, 1), 2), dtype=torch.float32, device=dev)
+    status = torch.empty(max(B, 1), dtype=torch.int32, device=dev)
+    _check(lib().bbo_mlp_holdout_eval(_ptr(X), _ptr(y), C.c_int64(n), C.c_int32(d), C.c_int32(n_classes),
+                                      _ptr(fold_idx), h, C.c_int32(B), C.c_int32(dtype), _ptr(scores), _ptr(status),
+                                      _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return scores[:B], status[:B]
+
+
+def bbo_mlp_holdout_lists(fold_idx, stream=None):
+    """-> (train_idx[n], val_idx[n], counts[2]) int32 device tensors."""
+    n = int(fold_idx.shape[0])
+    dev = fold_idx.device
+    tr = torch.full((max(n, 1),), -1, dtype=torch.int32, device=dev)
+    va = torch.full((max(n, 1),), -1, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(2, dtype=torch.int32, device=dev)
+    _check(lib().bbo_mlp_holdout_lists(_ptr(fold_idx), C.c_int64(n), _ptr(tr), _ptr(va), _ptr(cnt), _stream(stream)))
+    return tr, va, cnt
 
 
 def bbo_mlp_fold_lists(fold_idx, n_folds, stream=None):

@@ -160,22 +160,25 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
 }
 
 // ---------------------------------------------------------------------------
-// Fold lists (ascending), one workgroup per fold; also resets the work queue.
+// Fold lists (ascending), one workgroup per list; also resets the work queue.
+// List k is fold fold_base + k.  Fold -1 is the hold-out split: rows of every
+// fold train, rows of none are scored.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(NTHREADS) void k_fold_lists(const int32_t* __restrict__ fold_idx, int64_t n,
                                                          int32_t* __restrict__ train_idx,
                                                          int32_t* __restrict__ val_idx,
-                                                         int32_t* __restrict__ counts, int32_t* queue) {
+                                                         int32_t* __restrict__ counts, int32_t* queue,
+                                                         int fold_base) {
   __shared__ int wtr[NTHREADS / 64], wva[NTHREADS / 64];
   __shared__ int base_tr, base_va;
-  const int f = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int f = blockIdx.x, fold = (int)blockIdx.x + fold_base, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (f == 0 && tid == 0 && queue) *queue = 0;
   if (tid == 0) base_tr = base_va = 0;
   __syncthreads();
   for (int64_t c0 = 0; c0 < n; c0 += NTHREADS) {
     const int64_t i = c0 + tid;
     const int fi = i < n ? fold_idx[i] : -1;
-    const bool tr = fi >= 0 && fi != f, va = fi == f;
+    const bool tr = fi >= 0 && fi != fold, va = i < n && (fold >= 0 ? fi == fold : fi < 0);
     const uint64_t btr = __ballot(tr), bva = __ballot(va);
     const uint64_t below = ((uint64_t)1 << lane) - 1;
     if (lane == 0) {
@@ -467,14 +470,14 @@ struct Trainer {
   }
 
   __device__ void run() const {
-    const int f = it.fold;
-    const int n_tr = P.counts[2 * f], n_va = P.counts[2 * f + 1];
-    const int32_t* tr = P.train_idx + (int64_t)f * P.n;
-    const int32_t* va = P.val_idx + (int64_t)f * P.n;
+    const int f = it.fold, fl = it.fold - P.fold_base;  // fl: which row list
+    const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
+    const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
+    const int32_t* va = P.val_idx + (int64_t)fl * P.n;
     const int bs = eff_batch(it.batch_size, n_tr);
     const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f);
-    const bool traced = P.trace_item == it.b * P.n_folds + f;
+    const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     // zero the slot, then initial parameters
     {
@@ -545,7 +548,7 @@ struct Trainer {
     lsum = block_sum(lsum, red);
     hits = block_sum(hits, red);
     if (threadIdx.x == 0) {
-      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + f);
+      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
       out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
       out[1] = P.n_classes >= 2 ? (n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("")) : 0.f;
     }
@@ -600,13 +603,14 @@ __global__ void k_reduce(const float* __restrict__ item_out, int B, int K, float
 __global__ void k_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int64_t n, uint64_t seed,
                                  int fold, int epoch, int64_t step, int batch_size, int32_t* rows_out,
                                  int32_t* n_rows_out) {
-  const int n_tr = counts[2 * fold];
+  const int fl = fold < 0 ? 0 : fold;  // the hold-out lists are a set of their own, with one entry
+  const int n_tr = counts[2 * fl];
   const int bs = eff_batch(batch_size, n_tr);
   const int64_t lo = step * bs;
   const int mb = (int)max((int64_t)0, min((int64_t)bs, (int64_t)n_tr - lo));
   const uint64_t ke = key_epoch(key_model(seed, fold), epoch);
   for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < mb; p += gridDim.x * blockDim.x)
-    rows_out[p] = train_idx[(int64_t)fold * n + perm_index(ke, (uint32_t)n_tr, (uint32_t)(lo + p))];
+    rows_out[p] = train_idx[(int64_t)fl * n + perm_index(ke, (uint32_t)n_tr, (uint32_t)(lo + p))];
   if (blockIdx.x == 0 && threadIdx.x == 0) *n_rows_out = mb;
 }
 
@@ -731,7 +735,7 @@ bool force_generic() {
   return e && e[0] == '1';
 }
 
-int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_mlp_hparams* hp, int B,
+int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_base, const bbo_mlp_hparams* hp, int B,
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
   bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic();
@@ -743,7 +747,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
   pl.items.reserve((size_t)B * n_folds);
   std::vector<double> cost;
   cost.reserve((size_t)B * n_folds);
-  const double n_tr_est = n_folds > 1 ? (double)n * (n_folds - 1) / n_folds : (double)n;
+  const double n_tr_est = n_folds > 1 && fold_base >= 0 ? (double)n * (n_folds - 1) / n_folds : (double)n;
   uint64_t slot = 0;
   for (int b = 0; b < B; b++) {
     const bbo_mlp_hparams& h = hp[b];
@@ -794,7 +798,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, const bbo_
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
-      it.fold = f;
+      it.fold = f + fold_base;
       pl.items.push_back(it);
       cost.push_back(c);
     }
@@ -879,7 +883,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
              int32_t n_folds, const bbo_mlp_hparams* hp, int32_t B, int32_t dtype, float* scores,
              int32_t* status, float* per_fold, void* workspace, size_t workspace_bytes, void* stream,
              int32_t trace_b, int32_t trace_fold, int64_t step_begin, int64_t step_end, float* trace_out,
-             size_t trace_floats, const float* state_in, bool traced) {
+             size_t trace_floats, const float* state_in, bool traced, int fold_base = 0) {
   g_err.clear();
   int rc = check_problem(n, d, n_classes, n_folds, dtype);
   if (rc) return rc;
@@ -899,7 +903,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
       return fail(BBO_INVALID_ARG, "trace buffer too small");
   }
   Plan pl;
-  rc = make_plan(pl, n, d, n_classes, n_folds, hp, B, dtype);
+  rc = make_plan(pl, n, d, n_classes, n_folds, fold_base, hp, B, dtype);
   if (rc) return rc;
   if (workspace_bytes < pl.total) return fail(BBO_WORKSPACE_TOO_SMALL, "workspace too small");
   hipStream_t s = (hipStream_t)stream;
@@ -939,6 +943,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   P.d = d;
   P.n_classes = n_classes;
   P.n_folds = n_folds;
+  P.fold_base = fold_base;
   P.n_items = (int)pl.items.size();
   P.trace_item = traced ? trace_b * n_folds + trace_fold : -1;
   P.step_begin = step_begin;
@@ -947,7 +952,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   P.state_in = traced ? state_in : nullptr;
 
   hipLaunchKernelGGL(k_fold_lists, dim3(n_folds), dim3(NTHREADS), 0, s, fold_idx, n, (int32_t*)(ws + pl.o_train),
-                     (int32_t*)(ws + pl.o_val), (int32_t*)(ws + pl.o_counts), P.queue);
+                     (int32_t*)(ws + pl.o_val), (int32_t*)(ws + pl.o_counts), P.queue, fold_base);
   HIP_TRY(hipGetLastError());
   if (pl.tiled) {
     HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -988,7 +993,7 @@ int bbo_mlp_workspace_bytes(int64_t n, int32_t d, int32_t n_classes, int32_t n_f
   rc = check_hparams(hp, B);
   if (rc) return rc;
   Plan pl;
-  rc = make_plan(pl, n, d, n_classes, n_folds, hp, B, dtype);
+  rc = make_plan(pl, n, d, n_classes, n_folds, 0, hp, B, dtype);
   if (rc) return rc;
   *out = (size_t)pl.total;
   return BBO_OK;
@@ -1019,7 +1024,25 @@ int bbo_mlp_fold_lists(const int32_t* fold_idx, int64_t n, int32_t n_folds, int3
   if (n < 0 || n > 0x3fffffff || n_folds < 1 || n_folds > 1024) return fail(BBO_INVALID_ARG, "bad n or n_folds");
   if (!counts || (n > 0 && (!fold_idx || !train_idx || !val_idx))) return fail(BBO_INVALID_ARG, "null pointer");
   hipLaunchKernelGGL(k_fold_lists, dim3(n_folds), dim3(NTHREADS), 0, (hipStream_t)stream, fold_idx, n, train_idx,
-                     val_idx, counts, (int32_t*)nullptr);
+                     val_idx, counts, (int32_t*)nullptr, 0);
+  HIP_TRY(hipGetLastError());
+  return BBO_OK;
+}
+
+int bbo_mlp_holdout_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
+                         const int32_t* fold_idx, const bbo_mlp_hparams* hp, int32_t B, int32_t dtype,
+                         float* scores, int32_t* status, void* workspace, size_t workspace_bytes, void* stream) {
+  return run_eval(X, y, n, d, n_classes, fold_idx, 1, hp, B, dtype, scores, status, nullptr, workspace,
+                  workspace_bytes, stream, 0, 0, 0, 0, nullptr, 0, nullptr, false, -1);
+}
+
+int bbo_mlp_holdout_lists(const int32_t* fold_idx, int64_t n, int32_t* train_idx, int32_t* val_idx, int32_t* counts,
+                          void* stream) {
+  g_err.clear();
+  if (n < 0 || n > 0x3fffffff) return fail(BBO_INVALID_ARG, "bad n");
+  if (!counts || (n > 0 && (!fold_idx || !train_idx || !val_idx))) return fail(BBO_INVALID_ARG, "null pointer");
+  hipLaunchKernelGGL(k_fold_lists, dim3(1), dim3(NTHREADS), 0, (hipStream_t)stream, fold_idx, n, train_idx, val_idx,
+                     counts, (int32_t*)nullptr, -1);
   HIP_TRY(hipGetLastError());
   return BBO_OK;
 }
@@ -1028,7 +1051,7 @@ int bbo_mlp_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int6
                            int32_t fold, int32_t epoch, int64_t step, int32_t* rows_out, int32_t* n_rows_out,
                            void* stream) {
   g_err.clear();
-  if (!train_idx || !counts || !hp || !rows_out || !n_rows_out || n < 0 || fold < 0 || epoch < 0 || step < 0)
+  if (!train_idx || !counts || !hp || !rows_out || !n_rows_out || n < 0 || fold < -1 || epoch < 0 || step < 0)
     return fail(BBO_INVALID_ARG, "bad argument");
   hipLaunchKernelGGL(k_minibatch_rows, dim3(64), dim3(256), 0, (hipStream_t)stream, train_idx, counts, n, hp->seed,
                      fold, epoch, step, hp->batch_size, rows_out, n_rows_out);
@@ -1043,7 +1066,7 @@ int bbo_mlp_init_params(int32_t d, int32_t n_classes, const bbo_mlp_hparams* hp,
   if (rc) return rc;
   rc = check_hparams(hp, 1);
   if (rc) return rc;
-  if (!theta_out || fold < 0) return fail(BBO_INVALID_ARG, "bad argument");
+  if (!theta_out || fold < -1) return fail(BBO_INVALID_ARG, "bad argument");
   InitArgs a;
   memset(&a, 0, sizeof(a));
   a.seed = hp->seed;

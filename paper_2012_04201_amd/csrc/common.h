@@ -143,6 +143,7 @@ struct TrainParams {
   uint64_t slot_bytes;
   int64_t n;
   int32_t d, n_classes, n_folds, n_items;
+  int32_t fold_base;  // fold of list 0: 0 for cross-validation, -1 for the hold-out split
   // trace
   int32_t trace_item;  // b*K+fold or -1
   int64_t step_begin, step_end;

@@ -525,14 +525,14 @@ struct Small {
   }
 
   __device__ __forceinline__ void run() const {
-    const int f_ = it.fold;
-    const int n_tr = P.counts[2 * f_], n_va = P.counts[2 * f_ + 1];
-    const int32_t* tr = P.train_idx + (int64_t)f_ * P.n;
-    const int32_t* va = P.val_idx + (int64_t)f_ * P.n;
+    const int f_ = it.fold, fl = it.fold - P.fold_base;  // fl: which row list
+    const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
+    const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
+    const int32_t* va = P.val_idx + (int64_t)fl * P.n;
     const int bs = eff_batch(it.batch_size, n_tr);
     const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f_);
-    const bool traced = P.trace_item == it.b * P.n_folds + f_;
+    const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     // zero the weights and output-layer moments (pads must be zero), then the initial or given parameters
     {
@@ -683,7 +683,7 @@ struct Small {
     lsum = block_sum(lsum, red);
     hits = block_sum(hits, red);
     if (threadIdx.x == 0) {
-      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + f_);
+      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
       out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
       out[1] = P.n_classes >= 2 ? (n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("")) : 0.f;
     }

@@ -320,6 +320,83 @@ def test_full_size_scale_up_launch(bb, oracle):
     assert n_strict + n_wide >= 1
 
 
+# ------------------------------------------------------- hold-out score ----
+
+def with_holdout(cfg, every=5):
+    """The configuration with every `every`-th row taken out of all folds (the hold-out test rows)."""
+    cfg = dict(cfg)
+    fold = cfg["fold_idx"].copy()
+    fold[::every] = -1
+    cfg["fold_idx"] = fold
+    return cfg
+
+
+def test_holdout_lists_rows_and_init_bit_exact(bb, oracle):
+    rng = np.random.default_rng(5)
+    fold = rng.integers(-1, 5, size=1797).astype(np.int32)
+    ft = torch.from_numpy(fold).cuda()
+    tr, va, cnt = bb.bbo_mlp_holdout_lists(ft)
+    torch.cuda.synchronize()
+    rtr, rva = oracle.fold_lists(fold, -1)
+    cnt = cnt.cpu().numpy()
+    assert cnt[0] == len(rtr) and cnt[1] == len(rva)
+    assert np.array_equal(tr.cpu().numpy()[: cnt[0]], rtr) and np.array_equal(va.cpu().numpy()[: cnt[1]], rva)
+    hp = {"hidden": [20], "batch_size": 100, "seed": 99, "epochs": 2}
+    for ep, st in [(0, 0), (1, 3), (1, len(rtr) // 100)]:
+        rows = bb.bbo_mlp_minibatch_rows(tr, cnt_dev(cnt), len(fold), hp, -1, ep, st)
+        assert np.array_equal(rows.cpu().numpy(), oracle.minibatch_rows(fold, hp, -1, ep, st))
+    th = bb.bbo_mlp_init_params(64, 10, hp, -1).cpu().numpy()
+    assert np.array_equal(th.view(np.uint32), oracle.init_params(64, 10, hp, -1).astype(np.float32).view(np.uint32))
+
+
+def cnt_dev(cnt):
+    return torch.from_numpy(np.ascontiguousarray(cnt, dtype=np.int32)).cuda()
+
+
+@pytest.mark.parametrize("idx,kw", [
+    (0, {}),                                  # small fp32 kernel, full batch
+    (1, {"B": 4, "epochs": 12}),              # generic fp32 kernel
+    (2, {"B": 8, "epochs": 40}),              # regression / SGD-Nesterov
+    (3, {"B": 24, "epochs": 20}),             # many-studies shape
+    (4, {"B": 2, "epochs": 2, "n": 3000}),    # tiled bf16 kernel
+])
+def test_holdout_scores_match_oracle(bb, oracle, idx, kw):
+    cfg = with_holdout(inputs.make_config(idx, **kw))
+    X, y, ft = bb.to_device(cfg)
+    c, dt, hps = cfg["n_classes"], cfg["dtype"], cfg["hparams"]
+    scores, status = bb.bbo_mlp_holdout_eval(X, y, c, ft, hps, dt)
+    torch.cuda.synchronize()
+    scores, status = scores.cpu().numpy(), status.cpu().numpy()
+    run = lambda h, **k: oracle.holdout_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], h, dtype=dt, **k)
+    rs, rst = run(hps)
+    probes = [run(hps, prec=1)[0]]
+    for toward in (np.float32(1e9), np.float32(0)):
+        probes.append(run([dict(h, lr=float(np.nextafter(np.float32(h.get("lr", 1e-3)), toward))) for h in hps])[0])
+    n_va = int((cfg["fold_idx"] < 0).sum())
+    held = 0
+    for b in range(len(hps)):
+        if rst[b] != 0:
+            assert status[b] == 1 and not np.isfinite(scores[b, 0])
+            continue
+        noise = max(abs(rs[b, 0] - q[b, 0]) if np.isfinite(q[b, 0]) else np.inf for q in probes)
+        if noise >= ABS_SCORE:
+            continue
+        tol = ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
+        assert status[b] == 0 and abs(scores[b, 0] - rs[b, 0]) < tol, (b, scores[b], rs[b], noise)
+        if c >= 2 and noise < ABS_SCORE / 10:
+            assert explained_flips(scores[b, 1], rs[b, 1], n_va), (b, scores[b], rs[b])
+        held += 1
+    assert held >= 1
+
+
+def test_holdout_without_held_rows_flags_itself(bb):
+    cfg = inputs.make_config(0)
+    X, y, ft = bb.to_device(cfg)
+    s, st = bb.bbo_mlp_holdout_eval(X, y, 3, ft, cfg["hparams"][:2], 0)
+    torch.cuda.synchronize()
+    assert st.cpu().tolist() == [1, 1] and not np.isfinite(s.cpu().numpy()[:, 0]).any()
+
+
 def test_batch_composition_invariance_and_determinism(bb):
     cfg = inputs.make_config(3, B=16, epochs=5)
     X, y, ft = bb.to_device(cfg)
