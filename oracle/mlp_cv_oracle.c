@@ -532,7 +532,7 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
   }
 
   out[0] = NAN;
-  out[1] = net->n_classes >= 2 ? NAN : 0.0;
+  out[1] = NAN;
   if (n_va > 0 && !done) {
     forward(net, D, va, n_va, theta, &s, prec);
     out[0] = data_loss(net, D, va, n_va, &s, prec, 0, 0);
@@ -547,6 +547,12 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
         hit += best == ((const int32_t*)D->y)[va[r]];
       }
       out[1] = rnd((double)hit / (double)n_va, prec);
+    } else {
+      /* mean absolute error, the other regression metric of Section 2 */
+      double sa = 0.0;
+      for (int64_t r = 0; r < n_va; r++)
+        sa += fabs(s.a[net->L][r] - (double)((const float*)D->y)[va[r]]);
+      out[1] = rnd(sa / (double)n_va, prec);
     }
   }
   if (theta_out) memcpy(theta_out, theta, sizeof(double) * (size_t)P);
@@ -583,7 +589,7 @@ int oracle_train_one(const void* X, const void* y, int64_t n, int32_t d, int32_t
 }
 
 /* The evaluation call: B suggestions x n_folds folds.  scores[B][2] =
- * {mean nll | mse, mean acc | 0}; status[b] = 1 when the first score is not
+ * {mean nll | mse, mean acc | mae}; status[b] = 1 when the first score is not
  * finite; per_fold (optional) [B][n_folds][2].  Models run one per OpenMP
  * thread. */
 int oracle_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
@@ -640,7 +646,7 @@ int oracle_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32
  * trained once on all rows that belong to a fold and scored on the rows that
  * belong to none (fold_idx < 0).  The model is keyed as fold -1, so it shares
  * no random stream with the cross-validation models of the same suggestion.
- * scores[B][2] = {nll | mse, acc | 0}; status[b] = 1 when the first score is
+ * scores[B][2] = {nll | mse, acc | mae}; status[b] = 1 when the first score is
  * not finite. */
 int oracle_mlp_holdout_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
                             const int32_t* fold_idx, const oracle_hparams* hp, int32_t B,

@@ -464,6 +464,13 @@ def test_holdout_score_is_the_held_rows_loss_of_the_model_trained_on_all_folds(o
             else:
                 yh = torch.tensor(y[held], dtype=torch.float64)
                 loss = 2.0 * torch_loss(tt, dims, Xh, yh, n_classes, 0.0).item()  # reported mse has no 1/2
+                # the second regression metric (Section 2 lists mse and mae): mean |prediction - target|
+                a = Xh
+                for l, (W, bb_) in enumerate(unpack(tt, dims)):
+                    a = a @ W + bb_
+                    if l + 2 < len(dims):
+                        a = torch.relu(a)
+                assert abs((a[:, 0] - yh).abs().mean().item() - s[b, 1]) < 1e-6
             assert abs(loss - s[b, 0]) < 1e-6 * max(1.0, abs(loss))
         # the hold-out model shares no stream with the cross-validation models of the suggestion
         assert not np.array_equal(oracle.init_params(5, n_classes, hps[0], -1), oracle.init_params(5, n_classes, hps[0], 0))
