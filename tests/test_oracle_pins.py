@@ -357,7 +357,7 @@ def test_linear_mse_converges_to_least_squares_and_ridge(oracle):
         # the reported score is the plain mean squared error on the held rows
         pred = X[:12].astype(np.float64) @ w + b
         assert abs(res["scores"][0] - np.mean((pred - y[:12]) ** 2)) < 1e-12
-        assert res["scores"][1] == 0.0
+        assert abs(res["scores"][1] - np.mean(np.abs(pred - y[:12]))) < 1e-12  # and the mean absolute error
 
 
 def test_full_batch_gradient_descent_loss_is_monotone(oracle):
