@@ -79,7 +79,7 @@ int bbo_mlp_workspace_bytes(int64_t n, int32_t d, int32_t n_classes, int32_t n_f
  *             in every other fold; a negative value leaves the row unused
  *   hp        host, [B] suggestions
  *   scores    device, float32 [B][2]: {mean over folds of nll | mse,
- *             mean over folds of accuracy | 0}
+ *             mean over folds of accuracy | mean absolute error}
  *   status    device, int32 [B]: 0 ok, 1 the first score is not finite
  *   per_fold  device, float32 [B][n_folds][2], or NULL
  *   workspace device, >= bbo_mlp_workspace_bytes() bytes, 256-byte aligned;
@@ -137,7 +137,7 @@ int bbo_mlp_cv_eval_traced(const void* X, const void* y, int64_t n, int32_t d,
  * initial weights and minibatch order are independent of the suggestion's
  * cross-validation models.
  *   X, y, fold_idx, hp, dtype, status, workspace, stream: as for bbo_mlp_cv_eval
- *   scores     device, float32 [B][2] = {nll | mse, accuracy | 0} on the held
+ *   scores     device, float32 [B][2] = {nll | mse, accuracy | mae} on the held
  *              rows; NaN (status 1) when no row is held out
  *   workspace  at least bbo_mlp_workspace_bytes(..., n_folds = 1, ...) bytes
  * Returns BBO_OK after enqueueing, or an error code as bbo_mlp_cv_eval does.

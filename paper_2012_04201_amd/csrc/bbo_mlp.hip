@@ -134,7 +134,7 @@ __device__ inline void wg_gemm(const OpT* A, int lda, const OpT* B, int ldb, int
 // the output delta (p - onehot)/m or (z - y)/m.
 template <bool WANT_DELTA>
 __device__ inline float row_loss(const float* z, int c, int n_classes, const void* yv, int row, float inv_den,
-                                 float* delta, int* hit) {
+                                 float* delta, float* aux) {
   if (n_classes >= 2) {
     const int yr = ((const int32_t*)yv)[row];
     float mx = z[0];
@@ -149,12 +149,12 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
     const float lse = mx + logf(se);
     if (WANT_DELTA)
       for (int j = 0; j < c; j++) delta[j] = (expf(z[j] - lse) - (j == yr ? 1.f : 0.f)) * inv_den;
-    *hit = best == yr;
+    *aux = best == yr ? 1.f : 0.f;  // a correct prediction
     return lse - z[yr];
   } else {
     const float e = z[0] - ((const float*)yv)[row];
     if (WANT_DELTA) delta[0] = e * inv_den;
-    *hit = 0;
+    *aux = fabsf(e);  // the absolute error
     return e * e;
   }
 }
@@ -539,9 +539,9 @@ struct Trainer {
       const float* Z = fp(y.Z);
       const int32_t* rl = rowlist();
       for (int r = threadIdx.x; r < mb; r += blockDim.x) {
-        int hit;
-        lsum += (double)row_loss<false>(Z + r * zc, c, P.n_classes, P.y, rl[r], 0.f, nullptr, &hit);
-        hits += hit;
+        float aux;
+        lsum += (double)row_loss<false>(Z + r * zc, c, P.n_classes, P.y, rl[r], 0.f, nullptr, &aux);
+        hits += (double)aux;
       }
       __syncthreads();
     }
@@ -550,7 +550,7 @@ struct Trainer {
     if (threadIdx.x == 0) {
       float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
       out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
-      out[1] = P.n_classes >= 2 ? (n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("")) : 0.f;
+      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
     }
   }
 };

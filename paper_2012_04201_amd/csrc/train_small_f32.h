@@ -307,7 +307,7 @@ struct Small {
     f32x4 dl = f32x4{0.f, 0.f, 0.f, 0.f};
     if (lane < rows) {
       double l = 0.0;
-      int hit = 0;
+      double hit = 0.0;  // a correct prediction, or the absolute error
       if (P.n_classes >= 2) {
         const int yr = __float_as_int(yv);
         float mx = z[0], zy = z[0];
@@ -327,7 +327,7 @@ struct Small {
           if (cc < c) se += expf(z[cc] - mx);
         const float lse = mx + logf(se);
         l = (double)(lse - zy);
-        hit = best == yr;
+        hit = best == yr ? 1.0 : 0.0;
         if (TRAIN) {
 #pragma unroll
           for (int cc = 0; cc < 4; cc++)
@@ -336,6 +336,7 @@ struct Small {
       } else {
         const float e0 = z[0] - yv;
         l = TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+        hit = (double)fabsf(e0);
         if (TRAIN) dl[0] = e0 * inv_mb;
       }
       if (w == 0) {  // every wave computes the same values; one of them keeps the statistics
@@ -685,7 +686,7 @@ struct Small {
     if (threadIdx.x == 0) {
       float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
       out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
-      out[1] = P.n_classes >= 2 ? (n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("")) : 0.f;
+      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
     }
   }
 };

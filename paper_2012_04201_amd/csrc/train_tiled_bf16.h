@@ -494,7 +494,10 @@ struct Tiled {
           }
         } else {
           const float e0 = valid ? z[0] - ((const float*)P.y)[row] : 0.f;
-          if (valid && q == 0) lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+          if (valid && q == 0) {
+            lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+            hits += (double)fabsf(e0);  // the absolute error
+          }
           if (TRAIN && q == 0) delta[0] = e0 * inv_mb;
         }
         if (TRAIN) {
@@ -834,7 +837,7 @@ struct Tiled {
     if (threadIdx.x == 0) {
       float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
       out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
-      out[1] = P.n_classes >= 2 ? (n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("")) : 0.f;
+      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
     }
   }
 };

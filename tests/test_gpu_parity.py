@@ -268,6 +268,8 @@ def check_scores_against_oracle(oracle, cfg, hps, scores, status, pf):
         if c >= 2 and noise < ABS_SCORE / 10:
             for f in range(K):
                 assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (b, f)
+        if c == 0:  # regression: the second score is the mean absolute error
+            assert abs(scores[b, 1] - rs[b, 1]) < tol and np.abs(pf[b, :, 1] - rpf[b, :, 1]).max() < 2 * tol, (b, scores[b], rs[b])
         n_strict += noise < ABS_SCORE / 10
         n_wide += noise >= ABS_SCORE / 10
     return n_strict, n_wide
@@ -385,6 +387,8 @@ def test_holdout_scores_match_oracle(bb, oracle, idx, kw):
         assert status[b] == 0 and abs(scores[b, 0] - rs[b, 0]) < tol, (b, scores[b], rs[b], noise)
         if c >= 2 and noise < ABS_SCORE / 10:
             assert explained_flips(scores[b, 1], rs[b, 1], n_va), (b, scores[b], rs[b])
+        if c == 0:
+            assert abs(scores[b, 1] - rs[b, 1]) < tol, (b, scores[b], rs[b])
         held += 1
     assert held >= 1
 
