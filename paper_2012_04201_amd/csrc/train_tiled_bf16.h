@@ -29,7 +29,7 @@
 //   refreshed.
 //
 // Every global array is stored in the order its wave-level accesses touch it:
-// fp32 state as 16 x 16 tiles [out tile][in tile][lane][4] (1 KB per access),
+// fp32 state as 16 x 16 tiles [in tile][out tile][lane][4] (1 KB per access),
 // operand copies as 16 x 16 bf16 tiles (512 B per store, 1 KB per load), spills
 // as [unit tile][32-row block][unit][row].  Batches above 256 rows are processed
 // in chunks whose partial gradients pass through an fp32 scratch.
@@ -51,6 +51,7 @@ constexpr int TB_MAXL = 3;    // weight layers
 constexpr int TB_MAXU = 256;  // padded units per level
 constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns rows 32w..32w+31 in the row phases
 constexpr int TB_THREADS = 64 * TB_WAVES;
+constexpr int TB_STATE_AHEAD = 2;  // tiles of optimizer state in flight per wave
 constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 1024;  // dynamic LDS available to the kernel
 
 struct TLay {
@@ -59,8 +60,8 @@ struct TLay {
   int32_t UP[TB_MAXL + 1];  // padded to 32 (levels < L) or 16 (outputs)
   int32_t S;                // LDS row stride in elements
   int32_t cw[TB_MAXL], cb[TB_MAXL], P;
-  uint32_t lds_buf, lds_delta, lds_rows, lds_tr, lds_total;
-  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL], io[TB_MAXL][2], T[TB_MAXL];
+  uint32_t lds_buf, lds_delta, lds_rows, lds_tr, lds_stage, lds_total;
+  uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL][2], io[2], T[TB_MAXL];
   uint64_t bias[TB_MAXL], bm[TB_MAXL], bv[TB_MAXL], bg[TB_MAXL], total;  // bias: value, moments, partial gradient
 };
 
@@ -91,12 +92,14 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
   uint32_t lo = 0;
   y.lds_buf = lo;
   lo += TB_ROWS * y.S * 2;
-  y.lds_delta = lo;
-  lo += TB_ROWS * 16 * 2;
   y.lds_rows = lo;
   lo += TB_ROWS * 4;
-  y.lds_tr = lo;  // a 16 x 16 bf16 patch per wave
-  lo += TB_WAVES * 512;
+  // 16 KB that serve as: output delta (8 KB) + a 16 x 16 bf16 patch per wave (4 KB) from the output layer to
+  // the last weight gradient, and in between as 2 KB per wave of weight staging for the hidden data gradient
+  y.lds_stage = lo;
+  y.lds_delta = lo;
+  y.lds_tr = lo + TB_ROWS * 16 * 2;
+  lo += TB_WAVES * 2048;
   y.lds_total = lo;
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
@@ -110,11 +113,11 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
     y.m[l] = take(wn * 4);
     y.v[l] = take(wn * 4);
     y.gp[l] = take(wn * 4);
-    y.oi[l] = take((uint64_t)y.UP[l + 1] * y.UP[l] * 2);
-    y.io[l][0] = y.io[l][1] = 0;
-    if (l >= 1) {
-      y.io[l][0] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
-      y.io[l][1] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
+    y.oi[l][0] = take((uint64_t)y.UP[l + 1] * y.UP[l] * 2);
+    y.oi[l][1] = take((uint64_t)y.UP[l + 1] * y.UP[l] * 2);
+    if (l == L - 1) {  // the output layer alone keeps an [in][out] copy
+      y.io[0] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
+      y.io[1] = take((uint64_t)y.UP[l] * y.UP[l + 1] * 2);
     }
     y.bias[l] = take((uint64_t)y.UP[l + 1] * 4);
     y.bm[l] = take((uint64_t)y.UP[l + 1] * 4);
@@ -191,8 +194,8 @@ struct Tiled {
   // ---- blocked indices ------------------------------------------------------
   // state element (in unit k, out unit j) of layer l
   __device__ __forceinline__ size_t sidx(int l, int k, int j) const {
-    const int mta = y.UP[l] / 16;
-    return ((size_t)(j >> 4) * mta + (k >> 4)) * 256 + ((((k & 15) >> 2) << 4) + (j & 15)) * 4 + (k & 3);
+    const int nta = y.UP[l + 1] / 16;  // [in tile][out tile]: a wave walks the out tiles of one in tile
+    return ((size_t)(k >> 4) * nta + (j >> 4)) * 256 + ((((k & 15) >> 2) << 4) + (j & 15)) * 4 + (k & 3);
   }
   // forward operand copy: 16 x 16 tiles [out tile][in tile][out unit][in unit]
   __device__ __forceinline__ size_t oidx(int l, int j, int k) const {
@@ -212,8 +215,8 @@ struct Tiled {
       fp(y.bias[l])[j] = val;
     } else {
       fp(y.w[l])[sidx(l, k, j)] = val;
-      bp(y.oi[l])[oidx(l, j, k)] = (__bf16)val;
-      if (l >= 1) bp(y.io[l][par])[iidx(l, k, j)] = (__bf16)val;
+      bp(y.oi[l][par])[oidx(l, j, k)] = (__bf16)val;
+      if (l + 1 == y.L) bp(y.io[par])[iidx(l, k, j)] = (__bf16)val;
     }
   }
 
@@ -290,15 +293,28 @@ struct Tiled {
   // (tile-blocked in global) are read once per workgroup, the level comes from the buffer.  The lane ends up
   // with units (2w+ub)*16+4q..+3 of row 16jb+li.  The results stay in registers until every wave has read the
   // level, then overwrite it.
-  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int njb,
+  // TR = false: A is the [out][in] copy and the wave produces out units (forward).  TR = true: A is the same
+  // copy but the wave produces in units (data gradient), so each pair of 16 x 16 tiles it fetches passes
+  // through the wave's LDS staging patch and comes back through the transposing read; mt_a = in tiles of A.
+  template <bool TR>
+  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int njb, int mt_a,
                                                  f32x4 (&acc)[2][16]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     // weight operands of the wave's two unit tiles, fetched two k blocks ahead of their use
-    const __bf16* A0 = A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
-    const __bf16* A1 = A0 + (size_t)kbn * 512;
+    // (TR: lanes 0..31 fetch the tile of out tile 2kb, lanes 32..63 that of out tile 2kb + 1)
+    const __bf16* A0 = TR ? A + ((size_t)(lane >> 5) * mt_a + 2 * w) * 256 + (lane & 31) * 8
+                          : A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
+    const __bf16* A1 = A0 + (TR ? (size_t)256 : (size_t)kbn * 512);
+    const size_t kstep = TR ? (size_t)mt_a * 512 : (size_t)512;
+    char* patch = lds + y.lds_stage + w * 2048;
+    auto operand = [&](const bf16x8& raw, int ub) {
+      if (!TR) return raw;
+      *(bf16x8*)(patch + ub * 1024 + lane * 16) = raw;
+      return lds_operand_tr(patch + ub * 1024, 16, 0, 0, li, q);
+    };
     const int k1 = min(1, kbn - 1);
     bf16x8 a0 = *(const bf16x8*)A0, a1 = *(const bf16x8*)A1;
-    bf16x8 n0 = *(const bf16x8*)(A0 + k1 * 512), n1 = *(const bf16x8*)(A1 + k1 * 512);
+    bf16x8 n0 = *(const bf16x8*)(A0 + k1 * kstep), n1 = *(const bf16x8*)(A1 + k1 * kstep);
     const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2;
     const size_t tile_bytes = (size_t)16 * y.S * 2;
 #pragma unroll
@@ -311,13 +327,14 @@ struct Tiled {
 #pragma unroll 1
       for (int kb = 0; kb < kbn; kb++) {
         const int k2 = min(kb + 2, kbn - 1);
-        const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * 512), m1 = *(const bf16x8*)(A1 + k2 * 512);
+        const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * kstep), m1 = *(const bf16x8*)(A1 + k2 * kstep);
+        const bf16x8 o0 = operand(a0, 0), o1 = operand(a1, 1);
 #pragma unroll
         for (int jb = 0; jb < 16; jb++)
           if (FULL || jb < njb) {
             const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes);
-            acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][jb], 0, 0, 0);
-            acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][jb], 0, 0, 0);
+            acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
+            acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
           }
         a0 = n0;
         a1 = n1;
@@ -334,12 +351,12 @@ struct Tiled {
 
   // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
   // (bit 4*(16*ub + jb) + r).  Called by all waves.
-  __device__ __forceinline__ void forward_hidden(int l, int njb, uint32_t (&bits)[4]) const {
+  __device__ __forceinline__ void forward_hidden(int l, int par, int njb, uint32_t (&bits)[4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const bool active = 32 * w < y.UP[l + 1];
     f32x4 acc[2][16];
     if (active)
-      gemm_unitsplit(bp(y.oi[l]), y.UP[l] / 32, njb, acc);
+      gemm_unitsplit<false>(bp(y.oi[l][par]), y.UP[l] / 32, njb, 0, acc);
     __syncthreads();
     if (active) {
       const float* bias = fp(y.bias[l]);
@@ -385,7 +402,7 @@ struct Tiled {
     if (l + 1 == y.L) {
       // the 16-wide output delta sits in its own buffer: nothing is overwritten while it is read
       if (active) {
-        const __bf16* A = bp(y.io[l][par]);
+        const __bf16* A = bp(y.io[par]);
         const char* db = dbuf() + ((size_t)li * 16 + 4 * q) * 2;
 #pragma unroll
         for (int ub = 0; ub < 2; ub++) {
@@ -401,7 +418,7 @@ struct Tiled {
     } else {
       f32x4 acc[2][16];
       if (active)
-        gemm_unitsplit(bp(y.io[l][par]), y.UP[l + 1] / 32, njb, acc);
+        gemm_unitsplit<true>(bp(y.oi[l][par]), y.UP[l + 1] / 32, njb, y.UP[l] / 16, acc);
       __syncthreads();
       if (active) {
 #pragma unroll
@@ -416,14 +433,14 @@ struct Tiled {
 
   // Output layer + loss over the wave's rows (wave w: rows 32w..32w+31).  TRAIN: output delta -> dbuf.
   template <bool TRAIN>
-  __device__ __forceinline__ void forward_out(int rows, float inv_mb, double& lsum, double& hits) const {
+  __device__ __forceinline__ void forward_out(int par, int rows, float inv_mb, double& lsum, double& hits) const {
     const int l = y.L - 1, c = y.U[y.L];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const float* bias = fp(y.bias[l]);
     const int32_t* rl = rowlist();
     char* db = dbuf();
     const bool cls = P.n_classes >= 2;
-    const __bf16* A = bp(y.oi[l]);
+    const __bf16* A = bp(y.oi[l][par]);
     {
       const int kbn = y.UP[l] / 32;
       f32x4 accs[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
@@ -528,8 +545,8 @@ struct Tiled {
     float* bm = fp(y.bm[l]);
     float* bv = fp(y.bv[l]);
     float* bg = fp(y.bg[l]);
-    __bf16* oi = bp(y.oi[l]);
-    __bf16* io = bp(y.io[l][par_next]);
+    __bf16* oi = bp(y.oi[l][par_next]);
+    __bf16* io = bp(y.io[par_next]);
     const __bf16* T = bp(y.T[l]);
     const int fi = y.U[l], fo = y.U[l + 1];
     const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Me = (fi + 15) / 16 + 1, Ne = (fo + 15) / 16;
@@ -577,74 +594,98 @@ struct Tiled {
         sm[0] = bm[j];
         if (adam) sv[0] = bv[j];
       } else {
-        const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
+        const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
         sw = *(const f32x4*)(W + o);
         sm = *(const f32x4*)(Mo + o);
         if (adam) sv = *(const f32x4*)(Vo + o);
       }
     };
-    int u = w;
-    if (u >= NU) return;
-    int mt, nt0, nt1;
-    unit_tiles(u, mt, nt0, nt1);
-    bf16x8 an[8];
-    load_a(mt, an);
-    f32x4 nw = f32x4{0.f, 0.f, 0.f, 0.f}, nm = nw, nv = nw;
-    if (last) load_st(mt, nt0, nw, nm, nv);
-    while (u < NU) {
-      bf16x8 a[8];
-#pragma unroll
-      for (int kb = 0; kb < 8; kb++) a[kb] = an[kb];
-      const int u2 = u + TB_WAVES;
-      const bool more = u2 < NU;
-      int mt2 = mt, nt02 = nt0, nt12 = nt1;
-      if (more) {
-        unit_tiles(u2, mt2, nt02, nt12);
-        load_a(mt2, an);
+    if (w >= NU) return;
+    // The wave's tiles in order: position c is being worked on, pn[0..D-1] follow it.  The optimizer
+    // state is fetched D tiles ahead into D + 1 rotating register sets.
+    constexpr int D = TB_STATE_AHEAD;
+    struct TPos {
+      int u, mt, nt, nt1;
+    };
+    struct St {
+      f32x4 w, m, v;
+    };
+    auto unit_first = [&](int u) {
+      TPos p;
+      int nt0;
+      p.u = u;
+      unit_tiles(u, p.mt, nt0, p.nt1);
+      p.nt = nt0;
+      return p;
+    };
+    auto next_pos = [&](const TPos& p, bool& ok) {
+      TPos r = p;
+      if (ok) {
+        if (p.nt + 1 < p.nt1)
+          r.nt++;
+        else if (p.u + TB_WAVES < NU)
+          r = unit_first(p.u + TB_WAVES);
+        else
+          ok = false;
       }
-      const bool isb = mt == Me - 1;
-      for (int nt = nt0; nt < nt1; nt++) {
-        f32x4 wv = nw, mv = nm, vv = nv;
-        if (last) {  // state of the tile after this one (a repeat of this one when there is none)
-          const bool same = nt + 1 < nt1;
-          load_st(same || !more ? mt : mt2, same ? nt + 1 : (more ? nt02 : nt), nw, nm, nv);
-        }
-        const int j = nt * 16 + li;  // the lane's out unit
-        const size_t o = ((size_t)nt * Mt + mt) * 256 + lane * 4;
-        f32x4 g = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (!first) {
-          if (isb)
-            g[0] = bg[j];
-          else
-            g = *(const f32x4*)(Gp + o);
-        }
+      return r;
+    };
+    TPos c = unit_first(w);
+    TPos pn[D];
+    bool okn[D];
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    St S[D + 1];
 #pragma unroll
-        for (int kb = 0; kb < 8; kb++)
-          if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
-        if (!last) {
-          if (isb) {
-            if (q == 0) bg[j] = g[0];
-          } else {
-            *(f32x4*)(Gp + o) = g;
-          }
-          continue;
+    for (int k = 0; k <= D; k++) S[k] = St{zero4, zero4, zero4};
+    if (last) load_st(c.mt, c.nt, S[0].w, S[0].m, S[0].v);
+#pragma unroll
+    for (int k = 0; k < D; k++) {
+      okn[k] = k ? okn[k - 1] : true;
+      pn[k] = next_pos(k ? pn[k - 1] : c, okn[k]);
+      if (last && k + 1 < D && okn[k]) load_st(pn[k].mt, pn[k].nt, S[k + 1].w, S[k + 1].m, S[k + 1].v);
+    }
+    bf16x8 a[8], an[8];
+    load_a(c.mt, a);
+    if (c.u + TB_WAVES < NU) load_a(unit_first(c.u + TB_WAVES).mt, an);
+    bool alive = true;
+    auto tile = [&](St& cur, St& pre) __attribute__((always_inline)) {
+      if (last && okn[D - 1]) load_st(pn[D - 1].mt, pn[D - 1].nt, pre.w, pre.m, pre.v);
+      const int mt = c.mt, nt = c.nt;
+      const bool isb = mt == Me - 1;
+      const int j = nt * 16 + li;  // the lane's out unit
+      const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
+      f32x4 g = zero4;
+      if (!first) {
+        if (isb)
+          g[0] = bg[j];
+        else
+          g = *(const f32x4*)(Gp + o);
+      }
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++)
+        if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
+      if (!last) {
+        if (isb) {
+          if (q == 0) bg[j] = g[0];
+        } else {
+          *(f32x4*)(Gp + o) = g;
         }
-        if (isb) {  // r = 0 of lane group 0 holds the bias gradient of out unit j
-          if (q == 0 && j < fo) {
-            float wr = wv[0], mr = mv[0], vr = vv[0];
-            opt_update(oc, g[0], wr, mr, vr);
-            if (rec) {
-              rec[1 + cb + j] = g[0];
-              rec[1 + Pn + cb + j] = wr;
-            }
-            bias[j] = wr;
-            bm[j] = mr;
-            if (adam) bv[j] = vr;
+      } else if (isb) {  // r = 0 of lane group 0 holds the bias gradient of out unit j
+        if (q == 0 && j < fo) {
+          float wr = cur.w[0], mr = cur.m[0], vr = cur.v[0];
+          opt_update(oc, g[0], wr, mr, vr);
+          if (rec) {
+            rec[1 + cb + j] = g[0];
+            rec[1 + Pn + cb + j] = wr;
           }
-          continue;
+          bias[j] = wr;
+          bm[j] = mr;
+          if (adam) bv[j] = vr;
         }
+      } else {
         // the lane holds in units i0..i0+3 of out unit j
         const int i0 = mt * 16 + 4 * q;
+        f32x4 wv = cur.w, mv = cur.m, vv = cur.v;
         bf16x4 pk;
         if (!rec && mt * 16 + 16 <= fi && nt * 16 + 16 <= fo) {  // no pad unit in the tile
 #pragma unroll
@@ -681,17 +722,36 @@ struct Tiled {
         if (adam) *(f32x4*)(Vo + o) = vv;
         // both bf16 operand copies are made of 16 x 16 tiles, so the wave writes 512 contiguous bytes each
         *(bf16x4*)(oi + ((size_t)nt * Mt + mt) * 256 + li * 16 + 4 * q) = pk;
-        if (l >= 1) {
+        if (lastlayer) {
           // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
           *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
           const s16x4 tv = lds_read_tr(trp + ((4 * q + (li >> 2)) * 16 + 4 * (li & 3)) * 2);
           *(s16x4*)(io + ((size_t)mt * Nt + nt) * 256 + li * 16 + 4 * q) = tv;
         }
       }
-      u = u2;
-      mt = mt2;
-      nt0 = nt02;
-      nt1 = nt12;
+      // on to the next tile; a new unit brings its activation operand, fetched during the previous unit
+      if (!okn[0]) {
+        alive = false;
+        return;
+      }
+      const int old_u = c.u;
+      c = pn[0];
+#pragma unroll
+      for (int k = 0; k + 1 < D; k++) {
+        pn[k] = pn[k + 1];
+        okn[k] = okn[k + 1];
+      }
+      pn[D - 1] = next_pos(pn[D - 1], okn[D - 1]);
+      if (c.u != old_u) {
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++) a[kb] = an[kb];
+        if (c.u + TB_WAVES < NU) load_a(unit_first(c.u + TB_WAVES).mt, an);
+      }
+    };
+    while (alive) {
+#pragma unroll
+      for (int k = 0; k <= D; k++)
+        if (alive) tile(S[k], S[(k + D) % (D + 1)]);
     }
   }
 
@@ -717,14 +777,14 @@ struct Tiled {
   // Forward pass of the chunk through all layers.  TRAIN: spills the transposes the weight gradients
   // will need, keeps the ReLU patterns, writes the output delta.  Called by all waves.
   template <bool TRAIN>
-  __device__ __forceinline__ void forward_all(int rows, float inv_mb, uint32_t (&bits)[2][4], double& lsum,
+  __device__ __forceinline__ void forward_all(int par, int rows, float inv_mb, uint32_t (&bits)[2][4], double& lsum,
                                               double& hits) const {
     const int w = threadIdx.x >> 6;
     const int KB = (rows + 31) / 32;  // row blocks in use; whole blocks are computed
     for (int l = 0; l + 1 < y.L; l++) {
       if (TRAIN && w < KB) spill_transposed(l);
       uint32_t bl[4];
-      forward_hidden(l, 2 * KB, bl);
+      forward_hidden(l, par, 2 * KB, bl);
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         if (l & 1)
@@ -733,7 +793,7 @@ struct Tiled {
           bits[0][i] = bl[i];
       }
     }
-    if (w < KB) forward_out<TRAIN>(rows, inv_mb, lsum, hits);
+    if (w < KB) forward_out<TRAIN>(par, rows, inv_mb, lsum, hits);
   }
 
   __device__ __forceinline__ void run() const {
@@ -805,7 +865,7 @@ struct Tiled {
           const int KB = (rows + 31) / 32;
           const bool first = ch == 0, last = ch == nch - 1;
           stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true);
-          forward_all<true>(rows, inv_mb, bits, lsum, hits);
+          forward_all<true>(par, rows, inv_mb, bits, lsum, hits);
           __syncthreads();
           for (int l = L - 1; l >= 0; l--) {
             wgrad(l, KB, first, last, oc, par ^ 1, last ? rec : nullptr);
@@ -829,7 +889,7 @@ struct Tiled {
     for (int off = 0; off < n_va; off += TB_ROWS) {
       const int rows = min(TB_ROWS, n_va - off);
       stage_rows(va, 0, n_va, off, rows, false);
-      forward_all<false>(rows, 0.f, bits, lsum, hits);
+      forward_all<false>((int)(gstep & 1), rows, 0.f, bits, lsum, hits);
       __syncthreads();
     }
     lsum = block_sum(lsum, red);
