@@ -289,7 +289,7 @@ struct Tiled {
   }
 
   // ---- hidden layers, forward and data gradient: wave w owns units 32w..32w+31 of the level it produces ----
-  // acc[ub][jb] = sum_k A[(2w+ub)*16 + .][k] * level[16jb + .][k] over the row tiles jb < njb; the weights A
+  // acc[ub][jb] = sum_k A[(2w+ub)*16 + .][k] * level[16jb + .][k] for all 16 row tiles jb; the weights A
   // (tile-blocked in global) are read once per workgroup, the level comes from the buffer.  The lane ends up
   // with units (2w+ub)*16+4q..+3 of row 16jb+li.  The results stay in registers until every wave has read the
   // level, then overwrite it.
@@ -297,7 +297,7 @@ struct Tiled {
   // copy but the wave produces in units (data gradient), so each pair of 16 x 16 tiles it fetches passes
   // through the wave's LDS staging patch and comes back through the transposing read; mt_a = in tiles of A.
   template <bool TR>
-  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int njb, int mt_a,
+  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int mt_a,
                                                  f32x4 (&acc)[2][16]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     // weight operands of the wave's two unit tiles, fetched two k blocks ahead of their use
@@ -322,31 +322,25 @@ struct Tiled {
       acc[0][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
       acc[1][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    auto sweep = [&](auto full) {
-      constexpr bool FULL = decltype(full)::value;
+    // All 16 row tiles are multiplied whatever the chunk holds: tiles past the rows in use only cost
+    // arithmetic on stale buffer contents, and the callers never store their results.
 #pragma unroll 1
-      for (int kb = 0; kb < kbn; kb++) {
-        const int k2 = min(kb + 2, kbn - 1);
-        const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * kstep), m1 = *(const bf16x8*)(A1 + k2 * kstep);
-        const bf16x8 o0 = operand(a0, 0), o1 = operand(a1, 1);
+    for (int kb = 0; kb < kbn; kb++) {
+      const int k2 = min(kb + 2, kbn - 1);
+      const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * kstep), m1 = *(const bf16x8*)(A1 + k2 * kstep);
+      const bf16x8 o0 = operand(a0, 0), o1 = operand(a1, 1);
 #pragma unroll
-        for (int jb = 0; jb < 16; jb++)
-          if (FULL || jb < njb) {
-            const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes);
-            acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
-            acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
-          }
-        a0 = n0;
-        a1 = n1;
-        n0 = m0;
-        n1 = m1;
-        bp += 64;
+      for (int jb = 0; jb < 16; jb++) {
+        const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes);
+        acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
+        acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
       }
-    };
-    if (njb == 16)
-      sweep(std::true_type());
-    else
-      sweep(std::false_type());
+      a0 = n0;
+      a1 = n1;
+      n0 = m0;
+      n1 = m1;
+      bp += 64;
+    }
   }
 
   // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
@@ -356,7 +350,7 @@ struct Tiled {
     const bool active = 32 * w < y.UP[l + 1];
     f32x4 acc[2][16];
     if (active)
-      gemm_unitsplit<false>(bp(y.oi[l][par]), y.UP[l] / 32, njb, 0, acc);
+      gemm_unitsplit<false>(bp(y.oi[l][par]), y.UP[l] / 32, 0, acc);
     __syncthreads();
     if (active) {
       const float* bias = fp(y.bias[l]);
@@ -418,7 +412,7 @@ struct Tiled {
     } else {
       f32x4 acc[2][16];
       if (active)
-        gemm_unitsplit<true>(bp(y.oi[l][par]), y.UP[l + 1] / 32, njb, y.UP[l] / 16, acc);
+        gemm_unitsplit<true>(bp(y.oi[l][par]), y.UP[l + 1] / 32, y.UP[l] / 16, acc);
       __syncthreads();
       if (active) {
 #pragma unroll
