@@ -44,6 +44,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+// MFMA operands that live across loop iterations are kept as four dwords: the compiler carries vectors of
+// 16-bit elements through loops half by half
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 as_bf16x8(i32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ i32x4 as_i32x4(bf16x8 v) { return __builtin_bit_cast(i32x4, v); }
 
 constexpr int TB_ROWS = 256;  // rows per chunk
 constexpr int TB_PAD = 8;     // pad elements per LDS row: consecutive rows start 4 banks apart
@@ -300,21 +305,26 @@ struct Tiled {
   __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int mt_a,
                                                  f32x4 (&acc)[2][16]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    // weight operands of the wave's two unit tiles, fetched two k blocks ahead of their use
     // (TR: lanes 0..31 fetch the tile of out tile 2kb, lanes 32..63 that of out tile 2kb + 1)
     const __bf16* A0 = TR ? A + ((size_t)(lane >> 5) * mt_a + 2 * w) * 256 + (lane & 31) * 8
                           : A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
     const __bf16* A1 = A0 + (TR ? (size_t)256 : (size_t)kbn * 512);
     const size_t kstep = TR ? (size_t)mt_a * 512 : (size_t)512;
     char* patch = lds + y.lds_stage + w * 2048;
-    auto operand = [&](const bf16x8& raw, int ub) {
-      if (!TR) return raw;
-      *(bf16x8*)(patch + ub * 1024 + lane * 16) = raw;
+    auto operand = [&](const i32x4& raw, int ub) {
+      if (!TR) return as_bf16x8(raw);
+      *(i32x4*)(patch + ub * 1024 + lane * 16) = raw;
       return lds_operand_tr(patch + ub * 1024, 16, 0, 0, li, q);
     };
-    const int k1 = min(1, kbn - 1);
-    bf16x8 a0 = *(const bf16x8*)A0, a1 = *(const bf16x8*)A1;
-    bf16x8 n0 = *(const bf16x8*)(A0 + k1 * kstep), n1 = *(const bf16x8*)(A1 + k1 * kstep);
+    // all weight operands of the wave (two unit tiles x up to 8 k blocks) are fetched up front: one
+    // exposed latency per layer, and the waits inside the sweep are exact
+    i32x4 ar[8][2];
+#pragma unroll
+    for (int kb = 0; kb < 8; kb++)
+      if (kb < kbn) {
+        ar[kb][0] = *(const i32x4*)(A0 + (size_t)kb * kstep);
+        ar[kb][1] = *(const i32x4*)(A1 + (size_t)kb * kstep);
+      }
     const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2;
     const size_t tile_bytes = (size_t)16 * y.S * 2;
 #pragma unroll
@@ -324,23 +334,17 @@ struct Tiled {
     }
     // All 16 row tiles are multiplied whatever the chunk holds: tiles past the rows in use only cost
     // arithmetic on stale buffer contents, and the callers never store their results.
-#pragma unroll 1
-    for (int kb = 0; kb < kbn; kb++) {
-      const int k2 = min(kb + 2, kbn - 1);
-      const bf16x8 m0 = *(const bf16x8*)(A0 + k2 * kstep), m1 = *(const bf16x8*)(A1 + k2 * kstep);
-      const bf16x8 o0 = operand(a0, 0), o1 = operand(a1, 1);
 #pragma unroll
-      for (int jb = 0; jb < 16; jb++) {
-        const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes);
-        acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
-        acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
+    for (int kb = 0; kb < 8; kb++)
+      if (kb < kbn) {
+        const bf16x8 o0 = operand(ar[kb][0], 0), o1 = operand(ar[kb][1], 1);
+#pragma unroll
+        for (int jb = 0; jb < 16; jb++) {
+          const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes + kb * 64);
+          acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
+          acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
+        }
       }
-      a0 = n0;
-      a1 = n1;
-      n0 = m0;
-      n1 = m1;
-      bp += 64;
-    }
   }
 
   // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
@@ -568,17 +572,17 @@ struct Tiled {
       nt0 = sg * Ne / NS;
       nt1 = (sg + 1) * Ne / NS;
     };
-    auto load_a = [&](int mt, bf16x8(&a)[8]) {
+    auto load_a = [&](int mt, i32x4(&a)[8]) {
       if (mt == Me - 1) {
-        const __bf16 o = (__bf16)(li == 0 ? 1.f : 0.f);
+        const int o = li == 0 ? 0x3F803F80 : 0;  // two bf16 ones
 #pragma unroll
-        for (int kb = 0; kb < 8; kb++) a[kb] = bf16x8{o, o, o, o, o, o, o, o};
+        for (int kb = 0; kb < 8; kb++) a[kb] = i32x4{o, o, o, o};
       } else {
 #pragma unroll
         for (int kb = 0; kb < 8; kb++)
           if (kb < KB)
-            a[kb] = lastlayer ? lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q)
-                              : *(const bf16x8*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+            a[kb] = lastlayer ? as_i32x4(lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q))
+                              : *(const i32x4*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
       }
     };
     auto load_st = [&](int mt, int nt, f32x4& sw, f32x4& sm, f32x4& sv) {
@@ -638,7 +642,7 @@ struct Tiled {
       pn[k] = next_pos(k ? pn[k - 1] : c, okn[k]);
       if (last && k + 1 < D && okn[k]) load_st(pn[k].mt, pn[k].nt, S[k + 1].w, S[k + 1].m, S[k + 1].v);
     }
-    bf16x8 a[8], an[8];
+    i32x4 a[8], an[8];
     load_a(c.mt, a);
     if (c.u + TB_WAVES < NU) load_a(unit_first(c.u + TB_WAVES).mt, an);
     bool alive = true;
@@ -657,7 +661,7 @@ struct Tiled {
       }
 #pragma unroll
       for (int kb = 0; kb < 8; kb++)
-        if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
+        if (kb < KB) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[kb]), lds_operand_tr(Bl, ldb, kb * 32, nt * 16, li, q), g, 0, 0, 0);
       if (!last) {
         if (isb) {
           if (q == 0) bg[j] = g[0];
