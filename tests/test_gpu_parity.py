@@ -207,6 +207,98 @@ def test_per_step_gradients_and_weights_bf16(bb, oracle, n, d, c, hidden, bs):
             assert relerr(th1[sl], rth[sl]) < REL_BF16, (t, name, "theta")
 
 
+def random_tiled_case(seed):
+    """A seeded random shape inside what the LDS-tiled bf16 kernel takes: 1-2 hidden layers of width
+    1..256, inputs a multiple of 8 up to 256, up to 16 classes or regression, any batch size."""
+    r = np.random.default_rng(7000 + seed)
+    d = 8 * int(r.integers(1, 33))
+    hidden = [int(r.integers(1, 257)) for _ in range(int(r.integers(1, 3)))]
+    c = int(r.choice([0, 2, 3, 10, 16]))
+    n = int(r.integers(120, 700))
+    bs = int(r.choice([0, 1, 7, 64, 255, 256, 257, 300, 513]))
+    solver = str(r.choice(["adam", "adam", "sgd"]))
+    return n, d, c, hidden, bs, solver, bool(r.integers(0, 2)), float(r.choice([0.0, 0.01, 0.5]))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_bf16_steps(bb, oracle, seed):
+    n, d, c, hidden, bs, solver, nesterov, alpha = random_tiled_case(seed)
+    cfg = small_problem(500 + seed, n, d, c, bf16=True)
+    hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "momentum": 0.8, "batch_size": bs, "alpha": alpha,
+          "lr": 0.003, "epochs": 3, "seed": 99 + seed}
+    f = seed % 5
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    total = 3 * -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(6, total)
+    c_out = c if c >= 2 else 1
+    X, y, ft = bb.to_device(cfg)
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 1, want_per_fold=True, trace=(0, f, 0, 2))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=1, step_begin=0, step_end=2)
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    case = (n, d, c, hidden, bs, solver)
+    for t in range(min(2, total)):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_BF16, (case, t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (case, t, name, "theta")
+    # the fold score after 3 epochs of a free bf16 run, against the run's own sensitivity to rounding
+    # (batches of one row take a thousand noisy steps)
+    probes = [oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], dict(hp, **kw), f, dtype=1, prec=pr)["scores"][0]
+              for kw, pr in (({}, 1), ({"lr": float(np.nextafter(np.float32(hp["lr"]), np.float32(1)))}, 0),
+                             ({"lr": float(np.nextafter(np.float32(hp["lr"]), np.float32(0)))}, 0))]
+    noise = max(abs(q - ref["scores"][0]) for q in probes)
+    if noise < 5 * ABS_SCORE:
+        assert abs(pf[0, f, 0].item() - ref["scores"][0]) < 5 * ABS_SCORE + 2 * noise, (case, noise)
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in (3, 5) if t < T], T):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_BF16, (case, t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_BF16, (case, t, name, "theta")
+
+
+def random_fp32_case(seed):
+    """A seeded random fp32 shape: even seeds inside what the LDS-resident kernel takes (one hidden layer,
+    d <= 63, width <= 224, <= 4 outputs), odd seeds anything else the header admits (generic kernel)."""
+    r = np.random.default_rng(8000 + seed)
+    if seed % 2 == 0:
+        d, hidden, c = int(r.integers(1, 64)), [int(r.integers(1, 225))], int(r.choice([0, 2, 3, 4]))
+    else:
+        d = int(r.integers(1, 200))
+        hidden = [int(r.integers(1, 300)) for _ in range(int(r.integers(0, 4)))]
+        c = int(r.choice([0, 2, 5, 10, 33]))
+    n = int(r.integers(60, 500))
+    bs = int(r.choice([0, 1, 5, 16, 63, 64, 65, 100, 200]))
+    solver = str(r.choice(["adam", "sgd"]))
+    return n, d, c, hidden, bs, solver, bool(r.integers(0, 2)), float(r.choice([0.0, 0.05, 2.0]))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_shapes_fp32_steps(bb, oracle, seed):
+    n, d, c, hidden, bs, solver, nesterov, alpha = random_fp32_case(seed)
+    cfg = small_problem(900 + seed, n, d, c)
+    hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "momentum": 0.8, "batch_size": bs, "alpha": alpha,
+          "lr": 0.005, "epochs": 3, "seed": 77 + seed}
+    f = seed % 5
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    total = 3 * -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(8, total)
+    c_out = c if c >= 2 else 1
+    X, y, ft = bb.to_device(cfg)
+    out = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 0, trace=(0, f, 0, min(3, total)))
+    torch.cuda.synchronize()
+    tr = out[-1]
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, step_begin=0, step_end=min(3, total))
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    case = (n, d, c, hidden, bs, solver)
+    for t in range(min(3, total)):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_F32, (case, t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_F32, (case, t, name, "theta")
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 0, [t for t in (4, 7) if t < T], T):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_F32, (case, t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_F32, (case, t, name, "theta")
+
+
 # ----------------------------------------------------------- final scores ----
 
 def explained_flips(acc_gpu, acc_ref, n_va):
