@@ -593,9 +593,9 @@ struct Tiled {
         if (adam) sv[0] = bv[j];
       } else {
         const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
-        sw = *(const f32x4*)(W + o);
-        sm = *(const f32x4*)(Mo + o);
-        if (adam) sv = *(const f32x4*)(Vo + o);
+        sw = __builtin_nontemporal_load((const f32x4*)(W + o));
+        sm = __builtin_nontemporal_load((const f32x4*)(Mo + o));
+        if (adam) sv = __builtin_nontemporal_load((const f32x4*)(Vo + o));
       }
     };
     if (w >= NU) return;
@@ -715,9 +715,9 @@ struct Tiled {
             pk[r] = (__bf16)wr;
           }
         }
-        *(f32x4*)(W + o) = wv;
-        *(f32x4*)(Mo + o) = mv;
-        if (adam) *(f32x4*)(Vo + o) = vv;
+        __builtin_nontemporal_store(wv, (f32x4*)(W + o));
+        __builtin_nontemporal_store(mv, (f32x4*)(Mo + o));
+        if (adam) __builtin_nontemporal_store(vv, (f32x4*)(Vo + o));
         // both bf16 operand copies are made of 16 x 16 tiles, so the wave writes 512 contiguous bytes each
         *(bf16x4*)(oi + ((size_t)nt * Mt + mt) * 256 + li * 16 + 4 * q) = pk;
         if (lastlayer) {
