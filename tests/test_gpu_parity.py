@@ -220,7 +220,7 @@ def random_tiled_case(seed):
     return n, d, c, hidden, bs, solver, bool(r.integers(0, 2)), float(r.choice([0.0, 0.01, 0.5]))
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_shapes_bf16_steps(bb, oracle, seed):
     n, d, c, hidden, bs, solver, nesterov, alpha = random_tiled_case(seed)
     cfg = small_problem(500 + seed, n, d, c, bf16=True)
@@ -232,12 +232,15 @@ def test_random_shapes_bf16_steps(bb, oracle, seed):
     T = min(6, total)
     c_out = c if c >= 2 else 1
     X, y, ft = bb.to_device(cfg)
-    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 1, want_per_fold=True, trace=(0, f, 0, 2))
+    # step 0 from the shared initial weights (Adam's first step moves every weight by the full learning
+    # rate in the direction of its gradient's sign, so a free run's second step already differs where
+    # the sign of a near-zero gradient does: the later steps below start from the oracle's state)
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 1, want_per_fold=True, trace=(0, f, 0, 1))
     torch.cuda.synchronize()
-    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=1, step_begin=0, step_end=2)
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=1, step_begin=0, step_end=1)
     g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
     case = (n, d, c, hidden, bs, solver)
-    for t in range(min(2, total)):
+    for t in range(1):
         for name, sl in layer_slices(d, hidden, c_out):
             assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_BF16, (case, t, name, "grad")
             assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (case, t, name, "theta")
@@ -249,7 +252,7 @@ def test_random_shapes_bf16_steps(bb, oracle, seed):
     noise = max(abs(q - ref["scores"][0]) for q in probes)
     if noise < 5 * ABS_SCORE:
         assert abs(pf[0, f, 0].item() - ref["scores"][0]) < 5 * ABS_SCORE + 2 * noise, (case, noise)
-    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in (3, 5) if t < T], T):
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in (1, 3, 5) if t < T], T):
         for name, sl in layer_slices(d, hidden, c_out):
             assert relerr(g1[sl], rg[sl]) < REL_BF16, (case, t, name, "grad")
             assert relerr(th1[sl], rth[sl]) < REL_BF16, (case, t, name, "theta")
@@ -271,7 +274,7 @@ def random_fp32_case(seed):
     return n, d, c, hidden, bs, solver, bool(r.integers(0, 2)), float(r.choice([0.0, 0.05, 2.0]))
 
 
-@pytest.mark.parametrize("seed", range(20))
+@pytest.mark.parametrize("seed", range(40))
 def test_random_shapes_fp32_steps(bb, oracle, seed):
     n, d, c, hidden, bs, solver, nesterov, alpha = random_fp32_case(seed)
     cfg = small_problem(900 + seed, n, d, c)
