@@ -545,6 +545,32 @@ def test_edge_cases(bb, oracle):
     assert abs(s[1, 0].item() - rs[1, 0]) < ABS_SCORE
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_maximum_sizes(bb, oracle, dtype):
+    """The largest shape the header admits: 4 hidden layers of 1024 units, 4096 features, 256 classes
+    (7.6 M parameters), a few steps on a few rows."""
+    n, d, c = 40, 4096, 256
+    cfg = small_problem(77, n, d, c, bf16=bool(dtype))
+    hp = {"hidden": [1024, 1024, 1024, 1024], "solver": "adam", "batch_size": 16, "alpha": 0.01, "lr": 0.001,
+          "epochs": 1, "seed": 5}
+    X, y, ft = bb.to_device(cfg)
+    f = 0
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], dtype, want_per_fold=True, trace=(0, f, 0, 2))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=2)
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    tol = REL_BF16 if dtype else REL_F32
+    for name, sl in layer_slices(d, hp["hidden"], c):
+        assert relerr(g[0, sl], ref["grad"][0, sl]) < tol, (name, "grad")
+        assert relerr(th[0, sl], ref["theta_after"][0, sl]) < tol, (name, "theta")
+    assert np.all(np.isfinite(g[1])) and np.all(np.isfinite(th[1]))
+    assert status.item() == 0 and abs(pf[0, f, 0].item() - ref["scores"][0]) < (20 if dtype else 1) * ABS_SCORE
+    # one more unit, feature, class or layer is refused with a code, not a fault
+    for bad_hp, bad_d, bad_c in [(dict(hp, hidden=[1025]), d, c), (dict(hp, hidden=[8] * 5), d, c)]:
+        with pytest.raises(bb.BboError):
+            bb.bbo_mlp_cv_eval(X, y, bad_c, ft, 5, [bad_hp], dtype)
+
+
 def test_error_codes(bb):
     cfg = small_problem(5, 60, 6, 3)
     X, y, ft = bb.to_device(cfg)
