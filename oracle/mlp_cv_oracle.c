@@ -61,7 +61,10 @@ typedef struct oracle_hparams {
   int32_t batch_size; /* 0 => full batch; clipped to the fold's train rows */
   int32_t epochs;
   float lr, alpha, momentum, beta1, beta2, eps;
+  float power_t; /* sgd only: learning rate of epoch e = lr / (1 + e * n_train)^power_t; 0 = constant */
   uint64_t seed;
+  float tol;                /* with n_iter_no_change > 0: training stops once the epoch's mean data loss */
+  int32_t n_iter_no_change; /* has failed to improve on the best so far by tol more than this many epochs in a row */
 } oracle_hparams;
 
 /* ------------------------------------------------------------------ */
@@ -322,10 +325,11 @@ static double data_loss(const net_t* net, const data_t* D, const int32_t* rows, 
 /* Training loss (data loss + L2 penalty) and its gradient on one minibatch. */
 static double loss_grad(const net_t* net, const data_t* D, const int32_t* rows, int64_t m,
                         const double* theta, double alpha, double* grad, scratch_t* s,
-                        int prec) {
+                        int prec, double* data_part) {
   int dt = D->dtype;
   forward(net, D, rows, m, theta, s, prec);
   double loss = data_loss(net, D, rows, m, s, prec, 1, 1);
+  if (data_part) *data_part = loss;
   double pen = 0.0;
   for (int l = 0; l < net->L; l++) {
     const double* W = theta + net->w_off[l];
@@ -381,7 +385,7 @@ int oracle_loss_grad(const void* X, const void* y, int64_t n, int32_t d, int32_t
   data_t D = {X, y, n, d, dtype};
   scratch_t s;
   if (scratch_alloc(&s, &net, m)) return -2;
-  *loss_out = loss_grad(&net, &D, rows, m, theta, (double)hp->alpha, grad_out, &s, prec);
+  *loss_out = loss_grad(&net, &D, rows, m, theta, (double)hp->alpha, grad_out, &s, prec, NULL);
   scratch_free(&s, &net);
   return 0;
 }
@@ -409,9 +413,9 @@ static void adam_step(const oracle_hparams* hp, int64_t P, double* theta, const 
   }
 }
 
-static void sgd_step(const oracle_hparams* hp, int64_t P, double* theta, const double* g,
+static void sgd_step(const oracle_hparams* hp, double lr, int64_t P, double* theta, const double* g,
                      opt_t* o, int prec) {
-  double mu = hp->momentum, lr = hp->lr;
+  double mu = hp->momentum;
   for (int64_t i = 0; i < P; i++) {
     double u = rnd(rnd(mu * o->m[i], prec) - rnd(lr * g[i], prec), prec);
     o->m[i] = u;
@@ -429,7 +433,7 @@ int oracle_opt_step(const oracle_hparams* hp, int64_t P, double* theta, const do
   if (hp->solver == 0)
     adam_step(hp, P, theta, g, &o, prec);
   else {
-    sgd_step(hp, P, theta, g, &o, prec);
+    sgd_step(hp, (double)hp->lr, P, theta, g, &o, prec);
     o.t += 1;
   }
   *t = o.t;
@@ -508,17 +512,25 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
   init_params(net, hp->seed, fold, theta);
 
   int64_t steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0, gstep = 0;
-  int done = 0;
-  for (int e = 0; e < hp->epochs && !done; e++) {
+  int done = 0, stalled = 0, stop = 0;
+  float best = INFINITY;
+  for (int e = 0; e < hp->epochs && !done && !stop; e++) {
     uint64_t key = epoch_key(hp->seed, fold, e);
+    /* inverse-scaling schedule of the sgd solver: the rate falls with the rows seen before the epoch */
+    double lr_e = (double)hp->lr;
+    if (hp->solver != 0 && hp->power_t != 0.0f)
+      lr_e = rnd(lr_e / pow(1.0 + (double)e * (double)n_tr, (double)hp->power_t), prec);
+    double esum = 0.0;
     for (int64_t st = 0; st < steps && !done; st++, gstep++) {
       int64_t lo = st * bs, hi = lo + bs > n_tr ? n_tr : lo + bs, mb = hi - lo;
       for (int64_t p = lo; p < hi; p++) rows[p - lo] = tr[perm_index(key, n_tr, p)];
-      double loss = loss_grad(net, D, rows, mb, theta, (double)hp->alpha, grad, &s, prec);
+      double data = 0.0;
+      double loss = loss_grad(net, D, rows, mb, theta, (double)hp->alpha, grad, &s, prec, &data);
+      esum += data * (double)mb;
       if (hp->solver == 0)
         adam_step(hp, P, theta, grad, &o, prec);
       else
-        sgd_step(hp, P, theta, grad, &o, prec);
+        sgd_step(hp, lr_e, P, theta, grad, &o, prec);
       if (trace && gstep >= trace->step_begin && gstep < trace->step_end) {
         double* rec = trace->out + (gstep - trace->step_begin) * (1 + 4 * P);
         rec[0] = loss;
@@ -528,6 +540,13 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
         memcpy(rec + 1 + 3 * P, v, sizeof(double) * (size_t)P);
         if (trace->stop_after && gstep + 1 == trace->step_end) done = 1;
       }
+    }
+    /* plateau stop on the epoch's mean data loss (single precision, as the kernels decide it) */
+    if (hp->n_iter_no_change > 0 && steps > 0 && !done) {
+      float le = (float)(esum / (double)n_tr);
+      stalled = le > best - hp->tol ? stalled + 1 : 0;
+      if (le < best) best = le;
+      if (stalled > hp->n_iter_no_change) stop = 1;
     }
   }
 

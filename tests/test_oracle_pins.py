@@ -477,3 +477,64 @@ def test_holdout_score_is_the_held_rows_loss_of_the_model_trained_on_all_folds(o
     # no held rows: non-finite score, status 1
     s, st = oracle.holdout_eval(X, y, 0, np.zeros(90, dtype=np.int32), hps[:1])
     assert st[0] == 1 and not np.isfinite(s[0, 0])
+
+
+def test_inverse_scaling_rate_matches_a_hand_written_sgd_loop(oracle):
+    """SGD with the inverse-scaling schedule: the rate of epoch e is lr / (1 + e * n_train)^power_t;
+    checked against the same loop written with library autograd and an explicit momentum update."""
+    X, y = tiny_problem(8, n=50, d=4, n_classes=0)
+    fold = inputs.make_folds(50, 5, 1)
+    f, p_t = 1, 0.5
+    hp = {"hidden": [5], "solver": "sgd", "nesterov": False, "lr": 0.05, "alpha": 0.0, "momentum": 0.6, "batch_size": 20,
+          "epochs": 3, "seed": 4, "power_t": p_t}
+    res = oracle.train_one(X, y, 0, fold, hp, f, prec=1, step_begin=0, step_end=6)
+    tt = torch.tensor(oracle.init_params(4, 0, hp, f), dtype=torch.float64, requires_grad=True)
+    vel = torch.zeros_like(tt)
+    lr0, mu = float(np.float32(0.05)), float(np.float32(0.6))
+    n_tr, k = 40, 0
+    for ep in range(3):
+        lr_e = lr0 / (1.0 + ep * n_tr) ** float(np.float32(p_t))
+        for s in range(2):
+            rows = oracle.minibatch_rows(fold, hp, f, ep, s)
+            loss = torch_loss(tt, [4, 5, 1], torch.tensor(X[rows], dtype=torch.float64),
+                              torch.tensor(y[rows], dtype=torch.float64), 0, 0.0)
+            (g,) = torch.autograd.grad(loss, tt)
+            vel = mu * vel - lr_e * g
+            tt = (tt + vel).detach().requires_grad_(True)
+            np.testing.assert_allclose(res["theta_after"][k], tt.detach().numpy(), rtol=1e-9, atol=1e-12)
+            k += 1
+    # Adam ignores the schedule
+    a0 = oracle.train_one(X, y, 0, fold, dict(hp, solver="adam", power_t=0.0), f, prec=1)["theta"]
+    a1 = oracle.train_one(X, y, 0, fold, dict(hp, solver="adam", power_t=0.5), f, prec=1)["theta"]
+    assert np.array_equal(a0, a1)
+
+
+def test_plateau_stop_ends_training_at_the_epoch_the_rule_gives(oracle):
+    """With n_iter_no_change = k, training ends after the first epoch that closes a run of more than k epochs
+    whose mean data loss failed to beat the best so far by tol; the epoch losses are recomputed here from
+    the recorded per-step losses (alpha = 0, so the step loss is the data loss)."""
+    X, y = tiny_problem(9, n=60, d=4, n_classes=3)
+    fold = inputs.make_folds(60, 5, 2)
+    f = 0
+    base = {"hidden": [6], "solver": "adam", "lr": 0.05, "alpha": 0.0, "batch_size": 16, "epochs": 60, "seed": 12}
+    free = oracle.train_one(X, y, 3, fold, base, f, step_begin=0, step_end=60 * 3)
+    sizes = np.array([16, 16, 16])  # 48 training rows
+    ep_loss = (free["loss"].reshape(60, 3) * sizes).sum(1) / 48.0
+    for tol, k in [(1e-3, 2), (5e-2, 1), (0.0, 3)]:
+        best, stalled, stop_at = np.float32(np.inf), 0, 60
+        for e in range(60):
+            le = np.float32(ep_loss[e])
+            stalled = stalled + 1 if le > np.float32(best - np.float32(tol)) else 0
+            best = min(best, le)
+            if stalled > k:
+                stop_at = e + 1
+                break
+        hp = dict(base, tol=tol, n_iter_no_change=k)
+        got = oracle.train_one(X, y, 3, fold, hp, f, step_begin=0, step_end=60 * 3)
+        done = int(np.isfinite(got["loss"]).sum()) // 3
+        assert done == stop_at, (tol, k, done, stop_at)
+        # the stopped model is the free run's model at that epoch
+        np.testing.assert_array_equal(got["theta"], free["theta_after"][3 * stop_at - 1])
+    # n_iter_no_change = 0 switches the rule off whatever tol is
+    off = oracle.train_one(X, y, 3, fold, dict(base, tol=10.0), f)
+    np.testing.assert_array_equal(off["theta"], free["theta"])
