@@ -58,7 +58,15 @@ typedef struct bbo_mlp_hparams {
                                      training rows => full batch */
   int32_t epochs;                 /* >= 0; 0 scores the initial weights */
   float lr, alpha, momentum, beta1, beta2, eps;
+  float power_t;                  /* SGD only: learning rate of epoch e =
+                                     lr / (1 + e * n_train)^power_t; 0 = constant */
   uint64_t seed;                  /* initial weights and minibatch order */
+  float tol;                      /* plateau stop, active when n_iter_no_change > 0: */
+  int32_t n_iter_no_change;       /* training ends once the epoch's mean data loss has
+                                     failed to beat the best so far by tol for more
+                                     than this many epochs in a row; `epochs` stays
+                                     the upper limit.  Switched off in a traced call
+                                     that resumes from state_in. */
 } bbo_mlp_hparams;
 
 /*

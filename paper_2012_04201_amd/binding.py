@@ -36,7 +36,10 @@ class HParams(C.Structure):
         ("beta1", C.c_float),
         ("beta2", C.c_float),
         ("eps", C.c_float),
+        ("power_t", C.c_float),
         ("seed", C.c_uint64),
+        ("tol", C.c_float),
+        ("n_iter_no_change", C.c_int32),
     ]
 
 
@@ -86,6 +89,9 @@ def make_hparams(dicts):
         h.beta2 = float(dct.get("beta2", 0.999))
         h.eps = float(dct.get("eps", 1e-8))
         h.seed = int(dct.get("seed", 0))
+        h.power_t = float(dct.get("power_t", 0.0))
+        h.tol = float(dct.get("tol", 0.0))
+        h.n_iter_no_change = int(dct.get("n_iter_no_change", 0))
     return arr
 
 

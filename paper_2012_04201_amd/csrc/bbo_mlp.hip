@@ -39,6 +39,8 @@
 #include "train_tiled_bf16.h"
 #include "train_small_f32.h"
 
+static_assert(sizeof(bbo_mlp_hparams) == 80, "the hyper-parameter record is part of the ABI");
+
 namespace {
 
 // ---------------------------------------------------------------------------
@@ -407,7 +409,7 @@ struct Trainer {
     const int rows = y.rows;
     const float am = it.alpha / (float)mb;
     const bool adam = it.solver == BBO_ADAM, nest = it.nesterov != 0;
-    const float b1 = it.beta1, b2 = it.beta2, eps = it.eps, mu = it.momentum, lr = it.lr;
+    const float b1 = it.beta1, b2 = it.beta2, eps = it.eps, mu = it.momentum, lr = lr_t;  // lr: the SGD rate
     const float omb1 = 1.f - b1, omb2 = 1.f - b2;
     for (int l = 0; l < y.L; l++) {
       float* W = fp(y.w[l]);
@@ -504,13 +506,18 @@ struct Trainer {
     }
     __syncthreads();
 
+    Plateau plateau;
+    const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
     for (int e = e0; e < it.epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
+      const float lr_e = epoch_lr(it.lr, it.power_t, e, n_tr);  // SGD
+      double esum = 0.0;  // the thread's share of the epoch's summed data loss
       for (int st = e == e0 ? st0 : 0; st < steps; st++, gstep++) {
         const int lo = st * bs, mb = min(bs, n_tr - lo), Mrows = rup(mb, O::KSTEP);
         gather(tr, ke, n_tr, lo, mb, Mrows, true);
         forward(Mrows);
         const double lpart = loss_and_delta(mb, Mrows);
+        esum += lpart;
         float* rec = nullptr;
         if (traced && gstep >= P.step_begin && gstep < P.step_end) {
           rec = P.trace_out + (gstep - P.step_begin) * (1 + 2 * (int64_t)y.P);
@@ -519,7 +526,7 @@ struct Trainer {
           if (threadIdx.x == 0) rec[0] = (float)(data + 0.5 * (double)it.alpha * pen / (double)mb);
         }
         backward_data(Mrows);
-        float lr_t = it.lr;
+        float lr_t = lr_e;
         if (it.solver == BBO_ADAM) {
           b1t *= (double)it.beta1;
           b2t *= (double)it.beta2;
@@ -527,6 +534,7 @@ struct Trainer {
         }
         wgrad_update(mb, Mrows, lr_t, rec);
       }
+      if (watch && plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) break;
     }
 
     // validation score on the held rows, in chunks of the slot's row capacity
@@ -665,8 +673,9 @@ int check_hparams(const bbo_mlp_hparams* hp, int B) {
     if (h.solver != BBO_ADAM && h.solver != BBO_SGD) return fail(BBO_INVALID_ARG, "unknown solver");
     if (h.epochs < 0) return fail(BBO_INVALID_ARG, "epochs < 0");
     if (std::isnan(h.lr) || std::isnan(h.alpha) || std::isnan(h.momentum) || std::isnan(h.beta1) ||
-        std::isnan(h.beta2) || std::isnan(h.eps))
+        std::isnan(h.beta2) || std::isnan(h.eps) || std::isnan(h.power_t) || std::isnan(h.tol))
       return fail(BBO_INVALID_ARG, "NaN hyper-parameter");
+    if (h.n_iter_no_change < 0) return fail(BBO_INVALID_ARG, "n_iter_no_change < 0");
   }
   return BBO_OK;
 }
@@ -766,6 +775,10 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
     it.beta1 = h.beta1;
     it.beta2 = h.beta2;
     it.eps = h.eps;
+    it.power_t = h.power_t;
+    it.tol = h.tol;
+    it.patience = h.n_iter_no_change;
+    it.pad_ = 0;
     const int64_t bs = (h.batch_size <= 0 || h.batch_size > n) ? n : h.batch_size;
     it.rows_cap = rup((int)std::max<int64_t>(bs, 1), kstep);
     double fps = 0, params = 0;

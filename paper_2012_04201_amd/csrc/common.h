@@ -64,6 +64,8 @@ struct ItemDesc {
   uint64_t seed;
   int32_t b, fold, L, solver, nesterov, batch_size, epochs, rows_cap;
   float lr, alpha, momentum, beta1, beta2, eps;
+  float power_t, tol;
+  int32_t patience, pad_;
   int32_t dims[MAXL + 1];
   float bound[MAXL];
 };
@@ -164,5 +166,23 @@ __device__ inline double block_sum(double v, double* red) {
 
 
 __device__ inline int eff_batch(int bs, int n_tr) { return (bs <= 0 || bs > n_tr) ? n_tr : bs; }
+
+// Inverse-scaling schedule of the SGD solver: the rate of epoch e is lr / (1 + e * n_tr)^power_t
+// (n_tr rows seen per epoch); single-precision exp2 / log2, a few 1e-6 relative.
+__device__ inline float epoch_lr(float lr, float power_t, int e, int n_tr) {
+  if (power_t == 0.f) return lr;
+  return lr * exp2f(-power_t * log2f(1.f + (float)e * (float)n_tr));
+}
+
+// Plateau stop: the epoch's mean data loss against the best so far, decided in single precision.
+struct Plateau {
+  float best = INFINITY;
+  int stalled = 0;
+  __device__ bool stop_after(float epoch_loss, float tol, int patience) {
+    stalled = epoch_loss > best - tol ? stalled + 1 : 0;
+    if (epoch_loss < best) best = epoch_loss;
+    return stalled > patience;
+  }
+};
 
 }  // namespace

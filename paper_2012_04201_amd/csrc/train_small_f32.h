@@ -577,7 +577,8 @@ struct Small {
     oc.lr_t = it.lr;
 
     // ---- training: the chunks of all steps of all epochs, inputs fetched one chunk ahead ----
-    auto chunk_valid = [&](const ChunkPos& p) { return steps > 0 && p.e < it.epochs; };
+    int epochs_lim = it.epochs;  // lowered when the plateau rule ends training
+    auto chunk_valid = [&](const ChunkPos& p) { return steps > 0 && p.e < epochs_lim; };
     auto chunk_rows = [&](const ChunkPos& p) { return min(SM_RC, min(bs, n_tr - p.st * bs) - p.c0); };
     auto chunk_next = [&](ChunkPos p) {
       const int mb = min(bs, n_tr - p.st * bs);
@@ -607,13 +608,16 @@ struct Small {
     }
     f32x4 acc[4][4], accg[4][KT], g2p[4];
     f32x4 gb2 = f32x4{0.f, 0.f, 0.f, 0.f};
-    double lsum = 0.0, hits = 0.0, pen = 0.0;
+    double lsum = 0.0, hits = 0.0, pen = 0.0, esum = 0.0;  // esum: the lane's share of the epoch's summed data loss
     float* rec = nullptr;
+    Plateau plateau;
+    const bool watch = it.patience > 0 && !resume;
     while (chunk_valid(pos)) {
       const int mb = min(bs, n_tr - pos.st * bs);
       const int rows = chunk_rows(pos), nrt = (rows + 15) / 16;
       if (pos.c0 == 0) {  // first chunk of a step
         oc.am = it.alpha / (float)mb;
+        if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, pos.e, n_tr);
         if (oc.adam) {
           b1t *= (double)it.beta1;
           b2t *= (double)it.beta2;
@@ -660,6 +664,11 @@ struct Small {
           if (threadIdx.x == 0) rec[0] = (float)(data + 0.5 * (double)it.alpha * pen / (double)mb);
         }
         gstep++;
+        esum += lsum;
+        if (watch && nxt.e != pos.e) {  // that was the last step of the epoch
+          if (plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) epochs_lim = pos.e + 1;
+          esum = 0.0;
+        }
       }
       pos = nxt;
       par ^= 1;

@@ -840,8 +840,12 @@ struct Tiled {
     oc.lr_t = it.lr;
 
     uint32_t bits[2][4];
+    Plateau plateau;
+    const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
     for (int e = e0; e < it.epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
+      if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, e, n_tr);
+      double esum = 0.0;  // the lane's share of the epoch's summed data loss
       for (int st = e == e0 ? st0 : 0; st < steps; st++, gstep++) {
         const int lo = st * bs, mb = min(bs, n_tr - lo);
         const int nch = (mb + TB_ROWS - 1) / TB_ROWS, par = (int)(gstep & 1);
@@ -875,11 +879,13 @@ struct Tiled {
             }
           }
         }
+        esum += lsum;
         if (rec) {
           const double data = block_sum(lsum, red) / (double)mb;
           if (threadIdx.x == 0) rec[0] = (float)(data + 0.5 * (double)it.alpha * pen / (double)mb);
         }
       }
+      if (watch && plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) break;
     }
 
     // validation score on the held rows

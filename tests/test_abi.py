@@ -33,8 +33,8 @@ def test_header_symbols_are_exported(bb):
 
 
 def test_hparams_struct_layout(bb):
-    assert C.sizeof(bb.HParams) == 72
-    assert bb.HParams.seed.offset == 64 and bb.HParams.lr.offset == 36
+    assert C.sizeof(bb.HParams) == 80
+    assert bb.HParams.seed.offset == 64 and bb.HParams.lr.offset == 36 and bb.HParams.power_t.offset == 60 and bb.HParams.tol.offset == 72
 
 
 def test_argument_validation_without_gpu(bb):

@@ -302,6 +302,69 @@ def test_random_shapes_fp32_steps(bb, oracle, seed):
             assert relerr(th1[sl], rth[sl]) < REL_F32, (case, t, name, "theta")
 
 
+# -------------------------------------------- schedule and plateau stop ----
+
+CONTROL_SHAPES = [
+    # n, d, classes, hidden, batch, dtype: one shape per training kernel
+    (300, 20, 3, [40], 50, 0),        # LDS-resident fp32
+    (260, 70, 5, [33, 21], 64, 0),    # generic fp32
+    (400, 64, 10, [96, 80], 128, 1),  # LDS-tiled bf16
+]
+
+
+@pytest.mark.parametrize("n,d,c,hidden,bs,dtype", CONTROL_SHAPES)
+def test_inverse_scaling_rate_steps(bb, oracle, n, d, c, hidden, bs, dtype):
+    cfg = small_problem(1200 + d, n, d, c, bf16=bool(dtype))
+    hp = {"hidden": hidden, "solver": "sgd", "nesterov": True, "momentum": 0.7, "batch_size": bs, "alpha": 0.01,
+          "lr": 0.05, "power_t": 0.5, "epochs": 4, "seed": 21}
+    f = 1
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    spe = -(-n_tr // bs)
+    T = 3 * spe
+    tol = REL_BF16 if dtype else REL_F32
+    c_out = c if c >= 2 else 1
+    # single steps in the second and third epoch from the oracle's state: the rate they use has fallen.
+    # The update itself (new minus old parameters) is compared too: at the constant rate it would be
+    # about sqrt(1 + e * n_tr) times larger, which a comparison of the parameters alone could miss.
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=T)
+    picks = [spe, spe + 1, 2 * spe, T - 1]
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, dtype, picks, T):
+        before = ref["theta_after"][t - 1]
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g1[sl], rg[sl]) < tol, (t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < tol, (t, name, "theta")
+            assert relerr(th1[sl] - before[sl], rth[sl] - before[sl]) < 5 * tol + 1e-2, (t, name, "update")
+
+
+@pytest.mark.parametrize("n,d,c,hidden,bs,dtype", CONTROL_SHAPES)
+def test_plateau_stop_epoch_and_score(bb, oracle, n, d, c, hidden, bs, dtype):
+    cfg = small_problem(1300 + d, n, d, c, bf16=bool(dtype))
+    X, y, ft = bb.to_device(cfg)
+    f = 2
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    spe = -(-n_tr // bs)
+    E = 40
+    stops = []
+    for tol_, k in [(3e-2, 1), (1e-2, 3), (0.0, 0)]:
+        hp = {"hidden": hidden, "solver": "adam", "batch_size": bs, "alpha": 0.001, "lr": 0.01, "epochs": E, "seed": 33,
+              "tol": tol_, "n_iter_no_change": k}
+        scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], dtype, want_per_fold=True,
+                                                    trace=(0, f, 0, E * spe))
+        torch.cuda.synchronize()
+        done = int(np.isfinite(tr["loss"].cpu().numpy()).sum())
+        ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=E * spe)
+        ref_done = int(np.isfinite(ref["loss"]).sum())
+        assert done % spe == 0 and ref_done % spe == 0
+        # The rule compares losses that differ by rounding between the two sides; an epoch whose loss sits
+        # within that rounding of the threshold may be judged differently, so the stop may move by the
+        # length of one stall run.  When it does not move, the scores must agree.
+        assert abs(done - ref_done) <= (k + 1) * spe, (tol_, k, done // spe, ref_done // spe)
+        if done == ref_done:
+            assert abs(pf[0, f, 0].item() - ref["scores"][0]) < (5 if dtype else 1) * ABS_SCORE, (tol_, k)
+        stops.append(done // spe)
+    assert stops[0] < E and stops[2] == E  # the first rule does stop early; the switched-off rule never does
+
+
 # ----------------------------------------------------------- final scores ----
 
 def explained_flips(acc_gpu, acc_ref, n_va):
