@@ -54,7 +54,7 @@ constexpr int TB_ROWS = 256;  // rows per chunk
 constexpr int TB_PAD = 8;     // pad elements per LDS row: consecutive rows start 4 banks apart
 constexpr int TB_MAXL = 3;    // weight layers
 constexpr int TB_MAXU = 256;  // padded units per level
-constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns rows 32w..32w+31 in the row phases
+constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns rows 32w..32w+31 in the output layer and the spills
 constexpr int TB_THREADS = 64 * TB_WAVES;
 constexpr int TB_STATE_AHEAD = 2;  // tiles of optimizer state in flight per wave
 constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 1024;  // dynamic LDS available to the kernel
