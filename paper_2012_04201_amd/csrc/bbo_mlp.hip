@@ -973,15 +973,15 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     hipLaunchKernelGGL(k_train_tiled, dim3(pl.n_slots), dim3(TB_THREADS), pl.lds_bytes, s, P);
   } else if (pl.small) {
     const int kt = d + 1 <= 16 ? 1 : (d + 1 <= 32 ? 2 : 4);
-    const void* fn = kt == 1 ? (const void*)k_train_small<1>
-                             : (kt == 2 ? (const void*)k_train_small<2> : (const void*)k_train_small<4>);
-    HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
-    if (kt == 1)
-      hipLaunchKernelGGL(k_train_small<1>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
-    else if (kt == 2)
-      hipLaunchKernelGGL(k_train_small<2>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
-    else
-      hipLaunchKernelGGL(k_train_small<4>, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
+    const int c_out = n_classes >= 2 ? n_classes : 1, co = c_out <= 2 ? c_out : 4;
+    typedef void (*small_fn)(const TrainParams);
+    static const small_fn fns[3][3] = {
+        {k_train_small<1, 1>, k_train_small<1, 2>, k_train_small<1, 4>},
+        {k_train_small<2, 1>, k_train_small<2, 2>, k_train_small<2, 4>},
+        {k_train_small<4, 1>, k_train_small<4, 2>, k_train_small<4, 4>}};
+    const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
+    HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
+    hipLaunchKernelGGL(fn, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
   } else if (dtype == BBO_F32)
     hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
   else

@@ -110,7 +110,9 @@ struct ChunkPos {
   int e, st, c0;
 };
 
-template <int KT>
+// KT: 16-wide k tiles of the input layer (inputs + bias).  CO: output slots in use (1, 2 or 4); 1 and 2 are
+// exact output counts, 4 serves 3 or 4 outputs.
+template <int KT, int CO>
 struct Small {
   static constexpr int K0 = 16 * KT, RSTEP = SM_THREADS / K0, NX = SM_RC / RSTEP;
   const TrainParams& P;
@@ -218,7 +220,7 @@ struct Small {
     const int nut = y.HP / 16, ldw = y.ldw;
     const float* s = f(y.o_xs);
     const float* w1 = f(y.o_w1);
-    const bool c2 = y.c >= 2, c4 = y.c >= 3;
+    constexpr bool c2 = CO >= 2, c4 = CO >= 4;
 #pragma unroll
     for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -290,7 +292,7 @@ struct Small {
   // ---- phase 2a: outputs, loss and output delta of all 64 rows (lane = row), per wave ----
   template <bool TRAIN>
   __device__ __forceinline__ void outputs(int par, int rows, float inv_mb, double& lsum, double& hits, f32x4& gb2) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = y.c;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = CO <= 2 ? CO : y.c;
     const float* zp = f(y.o_zp);
     const f32x4 b2 = *(const f32x4*)(f(y.o_w2) + y.HP * 4);
     float z0 = b2[0], z1 = b2[1], z2 = b2[2], z3 = b2[3];
@@ -313,7 +315,7 @@ struct Small {
         float mx = z[0], zy = z[0];
         int best = 0;
 #pragma unroll
-        for (int cc = 1; cc < 4; cc++)
+        for (int cc = 1; cc < CO; cc++)
           if (cc < c) {
             if (z[cc] > mx) {
               mx = z[cc];
@@ -323,14 +325,14 @@ struct Small {
           }
         float se = 0.f;
 #pragma unroll
-        for (int cc = 0; cc < 4; cc++)
+        for (int cc = 0; cc < CO; cc++)
           if (cc < c) se += expf(z[cc] - mx);
         const float lse = mx + logf(se);
         l = (double)(lse - zy);
         hit = best == yr ? 1.0 : 0.0;
         if (TRAIN) {
 #pragma unroll
-          for (int cc = 0; cc < 4; cc++)
+          for (int cc = 0; cc < CO; cc++)
             if (cc < c) dl[cc] = (expf(z[cc] - lse) - (cc == yr ? 1.f : 0.f)) * inv_mb;
         }
       } else {
@@ -348,7 +350,7 @@ struct Small {
       *(f32x4*)(f(y.o_d2) + (w * SM_RC + lane) * 4) = dl;
       if (w == 0) {
 #pragma unroll
-        for (int cc = 0; cc < 4; cc++) gb2[cc] += dl[cc];
+        for (int cc = 0; cc < CO; cc++) gb2[cc] += dl[cc];
       }
       // the wave reads back what its other lanes wrote: LDS executes a wave's accesses in order
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -361,7 +363,7 @@ struct Small {
     const int nut = y.HP / 16, lda = y.lda;
     const float* t = xt(par);
     const float* d2 = f(y.o_d2) + w * SM_RC * 4;
-    const bool c2 = y.c >= 2, c4 = y.c >= 3;
+    constexpr bool c2 = CO >= 2, c4 = CO >= 4;
     f32x4 w2r[4];
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -407,7 +409,7 @@ struct Small {
   // ---- optimizer step: gradients (and hidden moments) in registers, weights in LDS ----
   __device__ __forceinline__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&g2p)[4], f32x4 gb2, float* rec) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h, c = y.c;
+    const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h, c = CO <= 2 ? CO : y.c;
     float* w1 = f(y.o_w1);
     float* m1 = m1g();
     float* v1 = v1g();
@@ -461,7 +463,7 @@ struct Small {
 #pragma unroll
     for (int i = 0; i < 4; i++)
 #pragma unroll
-      for (int cc = 0; cc < 4; cc++) {
+      for (int cc = 0; cc < CO; cc++) {
         float v = g2p[i][cc];
         v += __shfl_xor(v, 16);
         v += __shfl_xor(v, 32);
@@ -469,7 +471,7 @@ struct Small {
       }
     if (w == 0) {
 #pragma unroll
-      for (int cc = 0; cc < 4; cc++) {
+      for (int cc = 0; cc < CO; cc++) {
         float v = gb2[cc];
 #pragma unroll
         for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s);
@@ -489,7 +491,7 @@ struct Small {
         float* v2 = f(y.o_v2) + u * 4;
         f32x4 wv = *(const f32x4*)w2, mv = *(const f32x4*)m2, vv = *(const f32x4*)v2;
 #pragma unroll
-        for (int cc = 0; cc < 4; cc++)
+        for (int cc = 0; cc < CO; cc++)
           if (cc < c) {
             float wr = wv[cc], mr = mv[cc], vr = vv[cc];
             const float gg = isb ? g[cc] : g[cc] + oc.am * wr;
@@ -700,7 +702,7 @@ struct Small {
   }
 };
 
-template <int KT>
+template <int KT, int CO>
 __global__ __launch_bounds__(SM_THREADS, 2) void k_train_small(const TrainParams P) {
   extern __shared__ __align__(16) char smem[];
   __shared__ int s_item;
@@ -712,7 +714,7 @@ __global__ __launch_bounds__(SM_THREADS, 2) void k_train_small(const TrainParams
     const int item = __builtin_amdgcn_readfirstlane(s_item);
     if (item >= P.n_items) break;
     const SItem* __restrict__ si = (const SItem*)P.items + item;
-    Small<KT> T{P, si->d, si->y, smem, P.slots + (uint64_t)blockIdx.x * P.slot_bytes, red};
+    Small<KT, CO> T{P, si->d, si->y, smem, P.slots + (uint64_t)blockIdx.x * P.slot_bytes, red};
     T.run();
   }
 }
