@@ -21,16 +21,18 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
-KERNEL_SOURCES = ["bbo_mlp.hip", "common.h", "train_tiled_bf16.h", "train_small_f32.h"]
+# the sources each workload's training kernel is built from (the host code in bbo_mlp.hip does not count)
+KERNEL_SOURCES = {"k_train_tiled": ["common.h", "train_tiled_bf16.h"], "k_train_small": ["common.h", "train_small_f32.h"],
+                  "k_train": ["common.h", "bbo_mlp.hip"]}
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
-def kernel_source_hash():
-    """Hash of the kernel sources' code: comments and white space do not count, so that a reworded
-    comment does not void the counter record."""
+def kernel_source_hash(kernel):
+    """Hash of the code of one training kernel's sources: comments and white space do not count, so that a
+    reworded comment does not void the counter record."""
     import re
     h = hashlib.sha256()
-    for name in KERNEL_SOURCES:
+    for name in KERNEL_SOURCES[kernel]:
         with open(os.path.join(ROOT, "paper_2012_04201_amd", "csrc", name), "r") as fh:
             text = fh.read()
         text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
@@ -39,9 +41,9 @@ def kernel_source_hash():
     return h.hexdigest()[:16]
 
 
-def measured_traffic(workload):
+def measured_traffic(workload, kernel):
     """HBM bytes per launch from the committed rocprofv3 counter runs; None when
-    there is no record for this workload or the kernel sources changed since."""
+    there is no record for this workload or the kernel's sources changed since."""
     if not os.path.exists(TRAFFIC_FILE):
         return None
     rec = {}
@@ -50,7 +52,7 @@ def measured_traffic(workload):
         if "=" in line:
             k, v = line.split("=", 1)
             rec[k.strip()] = v.strip()
-    if rec.get(workload + ".source_hash") != kernel_source_hash():
+    if rec.get(workload + ".source_hash") != kernel_source_hash(kernel):
         return None
     try:
         return float(rec[workload + ".bytes_per_launch"])
@@ -141,7 +143,7 @@ def run_workload(idx, steps, warmup, suggestions=0, epochs=0):
     kernel = "k_train_tiled" if dt else ("k_train_small" if idx in (0, 2, 3) else "k_train")
     tflops = flops / per_step / 1e12
     abytes = algorithmic_bytes(cfg)
-    traffic = measured_traffic(cfg["name"])
+    traffic = measured_traffic(cfg["name"], kernel)
     mfma = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_TFLOPS[dname], "unit": "TFLOP/s",
             "frac": flops / kern_s / 1e12 / PEAK_TFLOPS[dname], "traffic": traffic, "kernel": kernel,
             "kernel_ms": kern_s * 1e3}
