@@ -294,92 +294,109 @@ struct Tiled {
   }
 
   // ---- hidden layers, forward and data gradient: wave w owns units 32w..32w+31 of the level it produces ----
-  // acc[ub][jb] = sum_k A[(2w+ub)*16 + .][k] * level[16jb + .][k] for all 16 row tiles jb; the weights A
-  // (tile-blocked in global) are read once per workgroup, the level comes from the buffer.  The lane ends up
-  // with units (2w+ub)*16+4q..+3 of row 16jb+li.  The results stay in registers until every wave has read the
-  // level, then overwrite it.
-  // TR = false: A is the [out][in] copy and the wave produces out units (forward).  TR = true: A is the same
-  // copy but the wave produces in units (data gradient), so each pair of 16 x 16 tiles it fetches passes
-  // through the wave's LDS staging patch and comes back through the transposing read; mt_a = in tiles of A.
+  // The wave's weight operands for a hidden-layer product: two unit tiles x up to 8 k blocks of the [out][in]
+  // copy A, all fetched at once (one exposed latency per layer, exact waits afterwards).  TR = false: the wave
+  // produces out units (forward).  TR = true: it produces in units (data gradient) and needs the transpose of
+  // the same tiles: lanes 0..31 fetch the tile of out tile 2kb, lanes 32..63 that of out tile 2kb + 1, and each
+  // pair passes through the wave's LDS staging patch and comes back through the transposing read; mt_a = in
+  // tiles of A.
   template <bool TR>
-  __device__ __forceinline__ void gemm_unitsplit(const __bf16* __restrict__ A, int kbn, int mt_a,
-                                                 f32x4 (&acc)[2][16]) const {
+  __device__ __forceinline__ void gemm_operands(const __bf16* __restrict__ A, int kbn, int mt_a, i32x4 (&ar)[8][2]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    // (TR: lanes 0..31 fetch the tile of out tile 2kb, lanes 32..63 that of out tile 2kb + 1)
     const __bf16* A0 = TR ? A + ((size_t)(lane >> 5) * mt_a + 2 * w) * 256 + (lane & 31) * 8
                           : A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
     const __bf16* A1 = A0 + (TR ? (size_t)256 : (size_t)kbn * 512);
     const size_t kstep = TR ? (size_t)mt_a * 512 : (size_t)512;
-    char* patch = lds + y.lds_stage + w * 2048;
-    auto operand = [&](const i32x4& raw, int ub) {
-      if (!TR) return as_bf16x8(raw);
-      *(i32x4*)(patch + ub * 1024 + lane * 16) = raw;
-      return lds_operand_tr(patch + ub * 1024, 16, 0, 0, li, q);
-    };
-    // all weight operands of the wave (two unit tiles x up to 8 k blocks) are fetched up front: one
-    // exposed latency per layer, and the waits inside the sweep are exact
-    i32x4 ar[8][2];
 #pragma unroll
     for (int kb = 0; kb < 8; kb++)
       if (kb < kbn) {
         ar[kb][0] = *(const i32x4*)(A0 + (size_t)kb * kstep);
         ar[kb][1] = *(const i32x4*)(A1 + (size_t)kb * kstep);
       }
-    const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2;
-    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    if (TR) {
+      char* patch = lds + y.lds_stage + w * 2048;
 #pragma unroll
-    for (int jb = 0; jb < 16; jb++) {
-      acc[0][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-      acc[1][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int kb = 0; kb < 8; kb++)
+        if (kb < kbn) {
+#pragma unroll
+          for (int ub = 0; ub < 2; ub++) {
+            *(i32x4*)(patch + ub * 1024 + lane * 16) = ar[kb][ub];
+            ar[kb][ub] = as_i32x4(lds_operand_tr(patch + ub * 1024, 16, 0, 0, li, q));
+          }
+        }
     }
-    // All 16 row tiles are multiplied whatever the chunk holds: tiles past the rows in use only cost
-    // arithmetic on stale buffer contents, and the callers never store their results.
+  }
+
+  // acc[ub][j] = sum_k A[(2w+ub)*16 + .][k] * level[128 half + 16j + .][k] for the 8 row tiles of one half of
+  // the chunk.  The lane ends up with units (2w+ub)*16+4q..+3 of row 128 half + 16j + li.  All 8 tiles are
+  // multiplied whatever the chunk holds: tiles past the rows in use only cost arithmetic on stale buffer
+  // contents, and the callers never store their results.
+  __device__ __forceinline__ void gemm_half(const i32x4 (&ar)[8][2], int kbn, int half, f32x4 (&acc)[2][8]) const {
+    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
+    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2 + half * 8 * tile_bytes;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      acc[0][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc[1][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
     for (int kb = 0; kb < 8; kb++)
       if (kb < kbn) {
-        const bf16x8 o0 = operand(ar[kb][0], 0), o1 = operand(ar[kb][1], 1);
+        const bf16x8 o0 = as_bf16x8(ar[kb][0]), o1 = as_bf16x8(ar[kb][1]);
 #pragma unroll
-        for (int jb = 0; jb < 16; jb++) {
-          const bf16x8 b = *(const bf16x8*)(bp + jb * tile_bytes + kb * 64);
-          acc[0][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][jb], 0, 0, 0);
-          acc[1][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][jb], 0, 0, 0);
+        for (int j = 0; j < 8; j++) {
+          const bf16x8 b = *(const bf16x8*)(bp + j * tile_bytes + kb * 64);
+          acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][j], 0, 0, 0);
+          acc[1][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][j], 0, 0, 0);
         }
       }
   }
 
-  // Hidden layer l: level l -> level l+1 in place; the ReLU pattern of the wave's units goes to `bits`
-  // (bit 4*(16*ub + jb) + r).  Called by all waves.
+  // Hidden layer l: level l -> level l+1 in place, the chunk's two halves of 128 rows one after the other: a
+  // half's results stay in registers until every wave has read that half, and are written while the other
+  // half is read.  The ReLU pattern of the wave's units goes to `bits` (bit 4*(16*ub + jb) + r).  Called by
+  // all waves.
   __device__ __forceinline__ void forward_hidden(int l, int par, int njb, uint32_t (&bits)[4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const bool active = 32 * w < y.UP[l + 1];
-    f32x4 acc[2][16];
-    if (active)
-      gemm_unitsplit<false>(bp(y.oi[l][par]), y.UP[l] / 32, 0, acc);
-    __syncthreads();
+    const int kbn = y.UP[l] / 32;
+    const float* bias = fp(y.bias[l]);
+    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    i32x4 ar[8][2];
+    f32x4 bv[2];
     if (active) {
-      const float* bias = fp(y.bias[l]);
-      char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2;
-      const size_t tile_bytes = (size_t)16 * y.S * 2;
+      gemm_operands<false>(bp(y.oi[l][par]), kbn, 0, ar);
 #pragma unroll
-      for (int i = 0; i < 4; i++) bits[i] = 0;
-#pragma unroll
-      for (int ub = 0; ub < 2; ub++) {
-        const f32x4 bv = *(const f32x4*)(bias + 32 * w + 16 * ub + 4 * q);
-#pragma unroll
-        for (int jb = 0; jb < 16; jb++)
-          if (jb < njb) {
-            bf16x4 pk;
-            uint32_t nib = 0;
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-              pk[r] = (__bf16)fmaxf(acc[ub][jb][r] + bv[r], 0.f);
-              nib |= ((float)pk[r] > 0.f ? 1u : 0u) << r;
-            }
-            *(bf16x4*)(b + jb * tile_bytes + ub * 32) = pk;
-            bits[ub * 2 + (jb >> 3)] |= nib << ((jb & 7) * 4);
-          }
-      }
+      for (int ub = 0; ub < 2; ub++) bv[ub] = *(const f32x4*)(bias + 32 * w + 16 * ub + 4 * q);
     }
+#pragma unroll
+    for (int i = 0; i < 4; i++) bits[i] = 0;
+#pragma unroll
+    for (int half = 0; half < 2; half++)
+      if (half * 8 < njb) {
+        f32x4 acc[2][8];
+        if (active) gemm_half(ar, kbn, half, acc);
+        __syncthreads();
+        if (active) {
+          char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2 + half * 8 * tile_bytes;
+#pragma unroll
+          for (int ub = 0; ub < 2; ub++)
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+              if (half * 8 + j < njb) {
+                bf16x4 pk;
+                uint32_t nib = 0;
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                  pk[r] = (__bf16)fmaxf(acc[ub][j][r] + bv[ub][r], 0.f);
+                  nib |= ((float)pk[r] > 0.f ? 1u : 0u) << r;
+                }
+                *(bf16x4*)(b + j * tile_bytes + ub * 32) = pk;
+                bits[ub * 2 + half] |= nib << (j * 4);
+              }
+        }
+      }
     __syncthreads();
   }
 
@@ -414,17 +431,23 @@ struct Tiled {
         }
       }
     } else {
-      f32x4 acc[2][16];
-      if (active)
-        gemm_unitsplit<true>(bp(y.oi[l][par]), y.UP[l + 1] / 32, y.UP[l] / 16, acc);
-      __syncthreads();
-      if (active) {
+      const int kbn = y.UP[l + 1] / 32;
+      i32x4 ar[8][2];
+      if (active) gemm_operands<true>(bp(y.oi[l][par]), kbn, y.UP[l] / 16, ar);
 #pragma unroll
-        for (int ub = 0; ub < 2; ub++)
+      for (int half = 0; half < 2; half++)
+        if (half * 8 < njb) {
+          f32x4 acc[2][8];
+          if (active) gemm_half(ar, kbn, half, acc);
+          __syncthreads();
+          if (active) {
 #pragma unroll
-          for (int jb = 0; jb < 16; jb++)
-            if (jb < njb) put(acc[ub][jb], ub, jb);
-      }
+            for (int ub = 0; ub < 2; ub++)
+#pragma unroll
+              for (int j = 0; j < 8; j++)
+                if (half * 8 + j < njb) put(acc[ub][j], ub, half * 8 + j);
+          }
+        }
     }
     __syncthreads();
   }
