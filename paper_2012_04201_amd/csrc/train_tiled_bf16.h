@@ -776,9 +776,194 @@ struct Tiled {
     }
   }
 
+  // The same for the common case: a layer below the last one, the whole minibatch in one full chunk (all 8
+  // row blocks).  Straight-line code per tile, so that the waits on memory are exact and the optimizer state
+  // really is in flight TB_STATE_AHEAD tiles ahead: the in x out tiles of the layer are numbered in-tile-major
+  // and each wave takes one contiguous eighth of them (its state is one contiguous stream per array, its
+  // activation operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the
+  // bias tiles (ones operand) are dealt round-robin and their state is fetched before anything else.  Pad
+  // elements of edge tiles keep their zeros through selects, not branches.
+  template <bool ADAM>
+  __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
+    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float* W = fp(y.w[l]);
+    float* Mo = fp(y.m[l]);
+    float* Vo = fp(y.v[l]);
+    float* bias = fp(y.bias[l]);
+    float* bm = fp(y.bm[l]);
+    float* bv = fp(y.bv[l]);
+    __bf16* oi = bp(y.oi[l][par_next]);
+    const __bf16* T = bp(y.T[l]);
+    const int fi = y.U[l], fo = y.U[l + 1], S = y.S;
+    const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Mr = (fi + 15) / 16, Ne = (fo + 15) / 16;
+    const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
+    const int TT = Mr * Ne, t0 = w * TT / TB_WAVES, t1 = (w + 1) * TT / TB_WAVES;
+    constexpr int D = TB_STATE_AHEAD;
+    struct St {
+      f32x4 w, m, v;
+    };
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the lane's delta operand of out tile 0, row block 0: rows 8q + li/4 (+4), units 4 (li%4)..
+    const char* bl = buf() + ((size_t)(8 * q + (li >> 2)) * S + 4 * (li & 3)) * 2;
+    const size_t kbs = (size_t)32 * S * 2, hs = (size_t)4 * S * 2;
+    auto delta_operands = [&](int nt, bf16x8(&b)[8]) {
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++) {
+        union {
+          struct {
+            s16x4 lo, hi;
+          } s;
+          bf16x8 v;
+        } u;
+        u.s.lo = lds_read_tr(bl + nt * 32 + kb * kbs);
+        u.s.hi = lds_read_tr(bl + nt * 32 + kb * kbs + hs);
+        b[kb] = u.v;
+      }
+    };
+    // bias state of the wave's bias tiles (out tiles w and w + 8)
+    float bw_[2], bm_[2], bv_[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int j = min(w + 8 * i, Ne - 1) * 16 + li;
+      bw_[i] = bias[j];
+      bm_[i] = bm[j];
+      bv_[i] = ADAM ? bv[j] : 0.f;
+    }
+    if (t1 > t0) {
+      auto load_a = [&](int mt, i32x4(&a)[8]) {
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++) a[kb] = *(const i32x4*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+      };
+      auto load_st = [&](int mt, int nt, St& s) {
+        const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
+        s.w = __builtin_nontemporal_load((const f32x4*)(W + o));
+        s.m = __builtin_nontemporal_load((const f32x4*)(Mo + o));
+        if (ADAM) s.v = __builtin_nontemporal_load((const f32x4*)(Vo + o));
+      };
+      int mt = t0 / Ne, nt = t0 - mt * Ne;  // the tile being worked on
+      int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next; stops at the wave's last tile
+      auto advance_fetch = [&]() {
+        const int step = pt < t1 - 1 ? 1 : 0;
+        pt += step;
+        pn += step;
+        const int wrap = pn == Ne ? 1 : 0;
+        pn = wrap ? 0 : pn;
+        pm += wrap;
+      };
+      St st[D + 1];
+#pragma unroll
+      for (int k = 0; k <= D; k++) st[k] = St{zero4, zero4, zero4};
+      i32x4 a[8], an[8];
+      load_a(mt, a);
+#pragma unroll
+      for (int k = 0; k < D; k++) {
+        load_st(pm, pn, st[k]);
+        advance_fetch();
+      }
+      const int mt_last = (t1 - 1) / Ne;
+      load_a(min(mt + 1, mt_last), an);
+      auto tile = [&](St& cur, St& pre) __attribute__((always_inline)) {
+        load_st(pm, pn, pre);
+        advance_fetch();
+        bf16x8 b[8];
+        delta_operands(nt, b);
+        f32x4 g = zero4;
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[kb]), b[kb], g, 0, 0, 0);
+        // the lane holds in units i0..i0+3 of out unit j
+        const int j = nt * 16 + li, i0 = mt * 16 + 4 * q;
+        const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
+        f32x4 wv = cur.w, mv = cur.m, vv = cur.v, gv;
+        bf16x4 pk;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          float wr = wv[r], mr = mv[r], vr = vv[r];
+          gv[r] = g[r] + oc.am * wr;
+          opt_update(oc, gv[r], wr, mr, vr);
+          const bool real = j < fo && i0 + r < fi;
+          wv[r] = real ? wr : wv[r];
+          mv[r] = real ? mr : mv[r];
+          vv[r] = real ? vr : vv[r];
+          pk[r] = (__bf16)wv[r];
+        }
+        __builtin_nontemporal_store(wv, (f32x4*)(W + o));
+        __builtin_nontemporal_store(mv, (f32x4*)(Mo + o));
+        if (ADAM) __builtin_nontemporal_store(vv, (f32x4*)(Vo + o));
+        *(bf16x4*)(oi + ((size_t)nt * Mt + mt) * 256 + li * 16 + 4 * q) = pk;
+        if (rec) {
+#pragma unroll
+          for (int r = 0; r < 4; r++)
+            if (j < fo && i0 + r < fi) {
+              const int ci = cw + (i0 + r) * fo + j;
+              rec[1 + ci] = gv[r];
+              rec[1 + Pn + ci] = wv[r];
+            }
+        }
+        nt++;
+        if (nt == Ne) {  // on to the next in tile: its operand has been in flight since the last change
+          nt = 0;
+          mt++;
+          // register moves written out: the prefetched operand's registers are free before the next fetch
+          // is issued, so the fetch lands in them directly instead of in temporaries that must be waited for
+#pragma unroll
+          for (int kb = 0; kb < 8; kb++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) asm volatile("v_mov_b32 %0, %1" : "=v"(a[kb][e]) : "v"(an[kb][e]));
+          load_a(min(mt + 1, mt_last), an);
+        }
+      };
+      // the only way back to the top is through all D + 1 tile bodies: a wait placed in one of them can count
+      // on the memory operations of all the others
+      for (int t = t0;;) {
+        bool done = false;
+#pragma unroll
+        for (int k = 0; k <= D; k++)
+          if (!done) {
+            tile(st[k], st[(k + D) % (D + 1)]);
+            done = ++t == t1;
+          }
+        if (done) break;
+      }
+    }
+    // bias gradient: the column sums of the delta, through a row of ones
+    const int ones = li == 0 ? 0x3F803F80 : 0;  // two bf16 ones
+    const bf16x8 a1 = as_bf16x8(i32x4{ones, ones, ones, ones});
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      const int nt = w + 8 * i;
+      if (nt < Ne) {
+        bf16x8 b[8];
+        delta_operands(nt, b);
+        f32x4 g = zero4;
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b[kb], g, 0, 0, 0);
+        const int j = nt * 16 + li;
+        if (q == 0 && j < fo) {  // r = 0 of lane group 0 holds the bias gradient of out unit j
+          float wr = bw_[i], mr = bm_[i], vr = bv_[i];
+          opt_update(oc, g[0], wr, mr, vr);
+          if (rec) {
+            rec[1 + cb + j] = g[0];
+            rec[1 + Pn + cb + j] = wr;
+          }
+          bias[j] = wr;
+          bm[j] = mr;
+          if (ADAM) bv[j] = vr;
+        }
+      }
+    }
+  }
+
   __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                         float* rec) const {
-    wgrad_t(l, KB, first, last, oc, par_next, rec);
+    if (first && last && KB == 8 && l + 1 < y.L) {
+      if (oc.adam)
+        wgrad_stream<true>(l, oc, par_next, rec);
+      else
+        wgrad_stream<false>(l, oc, par_next, rec);
+    } else {
+      wgrad_t(l, KB, first, last, oc, par_next, rec);
+    }
     __syncthreads();
   }
 
