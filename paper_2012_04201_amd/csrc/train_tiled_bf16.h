@@ -58,14 +58,25 @@ constexpr int TB_WAVES = 8;   // waves per workgroup (2 per SIMD); wave w owns r
 constexpr int TB_THREADS = 64 * TB_WAVES;
 constexpr int TB_STATE_AHEAD = 2;  // tiles of optimizer state in flight per wave
 constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 1024;  // dynamic LDS available to the kernel
+// The LDS layout is the same for every model (sized for the widest): the row stride and every offset are
+// compile-time constants, so LDS addresses need no arithmetic beyond the lane's base.
+constexpr int TB_S = TB_MAXU + TB_PAD;                        // LDS row stride in elements
+constexpr uint32_t TB_LDS_BUF = 0;                            // buf[row][unit]
+constexpr uint32_t TB_LDS_ROWS = TB_LDS_BUF + TB_ROWS * TB_S * 2;  // row list of the chunk
+// 16 KB that serve as: output delta (8 KB) + a 16 x 16 bf16 patch per wave (4 KB) from the output layer to
+// the last weight gradient, and in between as 2 KB per wave of weight staging for the hidden data gradient
+constexpr uint32_t TB_LDS_STAGE = TB_LDS_ROWS + TB_ROWS * 4;
+constexpr uint32_t TB_LDS_DELTA = TB_LDS_STAGE;
+constexpr uint32_t TB_LDS_TR = TB_LDS_STAGE + TB_ROWS * 16 * 2;
+constexpr uint32_t TB_LDS_TOTAL = TB_LDS_STAGE + TB_WAVES * 2048;
+static_assert(TB_LDS_TOTAL <= TB_LDS_LIMIT, "LDS layout does not fit");
 
 struct TLay {
   int32_t L;
   int32_t U[TB_MAXL + 1];   // units per level: inputs, hidden..., outputs
   int32_t UP[TB_MAXL + 1];  // padded to 32 (levels < L) or 16 (outputs)
-  int32_t S;                // LDS row stride in elements
   int32_t cw[TB_MAXL], cb[TB_MAXL], P;
-  uint32_t lds_buf, lds_delta, lds_rows, lds_tr, lds_stage, lds_total;
+  uint32_t lds_total;
   uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL][2], io[2], T[TB_MAXL];
   uint64_t bias[TB_MAXL], bm[TB_MAXL], bv[TB_MAXL], bg[TB_MAXL], total;  // bias: value, moments, partial gradient
 };
@@ -80,11 +91,9 @@ __host__ __device__ inline bool tiled_eligible(const int32_t* dims, int L) {
 
 __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
   y.L = L;
-  y.S = 0;
   for (int u = 0; u <= L; u++) {
     y.U[u] = dims[u];
     y.UP[u] = u < L ? rup(dims[u], 32) : 16;
-    if (u < L && y.UP[u] + TB_PAD > y.S) y.S = y.UP[u] + TB_PAD;
   }
   int c = 0;
   for (int l = 0; l < L; l++) {
@@ -94,18 +103,7 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
     c += dims[l + 1];
   }
   y.P = c;
-  uint32_t lo = 0;
-  y.lds_buf = lo;
-  lo += TB_ROWS * y.S * 2;
-  y.lds_rows = lo;
-  lo += TB_ROWS * 4;
-  // 16 KB that serve as: output delta (8 KB) + a 16 x 16 bf16 patch per wave (4 KB) from the output layer to
-  // the last weight gradient, and in between as 2 KB per wave of weight staging for the hidden data gradient
-  y.lds_stage = lo;
-  y.lds_delta = lo;
-  y.lds_tr = lo + TB_ROWS * 16 * 2;
-  lo += TB_WAVES * 2048;
-  y.lds_total = lo;
+  y.lds_total = TB_LDS_TOTAL;
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint64_t o = off;
@@ -192,9 +190,9 @@ struct Tiled {
 
   __device__ __forceinline__ float* fp(uint64_t off) const { return (float*)(slot + off); }
   __device__ __forceinline__ __bf16* bp(uint64_t off) const { return (__bf16*)(slot + off); }
-  __device__ __forceinline__ char* buf() const { return lds + y.lds_buf; }
-  __device__ __forceinline__ char* dbuf() const { return lds + y.lds_delta; }
-  __device__ __forceinline__ int32_t* rowlist() const { return (int32_t*)(lds + y.lds_rows); }
+  __device__ __forceinline__ char* buf() const { return lds + TB_LDS_BUF; }
+  __device__ __forceinline__ char* dbuf() const { return lds + TB_LDS_DELTA; }
+  __device__ __forceinline__ int32_t* rowlist() const { return (int32_t*)(lds + TB_LDS_ROWS); }
 
   // ---- blocked indices ------------------------------------------------------
   // state element (in unit k, out unit j) of layer l
@@ -269,7 +267,7 @@ struct Tiled {
     for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x)
       rl[p] = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
     __syncthreads();
-    const int d = y.U[0], up0 = y.UP[0], S = y.S, vpr = up0 / 8;  // 16-byte vectors per row
+    const int d = y.U[0], up0 = y.UP[0], S = TB_S, vpr = up0 / 8;  // 16-byte vectors per row
     char* b0 = buf();
     const __bf16* X = (const __bf16*)P.X;
     for (int idx = threadIdx.x; idx < TB_ROWS * vpr; idx += blockDim.x) {
@@ -288,7 +286,7 @@ struct Tiled {
     __bf16* T = bp(y.T[l]);
     const int mta = y.UP[l] / 16;
     for (int mt = 0; mt < mta; mt++) {
-      const bf16x8 v = lds_operand_tr(buf(), y.S, 32 * w, mt * 16, li, q);
+      const bf16x8 v = lds_operand_tr(buf(), TB_S, 32 * w, mt * 16, li, q);
       *(bf16x8*)(T + (((size_t)mt * 8 + w) * 16 + li) * 32 + q * 8) = v;
     }
   }
@@ -314,7 +312,7 @@ struct Tiled {
         ar[kb][1] = *(const i32x4*)(A1 + (size_t)kb * kstep);
       }
     if (TR) {
-      char* patch = lds + y.lds_stage + w * 2048;
+      char* patch = lds + TB_LDS_STAGE + w * 2048;
 #pragma unroll
       for (int kb = 0; kb < 8; kb++)
         if (kb < kbn) {
@@ -333,8 +331,8 @@ struct Tiled {
   // contents, and the callers never store their results.
   __device__ __forceinline__ void gemm_half(const i32x4 (&ar)[8][2], int kbn, int half, f32x4 (&acc)[2][8]) const {
     const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
-    const size_t tile_bytes = (size_t)16 * y.S * 2;
-    const char* bp = buf() + ((size_t)li * y.S + q * 8) * 2 + half * 8 * tile_bytes;
+    const size_t tile_bytes = (size_t)16 * TB_S * 2;
+    const char* bp = buf() + ((size_t)li * TB_S + q * 8) * 2 + half * 8 * tile_bytes;
 #pragma unroll
     for (int j = 0; j < 8; j++) {
       acc[0][j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -344,12 +342,17 @@ struct Tiled {
     for (int kb = 0; kb < 8; kb++)
       if (kb < kbn) {
         const bf16x8 o0 = as_bf16x8(ar[kb][0]), o1 = as_bf16x8(ar[kb][1]);
+        // all 8 level operands of the k block are requested before the first product waits for one
+        bf16x8 b[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) b[j] = *(const bf16x8*)(bp + j * tile_bytes + kb * 64);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-          const bf16x8 b = *(const bf16x8*)(bp + j * tile_bytes + kb * 64);
-          acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b, acc[0][j], 0, 0, 0);
-          acc[1][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b, acc[1][j], 0, 0, 0);
+          acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o0, b[j], acc[0][j], 0, 0, 0);
+          acc[1][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o1, b[j], acc[1][j], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);  // 8 LDS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // 16 MFMA
       }
   }
 
@@ -362,7 +365,7 @@ struct Tiled {
     const bool active = 32 * w < y.UP[l + 1];
     const int kbn = y.UP[l] / 32;
     const float* bias = fp(y.bias[l]);
-    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    const size_t tile_bytes = (size_t)16 * TB_S * 2;
     i32x4 ar[8][2];
     f32x4 bv[2];
     if (active) {
@@ -379,7 +382,7 @@ struct Tiled {
         if (active) gemm_half(ar, kbn, half, acc);
         __syncthreads();
         if (active) {
-          char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2 + half * 8 * tile_bytes;
+          char* b = buf() + ((size_t)li * TB_S + 32 * w + 4 * q) * 2 + half * 8 * tile_bytes;
 #pragma unroll
           for (int ub = 0; ub < 2; ub++)
 #pragma unroll
@@ -405,8 +408,8 @@ struct Tiled {
   __device__ __forceinline__ void backward_data(int l, int par, int njb, const uint32_t (&bits)[4]) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const bool active = 32 * w < y.UP[l];
-    char* b = buf() + ((size_t)li * y.S + 32 * w + 4 * q) * 2;
-    const size_t tile_bytes = (size_t)16 * y.S * 2;
+    char* b = buf() + ((size_t)li * TB_S + 32 * w + 4 * q) * 2;
+    const size_t tile_bytes = (size_t)16 * TB_S * 2;
     auto put = [&](const f32x4& acc, int ub, int jb) {
       const uint32_t nib = bits[ub * 2 + (jb >> 3)] >> ((jb & 7) * 4);
       bf16x4 pk;
@@ -466,8 +469,8 @@ struct Tiled {
       const int kbn = y.UP[l] / 32;
       f32x4 accs[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
       const __bf16* Ap = A + opnd_lane(li, q);
-      const char* bq = buf() + ((size_t)(32 * w + li) * y.S + q * 8) * 2;
-      const size_t tile_bytes = (size_t)16 * y.S * 2;
+      const char* bq = buf() + ((size_t)(32 * w + li) * TB_S + q * 8) * 2;
+      const size_t tile_bytes = (size_t)16 * TB_S * 2;
       bf16x8 a[8];
 #pragma unroll
       for (int kb = 0; kb < 8; kb++)
@@ -571,11 +574,11 @@ struct Tiled {
     const __bf16* T = bp(y.T[l]);
     const int fi = y.U[l], fo = y.U[l + 1];
     const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Me = (fi + 15) / 16 + 1, Ne = (fo + 15) / 16;
-    char* trp = lds + y.lds_tr + w * 512;
+    char* trp = lds + TB_LDS_TR + w * 512;
     const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
     const bool lastlayer = l + 1 == y.L;  // its activation operand is still in the buffer, its delta in dbuf
     const char* Bl = lastlayer ? dbuf() : buf();
-    const int ldb = lastlayer ? 16 : y.S;
+    const int ldb = lastlayer ? 16 : TB_S;
     const bool adam = oc.adam;
     // number of runs the out tiles are cut into: the one that spreads Me * NS units most evenly
     int NS = 1, best = 1 << 30;
@@ -604,7 +607,7 @@ struct Tiled {
 #pragma unroll
         for (int kb = 0; kb < 8; kb++)
           if (kb < KB)
-            a[kb] = lastlayer ? as_i32x4(lds_operand_tr(buf(), y.S, kb * 32, mt * 16, li, q))
+            a[kb] = lastlayer ? as_i32x4(lds_operand_tr(buf(), TB_S, kb * 32, mt * 16, li, q))
                               : *(const i32x4*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
       }
     };
@@ -795,7 +798,8 @@ struct Tiled {
     float* bv = fp(y.bv[l]);
     __bf16* oi = bp(y.oi[l][par_next]);
     const __bf16* T = bp(y.T[l]);
-    const int fi = y.U[l], fo = y.U[l + 1], S = y.S;
+    const int fi = y.U[l], fo = y.U[l + 1];
+    constexpr int S = TB_S;
     const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Mr = (fi + 15) / 16, Ne = (fo + 15) / 16;
     const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
     const int TT = Mr * Ne, t0 = w * TT / TB_WAVES, t1 = (w + 1) * TT / TB_WAVES;
@@ -831,15 +835,18 @@ struct Tiled {
       bv_[i] = ADAM ? bv[j] : 0.f;
     }
     if (t1 > t0) {
+      // every global address is a wave-uniform base plus a 32-bit lane offset that never changes
+      const uint32_t lane16 = (uint32_t)lane * 16, lane_t = (uint32_t)(li * 64 + q * 16), lane_oi = (uint32_t)(li * 32 + q * 8);
       auto load_a = [&](int mt, i32x4(&a)[8]) {
+        const char* base = (const char*)T + (size_t)mt * 8192;
 #pragma unroll
-        for (int kb = 0; kb < 8; kb++) a[kb] = *(const i32x4*)(T + (((size_t)mt * 8 + kb) * 16 + li) * 32 + q * 8);
+        for (int kb = 0; kb < 8; kb++) a[kb] = *(const i32x4*)(base + kb * 1024 + lane_t);
       };
       auto load_st = [&](int mt, int nt, St& s) {
-        const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
-        s.w = __builtin_nontemporal_load((const f32x4*)(W + o));
-        s.m = __builtin_nontemporal_load((const f32x4*)(Mo + o));
-        if (ADAM) s.v = __builtin_nontemporal_load((const f32x4*)(Vo + o));
+        const size_t tb = ((size_t)mt * Nt + nt) * 1024;
+        s.w = __builtin_nontemporal_load((const f32x4*)((const char*)W + tb + lane16));
+        s.m = __builtin_nontemporal_load((const f32x4*)((const char*)Mo + tb + lane16));
+        if (ADAM) s.v = __builtin_nontemporal_load((const f32x4*)((const char*)Vo + tb + lane16));
       };
       int mt = t0 / Ne, nt = t0 - mt * Ne;  // the tile being worked on
       int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next; stops at the wave's last tile
@@ -873,24 +880,35 @@ struct Tiled {
         for (int kb = 0; kb < 8; kb++) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[kb]), b[kb], g, 0, 0, 0);
         // the lane holds in units i0..i0+3 of out unit j
         const int j = nt * 16 + li, i0 = mt * 16 + 4 * q;
-        const size_t o = ((size_t)mt * Nt + nt) * 256 + lane * 4;
+        const size_t tb = ((size_t)mt * Nt + nt) * 1024;
         f32x4 wv = cur.w, mv = cur.m, vv = cur.v, gv;
         bf16x4 pk;
+        auto update = [&](auto masked) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-          float wr = wv[r], mr = mv[r], vr = vv[r];
-          gv[r] = g[r] + oc.am * wr;
-          opt_update(oc, gv[r], wr, mr, vr);
-          const bool real = j < fo && i0 + r < fi;
-          wv[r] = real ? wr : wv[r];
-          mv[r] = real ? mr : mv[r];
-          vv[r] = real ? vr : vv[r];
-          pk[r] = (__bf16)wv[r];
-        }
-        __builtin_nontemporal_store(wv, (f32x4*)(W + o));
-        __builtin_nontemporal_store(mv, (f32x4*)(Mo + o));
-        if (ADAM) __builtin_nontemporal_store(vv, (f32x4*)(Vo + o));
-        *(bf16x4*)(oi + ((size_t)nt * Mt + mt) * 256 + li * 16 + 4 * q) = pk;
+          for (int r = 0; r < 4; r++) {
+            float wr = wv[r], mr = mv[r], vr = vv[r];
+            gv[r] = g[r] + oc.am * wr;
+            opt_update(oc, gv[r], wr, mr, vr);
+            if (decltype(masked)::value) {
+              const bool real = j < fo && i0 + r < fi;
+              wr = real ? wr : wv[r];
+              mr = real ? mr : mv[r];
+              vr = real ? vr : vv[r];
+            }
+            wv[r] = wr;
+            mv[r] = mr;
+            vv[r] = vr;
+            pk[r] = (__bf16)wr;
+          }
+        };
+        if ((mt + 1) * 16 > fi || (nt + 1) * 16 > fo)  // a tile with pad units
+          update(std::true_type{});
+        else
+          update(std::false_type{});
+        __builtin_nontemporal_store(wv, (f32x4*)((char*)W + tb + lane16));
+        __builtin_nontemporal_store(mv, (f32x4*)((char*)Mo + tb + lane16));
+        if (ADAM) __builtin_nontemporal_store(vv, (f32x4*)((char*)Vo + tb + lane16));
+        *(bf16x4*)((char*)oi + ((size_t)nt * Mt + mt) * 512 + lane_oi) = pk;
         if (rec) {
 #pragma unroll
           for (int r = 0; r < 4; r++)
