@@ -47,6 +47,8 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 // MFMA operands that live across loop iterations are kept as four dwords: the compiler carries vectors of
 // 16-bit elements through loops half by half
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16x8 as_bf16x8(i32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ i32x4 as_i32x4(bf16x8 v) { return __builtin_bit_cast(i32x4, v); }
 
@@ -178,6 +180,16 @@ __device__ inline bf16x8 lds_operand_tr(const char* base, int ld, int r0, int u0
   u.s.lo = lds_read_tr(p);
   u.s.hi = lds_read_tr(p + (size_t)4 * ld * 2);
   return u.v;
+}
+
+// A wave-uniform value that the compiler holds in vector registers (anything read from memory the kernel also
+// writes), moved to scalar registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <class T>
+__device__ __forceinline__ T* uniform(T* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (T*)(((uint64_t)hi << 32) | lo);
 }
 
 struct Tiled {
@@ -789,18 +801,18 @@ struct Tiled {
   template <bool ADAM>
   __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
     const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float* W = fp(y.w[l]);
-    float* Mo = fp(y.m[l]);
-    float* Vo = fp(y.v[l]);
-    float* bias = fp(y.bias[l]);
-    float* bm = fp(y.bm[l]);
-    float* bv = fp(y.bv[l]);
-    __bf16* oi = bp(y.oi[l][par_next]);
-    const __bf16* T = bp(y.T[l]);
-    const int fi = y.U[l], fo = y.U[l + 1];
+    const int w = uniform((int)(threadIdx.x >> 6));
+    float* W = uniform(fp(y.w[l]));
+    float* Mo = uniform(fp(y.m[l]));
+    float* Vo = uniform(fp(y.v[l]));
+    float* bias = uniform(fp(y.bias[l]));
+    float* bm = uniform(fp(y.bm[l]));
+    float* bv = uniform(fp(y.bv[l]));
+    __bf16* oi = uniform(bp(y.oi[l][par_next]));
+    const __bf16* T = uniform(bp(y.T[l]));
+    const int fi = uniform(y.U[l]), fo = uniform(y.U[l + 1]);
     constexpr int S = TB_S;
-    const int Mt = y.UP[l] / 16, Nt = y.UP[l + 1] / 16, Mr = (fi + 15) / 16, Ne = (fo + 15) / 16;
+    const int Mt = uniform(y.UP[l]) / 16, Nt = uniform(y.UP[l + 1]) / 16, Mr = (fi + 15) / 16, Ne = (fo + 15) / 16;
     const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
     const int TT = Mr * Ne, t0 = w * TT / TB_WAVES, t1 = (w + 1) * TT / TB_WAVES;
     constexpr int D = TB_STATE_AHEAD;
@@ -835,25 +847,36 @@ struct Tiled {
       bv_[i] = ADAM ? bv[j] : 0.f;
     }
     if (t1 > t0) {
-      // every global address is a wave-uniform base plus a 32-bit lane offset that never changes
+      // Every global address is a wave-uniform base plus a 32-bit lane offset that never changes.  The
+      // fetches go through buffer descriptors: the look-ahead runs past the wave's last tile (and last in
+      // tile), and there the lane offset is pushed out of the descriptor's range, which makes the fetch
+      // return zeros without touching memory; the instruction stream stays the same for every tile.
       const uint32_t lane16 = (uint32_t)lane * 16, lane_t = (uint32_t)(li * 64 + q * 16), lane_oi = (uint32_t)(li * 32 + q * 8);
+      constexpr uint32_t OUT_OF_RANGE = 0x40000000u;
+      constexpr int NT_HINT = 2;  // cache policy bit 1: non-temporal
+      const uint32_t state_bytes = (uint32_t)Mt * Nt * 1024;
+      const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(W, 0, state_bytes, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rM = __builtin_amdgcn_make_buffer_rsrc(Mo, 0, state_bytes, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rV = __builtin_amdgcn_make_buffer_rsrc(Vo, 0, state_bytes, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rO = __builtin_amdgcn_make_buffer_rsrc(oi, 0, (uint32_t)Mt * Nt * 512, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rT = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(T), 0, (uint32_t)Mt * 8192, 0x00020000);
+      const int mt_last = (t1 - 1) / Ne;
       auto load_a = [&](int mt, i32x4(&a)[8]) {
-        const char* base = (const char*)T + (size_t)mt * 8192;
+        const uint32_t vo = lane_t + (mt > mt_last ? OUT_OF_RANGE : 0u);
 #pragma unroll
-        for (int kb = 0; kb < 8; kb++) a[kb] = *(const i32x4*)(base + kb * 1024 + lane_t);
-      };
-      auto load_st = [&](int mt, int nt, St& s) {
-        const size_t tb = ((size_t)mt * Nt + nt) * 1024;
-        s.w = __builtin_nontemporal_load((const f32x4*)((const char*)W + tb + lane16));
-        s.m = __builtin_nontemporal_load((const f32x4*)((const char*)Mo + tb + lane16));
-        if (ADAM) s.v = __builtin_nontemporal_load((const f32x4*)((const char*)Vo + tb + lane16));
+        for (int kb = 0; kb < 8; kb++)
+          a[kb] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rT, vo, mt * 8192 + kb * 1024, 0));
       };
       int mt = t0 / Ne, nt = t0 - mt * Ne;  // the tile being worked on
-      int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next; stops at the wave's last tile
-      auto advance_fetch = [&]() {
-        const int step = pt < t1 - 1 ? 1 : 0;
-        pt += step;
-        pn += step;
+      int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next
+      auto load_st = [&](St& s) {
+        const uint32_t vo = lane16 + (pt >= t1 ? OUT_OF_RANGE : 0u);
+        const int so = (pm * Nt + pn) * 1024;
+        s.w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, so, NT_HINT));
+        s.m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, so, NT_HINT));
+        if (ADAM) s.v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, so, NT_HINT));
+        pt++;
+        pn++;
         const int wrap = pn == Ne ? 1 : 0;
         pn = wrap ? 0 : pn;
         pm += wrap;
@@ -864,15 +887,10 @@ struct Tiled {
       i32x4 a[8], an[8];
       load_a(mt, a);
 #pragma unroll
-      for (int k = 0; k < D; k++) {
-        load_st(pm, pn, st[k]);
-        advance_fetch();
-      }
-      const int mt_last = (t1 - 1) / Ne;
-      load_a(min(mt + 1, mt_last), an);
+      for (int k = 0; k < D; k++) load_st(st[k]);
+      load_a(mt + 1, an);
       auto tile = [&](St& cur, St& pre) __attribute__((always_inline)) {
-        load_st(pm, pn, pre);
-        advance_fetch();
+        load_st(pre);
         bf16x8 b[8];
         delta_operands(nt, b);
         f32x4 g = zero4;
@@ -880,7 +898,7 @@ struct Tiled {
         for (int kb = 0; kb < 8; kb++) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a[kb]), b[kb], g, 0, 0, 0);
         // the lane holds in units i0..i0+3 of out unit j
         const int j = nt * 16 + li, i0 = mt * 16 + 4 * q;
-        const size_t tb = ((size_t)mt * Nt + nt) * 1024;
+        const int tb = (mt * Nt + nt) * 1024;
         f32x4 wv = cur.w, mv = cur.m, vv = cur.v, gv;
         bf16x4 pk;
         auto update = [&](auto masked) __attribute__((always_inline)) {
@@ -905,10 +923,10 @@ struct Tiled {
           update(std::true_type{});
         else
           update(std::false_type{});
-        __builtin_nontemporal_store(wv, (f32x4*)((char*)W + tb + lane16));
-        __builtin_nontemporal_store(mv, (f32x4*)((char*)Mo + tb + lane16));
-        if (ADAM) __builtin_nontemporal_store(vv, (f32x4*)((char*)Vo + tb + lane16));
-        *(bf16x4*)((char*)oi + ((size_t)nt * Mt + mt) * 512 + lane_oi) = pk;
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, wv), rW, lane16, tb, NT_HINT);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, mv), rM, lane16, tb, NT_HINT);
+        if (ADAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vv), rV, lane16, tb, NT_HINT);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), rO, lane_oi, (nt * Mt + mt) * 512, 0);
         if (rec) {
 #pragma unroll
           for (int r = 0; r < 4; r++)
@@ -928,7 +946,7 @@ struct Tiled {
           for (int kb = 0; kb < 8; kb++)
 #pragma unroll
             for (int e = 0; e < 4; e++) asm volatile("v_mov_b32 %0, %1" : "=v"(a[kb][e]) : "v"(an[kb][e]));
-          load_a(min(mt + 1, mt_last), an);
+          load_a(mt + 1, an);
         }
       };
       // the only way back to the top is through all D + 1 tile bodies: a wait placed in one of them can count
