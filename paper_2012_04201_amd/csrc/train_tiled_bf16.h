@@ -949,18 +949,18 @@ struct Tiled {
           load_a(mt + 1, an);
         }
       };
-      // the only way back to the top is through all D + 1 tile bodies: a wait placed in one of them can count
-      // on the memory operations of all the others
-      for (int t = t0;;) {
-        bool done = false;
-#pragma unroll
-        for (int k = 0; k <= D; k++)
-          if (!done) {
-            tile(st[k], st[(k + D) % (D + 1)]);
-            done = ++t == t1;
-          }
-        if (done) break;
+      // Whole groups of D + 1 tiles in a loop with one exit, the remaining one or two tiles after it: the
+      // only way from one tile body to the next is the one the tiles take, so a wait placed in one body
+      // can count on the memory operations of all the others.
+      static_assert(D == 2, "the rotation below is written out for three register sets");
+      const int groups = (t1 - t0) / 3, rest = (t1 - t0) - 3 * groups;
+      for (int i = 0; i < groups; i++) {
+        tile(st[0], st[2]);
+        tile(st[1], st[0]);
+        tile(st[2], st[1]);
       }
+      if (rest >= 1) tile(st[0], st[2]);
+      if (rest == 2) tile(st[1], st[0]);
     }
     // bias gradient: the column sums of the delta, through a row of ones
     const int ones = li == 0 ? 0x3F803F80 : 0;  // two bf16 ones
@@ -990,6 +990,122 @@ struct Tiled {
     }
   }
 
+  // The same for the last layer (one out tile, so at most 16 in tiles + the bias tile; whole minibatch in one
+  // full chunk): wave w takes in tiles w and w + 8, their state is requested before anything else, and the
+  // two tile bodies are straight-line code.  The activation operand comes from the buffer, the delta from its
+  // own buffer, both through the transposing read.  The bias tile goes to the wave with the fewest tiles.
+  template <bool ADAM>
+  __device__ __forceinline__ void wgrad_last(const OptC& oc, int par_next, float* rec) const {
+    const int l = y.L - 1;
+    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
+    const int w = uniform((int)(threadIdx.x >> 6));
+    float* W = uniform(fp(y.w[l]));
+    float* Mo = uniform(fp(y.m[l]));
+    float* Vo = uniform(fp(y.v[l]));
+    float* bias = uniform(fp(y.bias[l]));
+    float* bm = uniform(fp(y.bm[l]));
+    float* bv = uniform(fp(y.bv[l]));
+    __bf16* oi = uniform(bp(y.oi[l][par_next]));
+    __bf16* io = uniform(bp(y.io[par_next]));
+    const int fi = uniform(y.U[l]), fo = uniform(y.U[l + 1]);
+    const int Mt = uniform(y.UP[l]) / 16, Mr = (fi + 15) / 16;
+    const int cw = y.cw[l], cb = y.cb[l], Pn = y.P;
+    char* trp = lds + TB_LDS_TR + w * 512;
+    const uint32_t lane16 = (uint32_t)lane * 16, lane_oi = (uint32_t)(li * 32 + q * 8);
+    constexpr uint32_t OUT_OF_RANGE = 0x40000000u;
+    constexpr int NT_HINT = 2;
+    const uint32_t state_bytes = (uint32_t)Mt * 1024;
+    const __amdgpu_buffer_rsrc_t rW = __builtin_amdgcn_make_buffer_rsrc(W, 0, state_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rM = __builtin_amdgcn_make_buffer_rsrc(Mo, 0, state_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rV = __builtin_amdgcn_make_buffer_rsrc(Vo, 0, state_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rO = __builtin_amdgcn_make_buffer_rsrc(oi, 0, (uint32_t)Mt * 512, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rI = __builtin_amdgcn_make_buffer_rsrc(io, 0, (uint32_t)Mt * 512, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(bias, 0, 64, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rBm = __builtin_amdgcn_make_buffer_rsrc(bm, 0, 64, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rBv = __builtin_amdgcn_make_buffer_rsrc(bv, 0, 64, 0x00020000);
+    struct St {
+      f32x4 w, m, v;
+    };
+    const f32x4 zero4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    St st[2];
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      const int mt = w + 8 * k;
+      const uint32_t vo = lane16 + (mt < Mr ? 0u : OUT_OF_RANGE);
+      st[k].w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, mt * 1024, NT_HINT));
+      st[k].m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, mt * 1024, NT_HINT));
+      st[k].v = ADAM ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, mt * 1024, NT_HINT)) : zero4;
+    }
+    // bias state: out unit li (lanes of group 0 use it)
+    float bw_ = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rB, (uint32_t)li * 4, 0, 0));
+    float bm_ = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rBm, (uint32_t)li * 4, 0, 0));
+    float bv_ = ADAM ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rBv, (uint32_t)li * 4, 0, 0)) : 0.f;
+    // the delta operand is the same for every tile
+    bf16x8 b[8];
+#pragma unroll
+    for (int kb = 0; kb < 8; kb++) b[kb] = lds_operand_tr(dbuf(), 16, kb * 32, 0, li, q);
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      const int mt = w + 8 * k;
+      if (mt < Mr) {
+        f32x4 g = zero4;
+#pragma unroll
+        for (int kb = 0; kb < 8; kb++)
+          g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_operand_tr(buf(), TB_S, kb * 32, mt * 16, li, q), b[kb], g, 0, 0, 0);
+        // the lane holds in units i0..i0+3 of out unit li
+        const int i0 = mt * 16 + 4 * q;
+        f32x4 wv = st[k].w, mv = st[k].m, vv = st[k].v, gv;
+        bf16x4 pk;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          float wr = wv[r], mr = mv[r], vr = vv[r];
+          gv[r] = g[r] + oc.am * wr;
+          opt_update(oc, gv[r], wr, mr, vr);
+          const bool real = li < fo && i0 + r < fi;
+          wv[r] = real ? wr : wv[r];
+          mv[r] = real ? mr : mv[r];
+          vv[r] = real ? vr : vv[r];
+          pk[r] = (__bf16)wv[r];
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, wv), rW, lane16, mt * 1024, NT_HINT);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, mv), rM, lane16, mt * 1024, NT_HINT);
+        if (ADAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vv), rV, lane16, mt * 1024, NT_HINT);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), rO, lane_oi, mt * 512, 0);
+        // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
+        *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
+        const s16x4 tv = lds_read_tr(trp + ((4 * q + (li >> 2)) * 16 + 4 * (li & 3)) * 2);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, tv), rI, lane_oi, mt * 512, 0);
+        if (rec) {
+#pragma unroll
+          for (int r = 0; r < 4; r++)
+            if (li < fo && i0 + r < fi) {
+              const int ci = cw + (i0 + r) * fo + li;
+              rec[1 + ci] = gv[r];
+              rec[1 + Pn + ci] = wv[r];
+            }
+        }
+      }
+    }
+    if (w == (Mr & 7)) {  // bias gradient: the column sums of the delta, through a row of ones
+      const int ones = li == 0 ? 0x3F803F80 : 0;  // two bf16 ones
+      const bf16x8 a1 = as_bf16x8(i32x4{ones, ones, ones, ones});
+      f32x4 g = zero4;
+#pragma unroll
+      for (int kb = 0; kb < 8; kb++) g = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b[kb], g, 0, 0, 0);
+      if (q == 0 && li < fo) {  // r = 0 of lane group 0 holds the bias gradient of out unit li
+        float wr = bw_, mr = bm_, vr = bv_;
+        opt_update(oc, g[0], wr, mr, vr);
+        if (rec) {
+          rec[1 + cb + li] = g[0];
+          rec[1 + Pn + cb + li] = wr;
+        }
+        bias[li] = wr;
+        bm[li] = mr;
+        if (ADAM) bv[li] = vr;
+      }
+    }
+  }
+
   __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                         float* rec) const {
     if (first && last && KB == 8 && l + 1 < y.L) {
@@ -997,6 +1113,11 @@ struct Tiled {
         wgrad_stream<true>(l, oc, par_next, rec);
       else
         wgrad_stream<false>(l, oc, par_next, rec);
+    } else if (first && last && KB == 8) {
+      if (oc.adam)
+        wgrad_last<true>(oc, par_next, rec);
+      else
+        wgrad_last<false>(oc, par_next, rec);
     } else {
       wgrad_t(l, KB, first, last, oc, par_next, rec);
     }
