@@ -65,9 +65,10 @@ constexpr uint32_t TB_LDS_LIMIT = 160 * 1024 - 1024;  // dynamic LDS available t
 constexpr int TB_S = TB_MAXU + TB_PAD;                        // LDS row stride in elements
 constexpr uint32_t TB_LDS_BUF = 0;                            // buf[row][unit]
 constexpr uint32_t TB_LDS_ROWS = TB_LDS_BUF + TB_ROWS * TB_S * 2;  // row list of the chunk
+constexpr uint32_t TB_LDS_TARGETS = TB_LDS_ROWS + TB_ROWS * 4;     // the rows' targets (class index or value, 32 bits)
 // 16 KB that serve as: output delta (8 KB) + a 16 x 16 bf16 patch per wave (4 KB) from the output layer to
 // the last weight gradient, and in between as 2 KB per wave of weight staging for the hidden data gradient
-constexpr uint32_t TB_LDS_STAGE = TB_LDS_ROWS + TB_ROWS * 4;
+constexpr uint32_t TB_LDS_STAGE = TB_LDS_TARGETS + TB_ROWS * 4;
 constexpr uint32_t TB_LDS_DELTA = TB_LDS_STAGE;
 constexpr uint32_t TB_LDS_TR = TB_LDS_STAGE + TB_ROWS * 16 * 2;
 constexpr uint32_t TB_LDS_TOTAL = TB_LDS_STAGE + TB_WAVES * 2048;
@@ -205,6 +206,7 @@ struct Tiled {
   __device__ __forceinline__ char* buf() const { return lds + TB_LDS_BUF; }
   __device__ __forceinline__ char* dbuf() const { return lds + TB_LDS_DELTA; }
   __device__ __forceinline__ int32_t* rowlist() const { return (int32_t*)(lds + TB_LDS_ROWS); }
+  __device__ __forceinline__ int32_t* targets() const { return (int32_t*)(lds + TB_LDS_TARGETS); }
 
   // ---- blocked indices ------------------------------------------------------
   // state element (in unit k, out unit j) of layer l
@@ -276,18 +278,35 @@ struct Tiled {
   __device__ __forceinline__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows,
                                              bool permute) const {
     int32_t* rl = rowlist();
-    for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x)
-      rl[p] = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
+    int32_t* tg = targets();
+    const int32_t* Y = (const int32_t*)P.y;  // class indices or float values: 32 bits either way
+    for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x) {
+      const int row = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
+      rl[p] = row;
+      tg[p] = row >= 0 ? Y[row] : 0;  // in flight while the rows are gathered
+    }
     __syncthreads();
-    const int d = y.U[0], up0 = y.UP[0], S = TB_S, vpr = up0 / 8;  // 16-byte vectors per row
+    const int d = y.U[0], up0 = y.UP[0], vpr = up0 / 8;  // 16-byte vectors per row
     char* b0 = buf();
     const __bf16* X = (const __bf16*)P.X;
-    for (int idx = threadIdx.x; idx < TB_ROWS * vpr; idx += blockDim.x) {
-      const int r = idx / vpr, vv = idx - r * vpr;
-      const int row = rl[r];
-      uint4 val = uint4{0, 0, 0, 0};
-      if (row >= 0 && vv * 8 < d) val = *(const uint4*)(X + (size_t)row * d + vv * 8);
-      *(uint4*)(b0 + ((size_t)r * S + vv * 8) * 2) = val;
+    // four vectors per thread in flight: the gather is all latency
+    const int nvec = TB_ROWS * vpr;
+    for (int base = threadIdx.x; base < nvec; base += 4 * TB_THREADS) {
+      uint4 val[4];
+      int r[4], vv[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const int idx = base + u * TB_THREADS;
+        r[u] = idx / vpr;
+        vv[u] = idx - r[u] * vpr;
+        const int row = idx < nvec ? rl[r[u]] : -1;
+        // always a valid address, so the four loads are unconditional; pad rows and columns become zeros
+        const uint4 v = *(const uint4*)(X + (size_t)max(row, 0) * d + min(vv[u] * 8, d - 8));
+        val[u] = row >= 0 && vv[u] * 8 < d ? v : uint4{0, 0, 0, 0};
+      }
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+        if (base + u * TB_THREADS < nvec) *(uint4*)(b0 + ((size_t)r[u] * TB_S + vv[u] * 8) * 2) = val[u];
     }
     __syncthreads();
   }
@@ -474,6 +493,7 @@ struct Tiled {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
     const float* bias = fp(y.bias[l]);
     const int32_t* rl = rowlist();
+    const int32_t* tg = targets();
     char* db = dbuf();
     const bool cls = P.n_classes >= 2;
     const __bf16* A = bp(y.oi[l][par]);
@@ -505,7 +525,7 @@ struct Tiled {
         for (int e = 0; e < 4; e++) z[e] = acc[e] + b[e];
         float delta[4] = {0.f, 0.f, 0.f, 0.f};
         if (cls) {
-          const int yr = valid ? ((const int32_t*)P.y)[row] : 0;
+          const int yr = valid ? tg[r] : 0;
           float mx = -INFINITY;
           int best = 0;
 #pragma unroll
@@ -546,7 +566,7 @@ struct Tiled {
               if (4 * q + e < c) delta[e] = (expf(z[e] - lse) - (4 * q + e == yr ? 1.f : 0.f)) * inv_mb;
           }
         } else {
-          const float e0 = valid ? z[0] - ((const float*)P.y)[row] : 0.f;
+          const float e0 = valid ? z[0] - __builtin_bit_cast(float, tg[r]) : 0.f;
           if (valid && q == 0) {
             lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
             hits += (double)fabsf(e0);  // the absolute error
