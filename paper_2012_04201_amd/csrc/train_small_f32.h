@@ -407,12 +407,17 @@ struct Small {
   }
 
   // ---- optimizer step: gradients (and hidden moments) in registers, weights in LDS ----
-  __device__ __forceinline__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&g2p)[4], f32x4 gb2, float* rec) const {
+  // Hidden-layer update of the wave's tiles.  ADAM and TRACED are compile-time so that the element loop is
+  // straight-line code: the L2 term and the pad columns are handled by selects, not branches.
+  template <bool ADAM, bool TRACED>
+  __device__ __forceinline__ void update_hidden(const OptC& oc, const f32x4 (&accg)[4][KT], float* rec) const {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
-    const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h, c = CO <= 2 ? CO : y.c;
+    const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h;
     float* w1 = f(y.o_w1);
     float* m1 = m1g();
     float* v1 = v1g();
+    OptC c = oc;
+    c.adam = ADAM;
     // all moment loads of the wave first, so that their latency overlaps
     f32x4 m1r[4][KT], v1r[4][KT];
 #pragma unroll
@@ -423,7 +428,7 @@ struct Small {
         m1r[i][m] = v1r[i][m] = f32x4{0.f, 0.f, 0.f, 0.f};
         if (w + 4 * i < nut && j < h && k0 <= d) {
           m1r[i][m] = *(const f32x4*)(m1 + j * ldw + k0);
-          if (oc.adam) v1r[i][m] = *(const f32x4*)(v1 + j * ldw + k0);
+          if (ADAM) v1r[i][m] = *(const f32x4*)(v1 + j * ldw + k0);
         }
       }
 #pragma unroll
@@ -436,29 +441,49 @@ struct Small {
           if (j < h && k0 <= d) {
             const int o = j * ldw + k0;
             f32x4 wv = *(const f32x4*)(w1 + o);
+            f32x4 mv = m1r[i][m], vv = v1r[i][m], gv;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
               const int k = k0 + e;
-              if (k <= d) {
-                float wr = wv[e], mr = m1r[i][m][e], vr = v1r[i][m][e];
-                const float gg = k < d ? accg[i][m][e] + oc.am * wr : accg[i][m][e];
-                opt_update(oc, gg, wr, mr, vr);
-                if (rec) {
-                  const int ci = ci_hidden(j, k);
-                  rec[1 + ci] = gg;
-                  rec[1 + y.P + ci] = wr;
-                }
-                wv[e] = wr;
-                m1r[i][m][e] = mr;
-                v1r[i][m][e] = vr;
-              }
+              float wr = wv[e], mr = mv[e], vr = vv[e];
+              gv[e] = accg[i][m][e] + (k < d ? c.am * wr : 0.f);  // column d is the bias: no penalty
+              opt_update(c, gv[e], wr, mr, vr);
+              const bool real = k <= d;
+              wv[e] = real ? wr : wv[e];
+              mv[e] = real ? mr : mv[e];
+              vv[e] = real ? vr : vv[e];
             }
             *(f32x4*)(w1 + o) = wv;
-            *(f32x4*)(m1 + o) = m1r[i][m];
-            if (oc.adam) *(f32x4*)(v1 + o) = v1r[i][m];
+            *(f32x4*)(m1 + o) = mv;
+            if (ADAM) *(f32x4*)(v1 + o) = vv;
+            if (TRACED) {
+#pragma unroll
+              for (int e = 0; e < 4; e++)
+                if (k0 + e <= d) {
+                  const int ci = ci_hidden(j, k0 + e);
+                  rec[1 + ci] = gv[e];
+                  rec[1 + y.P + ci] = wv[e];
+                }
+            }
           }
         }
       }
+  }
+
+  __device__ __forceinline__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&g2p)[4], f32x4 gb2, float* rec) const {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int h = y.h, c = CO <= 2 ? CO : y.c;
+    if (rec) {
+      if (oc.adam)
+        update_hidden<true, true>(oc, accg, rec);
+      else
+        update_hidden<false, true>(oc, accg, rec);
+    } else {
+      if (oc.adam)
+        update_hidden<true, false>(oc, accg, rec);
+      else
+        update_hidden<false, false>(oc, accg, rec);
+    }
     // output layer: finish the sums over the rows held by the four lane groups, lane group 0 updates
 #pragma unroll
     for (int i = 0; i < 4; i++)
