@@ -747,7 +747,8 @@ bool force_generic() {
 int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_base, const bbo_mlp_hparams* hp, int B,
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
-  bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic();
+  // the tiled kernel addresses the input matrix with 32-bit byte offsets
+  bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic() && (uint64_t)n * (uint64_t)d * 2 < (1ull << 31);
   bool small = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
   uint64_t tslot = 0;
   uint32_t tlds = 0, slds = 0;

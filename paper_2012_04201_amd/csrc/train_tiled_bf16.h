@@ -818,7 +818,7 @@ struct Tiled {
   // activation operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the
   // bias tiles (ones operand) are dealt round-robin and their state is fetched before anything else.  Pad
   // elements of edge tiles keep their zeros through selects, not branches.
-  template <bool ADAM>
+  template <bool ADAM, bool FROM_X>
   __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
     const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
     const int w = uniform((int)(threadIdx.x >> 6));
@@ -881,11 +881,49 @@ struct Tiled {
       const __amdgpu_buffer_rsrc_t rO = __builtin_amdgcn_make_buffer_rsrc(oi, 0, (uint32_t)Mt * Nt * 512, 0x00020000);
       const __amdgpu_buffer_rsrc_t rT = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(T), 0, (uint32_t)Mt * 8192, 0x00020000);
       const int mt_last = (t1 - 1) / Ne;
+      // Activation operand of in tile mt.  Hidden levels: the spilled transpose, 16 bytes per lane and row
+      // block.  Input level (FROM_X): no spill exists; the lane fetches 8 units of one row of the minibatch from
+      // the input matrix itself (row block kb, row lane / 2, half lane % 2: 32 rows x 16 units per fetch), and
+      // operand() passes each fetched block through the wave's LDS patch and the transposing read.  Rows past
+      // the minibatch, units past the input width and in tiles past the wave's range are out of range: zeros.
+      const __amdgpu_buffer_rsrc_t rX = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<void*>(P.X), 0, FROM_X ? (uint32_t)((uint64_t)P.n * (uint64_t)fi * 2) : 0u, 0x00020000);
+      const int32_t* rl = rowlist();
+      char* patch = lds + TB_LDS_STAGE + w * 2048;
       auto load_a = [&](int mt, i32x4(&a)[8]) {
-        const uint32_t vo = lane_t + (mt > mt_last ? OUT_OF_RANGE : 0u);
+        if (FROM_X) {
+          const int u0 = mt * 16 + (lane & 1) * 8;
 #pragma unroll
-        for (int kb = 0; kb < 8; kb++)
-          a[kb] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rT, vo, mt * 8192 + kb * 1024, 0));
+          for (int kb = 0; kb < 8; kb++) {
+            const int row = rl[kb * 32 + (lane >> 1)];
+            const bool ok = row >= 0 && u0 < fi && mt <= mt_last;
+            const uint32_t vo = ok ? (uint32_t)(row * fi + u0) * 2 : OUT_OF_RANGE;
+            a[kb] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rX, vo, 0, 0));
+          }
+        } else {
+          const uint32_t vo = lane_t + (mt > mt_last ? OUT_OF_RANGE : 0u);
+#pragma unroll
+          for (int kb = 0; kb < 8; kb++)
+            a[kb] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rT, vo, mt * 8192 + kb * 1024, 0));
+        }
+      };
+      // fetched form -> MFMA operand form
+      auto operand = [&](const i32x4(&raw)[8], i32x4(&a)[8]) {
+        if (FROM_X) {
+#pragma unroll
+          for (int kb = 0; kb < 8; kb++) {
+            char* pk = patch + (kb & 1) * 1024;
+            *(i32x4*)(pk + lane * 16) = raw[kb];
+            a[kb] = as_i32x4(lds_operand_tr(pk, 16, 0, 0, li, q));
+          }
+        } else {
+          // register moves written out: the prefetched operand's registers are free before the next fetch
+          // is issued, so the fetch lands in them directly instead of in temporaries that must be waited for
+#pragma unroll
+          for (int kb = 0; kb < 8; kb++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) asm volatile("v_mov_b32 %0, %1" : "=v"(a[kb][e]) : "v"(raw[kb][e]));
+        }
       };
       int mt = t0 / Ne, nt = t0 - mt * Ne;  // the tile being worked on
       int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next
@@ -905,9 +943,10 @@ struct Tiled {
 #pragma unroll
       for (int k = 0; k <= D; k++) st[k] = St{zero4, zero4, zero4};
       i32x4 a[8], an[8];
-      load_a(mt, a);
+      load_a(mt, an);
 #pragma unroll
       for (int k = 0; k < D; k++) load_st(st[k]);
+      operand(an, a);
       load_a(mt + 1, an);
       auto tile = [&](St& cur, St& pre) __attribute__((always_inline)) {
         load_st(pre);
@@ -960,12 +999,7 @@ struct Tiled {
         if (nt == Ne) {  // on to the next in tile: its operand has been in flight since the last change
           nt = 0;
           mt++;
-          // register moves written out: the prefetched operand's registers are free before the next fetch
-          // is issued, so the fetch lands in them directly instead of in temporaries that must be waited for
-#pragma unroll
-          for (int kb = 0; kb < 8; kb++)
-#pragma unroll
-            for (int e = 0; e < 4; e++) asm volatile("v_mov_b32 %0, %1" : "=v"(a[kb][e]) : "v"(an[kb][e]));
+          operand(an, a);
           load_a(mt + 1, an);
         }
       };
@@ -1129,10 +1163,17 @@ struct Tiled {
   __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                         float* rec) const {
     if (first && last && KB == 8 && l + 1 < y.L) {
-      if (oc.adam)
-        wgrad_stream<true>(l, oc, par_next, rec);
-      else
-        wgrad_stream<false>(l, oc, par_next, rec);
+      if (l == 0) {
+        if (oc.adam)
+          wgrad_stream<true, true>(l, oc, par_next, rec);
+        else
+          wgrad_stream<false, true>(l, oc, par_next, rec);
+      } else {
+        if (oc.adam)
+          wgrad_stream<true, false>(l, oc, par_next, rec);
+        else
+          wgrad_stream<false, false>(l, oc, par_next, rec);
+      }
     } else if (first && last && KB == 8) {
       if (oc.adam)
         wgrad_last<true>(oc, par_next, rec);
@@ -1161,11 +1202,11 @@ struct Tiled {
   // will need, keeps the ReLU patterns, writes the output delta.  Called by all waves.
   template <bool TRAIN>
   __device__ __forceinline__ void forward_all(int par, int rows, float inv_mb, uint32_t (&bits)[2][4], double& lsum,
-                                              double& hits) const {
+                                              double& hits, bool spill_inputs = true) const {
     const int w = threadIdx.x >> 6;
     const int KB = (rows + 31) / 32;  // row blocks in use; whole blocks are computed
     for (int l = 0; l + 1 < y.L; l++) {
-      if (TRAIN && w < KB) spill_transposed(l);
+      if (TRAIN && w < KB && (l > 0 || spill_inputs)) spill_transposed(l);
       uint32_t bl[4];
       forward_hidden(l, par, 2 * KB, bl);
 #pragma unroll
@@ -1252,7 +1293,8 @@ struct Tiled {
           const int KB = (rows + 31) / 32;
           const bool first = ch == 0, last = ch == nch - 1;
           stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true);
-          forward_all<true>(par, rows, inv_mb, bits, lsum, hits);
+          // a whole minibatch in one full chunk takes the streaming weight gradient, which reads the inputs themselves
+          forward_all<true>(par, rows, inv_mb, bits, lsum, hits, !(first && last && KB == 8));
           __syncthreads();
           for (int l = L - 1; l >= 0; l--) {
             wgrad(l, KB, first, last, oc, par ^ 1, last ? rec : nullptr);
