@@ -7,12 +7,12 @@
 // LDS buffer buf[row][unit], which every layer overwrites in place:
 //
 //   hidden layers, forward and data gradient: wave w owns units 32w..32w+31 of
-//     the level it produces.  It streams its tiles of the bf16 weight copy from
+//     the level it produces.  It fetches its tiles of the bf16 weight copy from
 //     global memory as MFMA A operands (D[unit][row] = W[unit][k] . act[row][k]),
-//     takes the level from the buffer as B operands, keeps all results in
-//     registers until every wave has read the level (barrier), then writes the
-//     next level over it.  ReLU masks are kept as bits in registers, so a delta
-//     can overwrite the activation it is masked by.
+//     takes the level from the buffer as B operands, 128 rows at a time, keeps
+//     the results in registers until every wave has read those rows (barrier),
+//     then writes the next level over them.  ReLU masks are kept as bits in
+//     registers, so a delta can overwrite the activation it is masked by.
 //   output layer: one wave per 32 rows; softmax, loss and output delta in the
 //     MFMA result layout; the 16-wide delta has a buffer of its own.
 //   weight gradient: contraction over the rows.  The delta operand comes from
@@ -22,11 +22,19 @@
 //     rows to global memory before that happens (tile-blocked, read back as
 //     16-byte operand vectors).  The bias gradient uses a row of ones as operand.
 //   The optimizer runs in the weight-gradient epilogue on the accumulator
-//   registers: fp32 master weights and moments are read (one tile ahead) and
-//   written once per step and the two bf16 operand copies ([out][in] for
-//   forward, [in][out] for backward; the latter double-buffered by step parity,
-//   because the backward pass of the same step still needs the old weights) are
-//   refreshed.
+//   registers: fp32 master weights and moments are read (two tiles ahead) and
+//   written once per step, and the bf16 [out][in] operand copy (double-buffered
+//   by step parity, because the backward pass of the same step still needs the
+//   old weights; the output layer keeps an [in][out] copy as well) is refreshed.
+//
+// The weight gradient exists three times.  wgrad_t handles every case (several
+// chunks per minibatch, ragged chunks).  wgrad_stream (layers below the last)
+// and wgrad_last (the output layer) handle a whole minibatch in one full chunk,
+// which is nearly every step of a run: straight-line tile bodies, all memory
+// operations through buffer descriptors, so that the compiler's waits are exact
+// and the state really is in flight two tiles ahead; for the input layer the
+// activation operand is gathered from the input matrix itself, so the inputs
+// are never spilled.
 //
 // Every global array is stored in the order its wave-level accesses touch it:
 // fp32 state as 16 x 16 tiles [in tile][out tile][lane][4] (1 KB per access),
