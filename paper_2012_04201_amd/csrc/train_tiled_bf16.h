@@ -1011,18 +1011,17 @@ struct Tiled {
           load_a(mt + 1, an);
         }
       };
-      // Whole groups of D + 1 tiles in a loop with one exit, the remaining one or two tiles after it: the
+      // Whole groups of D + 1 tiles in a loop with one exit, the remaining tiles (at most D) after it: the
       // only way from one tile body to the next is the one the tiles take, so a wait placed in one body
       // can count on the memory operations of all the others.
-      static_assert(D == 2, "the rotation below is written out for three register sets");
-      const int groups = (t1 - t0) / 3, rest = (t1 - t0) - 3 * groups;
+      const int groups = (t1 - t0) / (D + 1), rest = (t1 - t0) - (D + 1) * groups;
       for (int i = 0; i < groups; i++) {
-        tile(st[0], st[2]);
-        tile(st[1], st[0]);
-        tile(st[2], st[1]);
+#pragma unroll
+        for (int k = 0; k <= D; k++) tile(st[k], st[(k + D) % (D + 1)]);
       }
-      if (rest >= 1) tile(st[0], st[2]);
-      if (rest == 2) tile(st[1], st[0]);
+#pragma unroll
+      for (int k = 0; k < D; k++)
+        if (rest > k) tile(st[k], st[(k + D) % (D + 1)]);
     }
     // bias gradient: the column sums of the delta, through a row of ones
     const int ones = li == 0 ? 0x3F803F80 : 0;  // two bf16 ones
