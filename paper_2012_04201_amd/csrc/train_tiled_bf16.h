@@ -150,6 +150,11 @@ struct TItem {
   TLay y;
 };
 
+// The staged items are written by the host before the launch and never by a kernel: reading them through the
+// constant address space lets the compiler use scalar loads and keep the layout in scalar registers.
+typedef const __attribute__((address_space(4))) ItemDesc ConstItemDesc;
+typedef const __attribute__((address_space(4))) TLay ConstTLay;
+
 struct OptC {
   bool adam, nest;
   float b1, b2, omb1, omb2, eps, lr_t, mu, lr, am;
@@ -203,8 +208,8 @@ __device__ __forceinline__ T* uniform(T* p) {
 
 struct Tiled {
   const TrainParams& P;
-  const ItemDesc& it;
-  const TLay& y;
+  const ConstItemDesc& it;
+  const ConstTLay& y;
   char* slot;
   char* lds;
   double* red;
@@ -1351,7 +1356,7 @@ __global__ __launch_bounds__(TB_THREADS) void k_train_tiled(const TrainParams P)
     __syncthreads();
     const int item = __builtin_amdgcn_readfirstlane(s_item);
     if (item >= P.n_items) break;
-    const TItem* __restrict__ ti = (const TItem*)P.items + item;
+    const __attribute__((address_space(4))) TItem* ti = (const __attribute__((address_space(4))) TItem*)P.items + item;
     Tiled T{P, ti->d, ti->y, slot, smem, red};
     T.run();
   }
