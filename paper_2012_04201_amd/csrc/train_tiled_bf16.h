@@ -29,8 +29,9 @@
 //
 // The weight gradient exists three times.  wgrad_t handles every case (several
 // chunks per minibatch, ragged chunks).  wgrad_stream (layers below the last)
-// and wgrad_last (the output layer) handle a whole minibatch in one full chunk,
-// which is nearly every step of a run: straight-line tile bodies, all memory
+// and wgrad_last (the output layer) handle a whole minibatch in one chunk (rows
+// past a ragged chunk carry zero deltas), which is nearly every step of a run:
+// straight-line tile bodies, all memory
 // operations through buffer descriptors, so that the compiler's waits are exact
 // and the state really is in flight two tiles ahead; for the input layer the
 // activation operand is gathered from the input matrix itself, so the inputs
@@ -461,6 +462,11 @@ struct Tiled {
       for (int r = 0; r < 4; r++) pk[r] = (__bf16)(((nib >> r) & 1u) ? acc[r] : 0.f);
       *(bf16x4*)(b + jb * tile_bytes + ub * 32) = pk;
     };
+    // Row tiles past the chunk's rows get zeros: the single-chunk weight gradients contract over all 256 rows
+    // whatever the minibatch holds, and a zero delta silences whatever the other operand has there.
+    auto put_zero = [&](int ub, int jb) {
+      *(bf16x4*)(b + jb * tile_bytes + ub * 32) = bf16x4{(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+    };
     if (l + 1 == y.L) {
       // the 16-wide output delta sits in its own buffer: nothing is overwritten while it is read
       if (active) {
@@ -474,6 +480,8 @@ struct Tiled {
             if (jb < njb) {
               const bf16x4 d = *(const bf16x4*)(db + jb * 16 * 16 * 2);
               put(__builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, d, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0), ub, jb);
+            } else {
+              put_zero(ub, jb);
             }
         }
       }
@@ -491,9 +499,18 @@ struct Tiled {
 #pragma unroll
             for (int ub = 0; ub < 2; ub++)
 #pragma unroll
-              for (int j = 0; j < 8; j++)
-                if (half * 8 + j < njb) put(acc[ub][j], ub, half * 8 + j);
+              for (int j = 0; j < 8; j++) {
+                if (half * 8 + j < njb)
+                  put(acc[ub][j], ub, half * 8 + j);
+                else
+                  put_zero(ub, half * 8 + j);
+              }
           }
+        } else if (active) {  // nobody reads these rows in this pass
+#pragma unroll
+          for (int ub = 0; ub < 2; ub++)
+#pragma unroll
+            for (int j = 0; j < 8; j++) put_zero(ub, half * 8 + j);
         }
     }
     __syncthreads();
@@ -824,8 +841,8 @@ struct Tiled {
     }
   }
 
-  // The same for the common case: a layer below the last one, the whole minibatch in one full chunk (all 8
-  // row blocks).  Straight-line code per tile, so that the waits on memory are exact and the optimizer state
+  // The same for the common case: a layer below the last one, the whole minibatch in one chunk.  All 8 row
+  // blocks are contracted: rows past a ragged chunk carry zero deltas (backward_data) and finite activations.  Straight-line code per tile, so that the waits on memory are exact and the optimizer state
   // really is in flight TB_STATE_AHEAD tiles ahead: the in x out tiles of the layer are numbered in-tile-major
   // and each wave takes one contiguous eighth of them (its state is one contiguous stream per array, its
   // activation operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the
@@ -1057,7 +1074,7 @@ struct Tiled {
   }
 
   // The same for the last layer (one out tile, so at most 16 in tiles + the bias tile; whole minibatch in one
-  // full chunk): wave w takes in tiles w and w + 8, their state is requested before anything else, and the
+  // chunk, rows past it carry zero deltas): wave w takes in tiles w and w + 8, their state is requested before anything else, and the
   // two tile bodies are straight-line code.  The activation operand comes from the buffer, the delta from its
   // own buffer, both through the transposing read.  The bias tile goes to the wave with the fewest tiles.
   template <bool ADAM>
@@ -1174,7 +1191,7 @@ struct Tiled {
 
   __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                         float* rec) const {
-    if (first && last && KB == 8 && l + 1 < y.L) {
+    if (first && last && l + 1 < y.L) {
       if (l == 0) {
         if (oc.adam)
           wgrad_stream<true, true>(l, oc, par_next, rec);
@@ -1186,7 +1203,7 @@ struct Tiled {
         else
           wgrad_stream<false, false>(l, oc, par_next, rec);
       }
-    } else if (first && last && KB == 8) {
+    } else if (first && last) {
       if (oc.adam)
         wgrad_last<true>(oc, par_next, rec);
       else
@@ -1229,7 +1246,10 @@ struct Tiled {
           bits[0][i] = bl[i];
       }
     }
-    if (w < KB) forward_out<TRAIN>(par, rows, inv_mb, lsum, hits);
+    if (w < KB)
+      forward_out<TRAIN>(par, rows, inv_mb, lsum, hits);
+    else if (TRAIN)  // no output delta for the rows of this wave: zeros (see backward_data)
+      *(uint4*)(dbuf() + (32 * w) * 32 + (threadIdx.x & 63) * 16) = uint4{0, 0, 0, 0};
   }
 
   __device__ __forceinline__ void run() const {
@@ -1246,6 +1266,10 @@ struct Tiled {
       uint4* z = (uint4*)slot;
       const uint64_t n16 = y.total / 16;
       for (uint64_t i = threadIdx.x; i < n16; i += blockDim.x) z[i] = uint4{0, 0, 0, 0};
+      // The activation buffer too: rows past a ragged chunk are never written, but the weight gradients read
+      // them (against zero deltas), so they must hold finite numbers whatever ran on this CU before.
+      uint4* zb = (uint4*)buf();
+      for (uint32_t i = threadIdx.x; i < TB_ROWS * TB_S * 2 / 16; i += blockDim.x) zb[i] = uint4{0, 0, 0, 0};
     }
     __syncthreads();
     double b1t = 1.0, b2t = 1.0;
@@ -1305,8 +1329,8 @@ struct Tiled {
           const int KB = (rows + 31) / 32;
           const bool first = ch == 0, last = ch == nch - 1;
           stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true);
-          // a whole minibatch in one full chunk takes the streaming weight gradient, which reads the inputs themselves
-          forward_all<true>(par, rows, inv_mb, bits, lsum, hits, !(first && last && KB == 8));
+          // a minibatch of one chunk takes the streaming weight gradient, which reads the inputs themselves
+          forward_all<true>(par, rows, inv_mb, bits, lsum, hits, !(first && last));
           __syncthreads();
           for (int l = L - 1; l >= 0; l--) {
             wgrad(l, KB, first, last, oc, par ^ 1, last ? rec : nullptr);
