@@ -572,6 +572,25 @@ def test_batch_composition_invariance_and_determinism(bb):
     assert torch.equal(s3, s1[order])
 
 
+def test_divergent_neighbours_on_the_same_workgroup_bf16(bb):
+    """More models than resident workgroups, every other one divergent, ragged minibatches: a workgroup
+    that has just trained a model full of NaNs goes on to a healthy one, whose score must be bit-identical
+    to what it is without such neighbours (nothing of the previous model may be read, also not in the
+    rows past a ragged chunk, which the weight gradients contract over with zero deltas)."""
+    cfg = small_problem(77, 260, 16, 3, bf16=True)
+    X, y, ft = bb.to_device(cfg)
+    good = [{"hidden": [24 + (i % 5) * 8, 16], "solver": "adam", "batch_size": 50 + 3 * (i % 7), "lr": 0.003,
+             "alpha": 0.01, "epochs": 2, "seed": 1000 + i} for i in range(64)]
+    bad = [dict(h, solver="sgd", momentum=0.99, nesterov=True, lr=1e6, epochs=4) for h in good]
+    mixed = [h for pair in zip(bad, good) for h in pair]  # 128 suggestions x 5 folds = 640 items on 256 CUs
+    s_alone, st_alone = bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, good, 1)
+    s_mixed, st_mixed = bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, mixed, 1)
+    torch.cuda.synchronize()
+    assert st_alone.cpu().tolist() == [0] * 64
+    assert st_mixed.cpu().tolist() == [1, 0] * 64
+    assert torch.equal(s_mixed[1::2], s_alone)
+
+
 def test_edge_cases(bb, oracle):
     cfg = small_problem(5, 60, 6, 3)
     X, y, ft = bb.to_device(cfg)
