@@ -215,6 +215,14 @@ struct Tiled {
   char* lds;
   double* red;
 
+  // The thread index as a value the compiler cannot see through: what a phase derives from it (lane
+  // coordinates, LDS and global addresses) is then recomputed where it is used, in a few instructions, instead
+  // of being computed once ahead of every loop and kept, mostly spilled, for the whole run.
+  __device__ __forceinline__ static int tid() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+  }
   __device__ __forceinline__ float* fp(uint64_t off) const { return (float*)(slot + off); }
   __device__ __forceinline__ __bf16* bp(uint64_t off) const { return (__bf16*)(slot + off); }
   __device__ __forceinline__ char* buf() const { return lds + TB_LDS_BUF; }
@@ -327,7 +335,7 @@ struct Tiled {
 
   // Transpose of the wave's rows of level l to global, tile-blocked [unit tile][row block][unit][32 rows].
   __device__ __forceinline__ void spill_transposed(int l) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     __bf16* T = bp(y.T[l]);
     const int mta = y.UP[l] / 16;
     for (int mt = 0; mt < mta; mt++) {
@@ -345,7 +353,7 @@ struct Tiled {
   // tiles of A.
   template <bool TR>
   __device__ __forceinline__ void gemm_operands(const __bf16* __restrict__ A, int kbn, int mt_a, i32x4 (&ar)[8][2]) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const __bf16* A0 = TR ? A + ((size_t)(lane >> 5) * mt_a + 2 * w) * 256 + (lane & 31) * 8
                           : A + (size_t)(2 * w) * kbn * 512 + opnd_lane(li, q);
     const __bf16* A1 = A0 + (TR ? (size_t)256 : (size_t)kbn * 512);
@@ -375,7 +383,7 @@ struct Tiled {
   // multiplied whatever the chunk holds: tiles past the rows in use only cost arithmetic on stale buffer
   // contents, and the callers never store their results.
   __device__ __forceinline__ void gemm_half(const i32x4 (&ar)[8][2], int kbn, int half, f32x4 (&acc)[2][8]) const {
-    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
+    const int lane = tid() & 63, li = lane & 15, q = lane >> 4;
     const size_t tile_bytes = (size_t)16 * TB_S * 2;
     const char* bp = buf() + ((size_t)li * TB_S + q * 8) * 2 + half * 8 * tile_bytes;
 #pragma unroll
@@ -406,7 +414,7 @@ struct Tiled {
   // half is read.  The ReLU pattern of the wave's units goes to `bits` (bit 4*(16*ub + jb) + r).  Called by
   // all waves.
   __device__ __forceinline__ void forward_hidden(int l, int par, int njb, uint32_t (&bits)[4]) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const bool active = 32 * w < y.UP[l + 1];
     const int kbn = y.UP[l] / 32;
     const float* bias = fp(y.bias[l]);
@@ -451,7 +459,7 @@ struct Tiled {
   // Delta of level l (1 <= l < L) from the delta of level l+1 (in dbuf for the output level, else in
   // the buffer), masked by the ReLU pattern of level l, written over the buffer.  Called by all waves.
   __device__ __forceinline__ void backward_data(int l, int par, int njb, const uint32_t (&bits)[4]) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const bool active = 32 * w < y.UP[l];
     char* b = buf() + ((size_t)li * TB_S + 32 * w + 4 * q) * 2;
     const size_t tile_bytes = (size_t)16 * TB_S * 2;
@@ -520,7 +528,7 @@ struct Tiled {
   template <bool TRAIN>
   __device__ __forceinline__ void forward_out(int par, int rows, float inv_mb, double& lsum, double& hits) const {
     const int l = y.L - 1, c = y.U[y.L];
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const float* bias = fp(y.bias[l]);
     const int32_t* rl = rowlist();
     const int32_t* tg = targets();
@@ -622,7 +630,7 @@ struct Tiled {
   // the bias gradient (the deltas of unused rows are zero); the bias and its moments are plain arrays.
   __device__ __forceinline__ void wgrad_t(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                           float* rec) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     float* W = fp(y.w[l]);
     float* Mo = fp(y.m[l]);
     float* Vo = fp(y.v[l]);
@@ -850,8 +858,8 @@ struct Tiled {
   // elements of edge tiles keep their zeros through selects, not branches.
   template <bool ADAM, bool FROM_X>
   __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
-    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
-    const int w = uniform((int)(threadIdx.x >> 6));
+    const int t_ = tid(), lane = t_ & 63, li = lane & 15, q = lane >> 4;
+    const int w = uniform(t_ >> 6);
     float* W = uniform(fp(y.w[l]));
     float* Mo = uniform(fp(y.m[l]));
     float* Vo = uniform(fp(y.v[l]));
@@ -1080,8 +1088,8 @@ struct Tiled {
   template <bool ADAM>
   __device__ __forceinline__ void wgrad_last(const OptC& oc, int par_next, float* rec) const {
     const int l = y.L - 1;
-    const int lane = threadIdx.x & 63, li = lane & 15, q = lane >> 4;
-    const int w = uniform((int)(threadIdx.x >> 6));
+    const int t_ = tid(), lane = t_ & 63, li = lane & 15, q = lane >> 4;
+    const int w = uniform(t_ >> 6);
     float* W = uniform(fp(y.w[l]));
     float* Mo = uniform(fp(y.m[l]));
     float* Vo = uniform(fp(y.v[l]));
