@@ -134,6 +134,13 @@ struct Small {
     if (j >= y.h || k > y.d) return -1;
     return k < y.d ? y.cw[0] + k * y.h + j : y.cb[0] + j;
   }
+  // The thread index as a value the compiler cannot see through: lane coordinates and the addresses derived
+  // from them are recomputed in each phase instead of being kept in registers for the whole run.
+  __device__ __forceinline__ static int tid() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+  }
   __device__ __forceinline__ float init_value(int l, int e, bool isb) const {
     const uint64_t kt = key_fold(key_model(it.seed, it.fold), 16 + 2 * l + (isb ? 1 : 0));
     const uint32_t k24 = (uint32_t)(key_fold(kt, (uint64_t)e) >> 40);
@@ -187,7 +194,7 @@ struct Small {
   __device__ __forceinline__ void fetch_inputs(int par, float (&xr)[NX], float& yv) const {
     const int32_t* rl = rowlist(par);
     const float* X = (const float*)P.X;
-    const int k = threadIdx.x % K0, r0 = threadIdx.x / K0, d = y.d;
+    const int t_ = tid(), k = t_ % K0, r0 = t_ / K0, d = y.d;
 #pragma unroll
     for (int i = 0; i < NX; i++) {
       const int row = rl[r0 + i * RSTEP];
@@ -204,7 +211,7 @@ struct Small {
   __device__ __forceinline__ void commit_inputs(int par, const float (&xr)[NX], float yv) const {
     float* s = f(y.o_xs);
     float* t = xt(par);
-    const int k = threadIdx.x % K0, r0 = threadIdx.x / K0;
+    const int t_ = tid(), k = t_ % K0, r0 = t_ / K0;
 #pragma unroll
     for (int i = 0; i < NX; i++) {
       const int r = r0 + i * RSTEP;
@@ -216,7 +223,7 @@ struct Small {
 
   // ---- phase 1: hidden layer forward; the wave's share of the outputs -> zp ----
   __device__ __forceinline__ void forward(int nrt, f32x4 (&acc)[4][4]) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, ldw = y.ldw;
     const float* s = f(y.o_xs);
     const float* w1 = f(y.o_w1);
@@ -292,7 +299,7 @@ struct Small {
   // ---- phase 2a: outputs, loss and output delta of all 64 rows (lane = row), per wave ----
   template <bool TRAIN>
   __device__ __forceinline__ void outputs(int par, int rows, float inv_mb, double& lsum, double& hits, f32x4& gb2) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = CO <= 2 ? CO : y.c;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, c = CO <= 2 ? CO : y.c;
     const float* zp = f(y.o_zp);
     const f32x4 b2 = *(const f32x4*)(f(y.o_w2) + y.HP * 4);
     float z0 = b2[0], z1 = b2[1], z2 = b2[2], z3 = b2[3];
@@ -359,7 +366,7 @@ struct Small {
 
   // ---- phase 2b: hidden deltas in the accumulators, output-layer gradient, hidden weight gradient ----
   __device__ __forceinline__ void backward(int par, int nrt, f32x4 (&acc)[4][4], f32x4 (&accg)[4][KT], f32x4 (&g2p)[4]) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, lda = y.lda;
     const float* t = xt(par);
     const float* d2 = f(y.o_d2) + w * SM_RC * 4;
@@ -411,7 +418,7 @@ struct Small {
   // straight-line code: the L2 term and the pad columns are handled by selects, not branches.
   template <bool ADAM, bool TRACED>
   __device__ __forceinline__ void update_hidden(const OptC& oc, const f32x4 (&accg)[4][KT], float* rec) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, ldw = y.ldw, d = y.d, h = y.h;
     float* w1 = f(y.o_w1);
     float* m1 = m1g();
@@ -471,7 +478,7 @@ struct Small {
   }
 
   __device__ __forceinline__ void update(const OptC& oc, const f32x4 (&accg)[4][KT], f32x4 (&g2p)[4], f32x4 gb2, float* rec) const {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, li = lane & 15, q = lane >> 4;
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const int h = y.h, c = CO <= 2 ? CO : y.c;
     if (rec) {
       if (oc.adam)
