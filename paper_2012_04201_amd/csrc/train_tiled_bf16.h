@@ -850,11 +850,12 @@ struct Tiled {
   }
 
   // The same for the common case: a layer below the last one, the whole minibatch in one chunk.  All 8 row
-  // blocks are contracted: rows past a ragged chunk carry zero deltas (backward_data) and finite activations.  Straight-line code per tile, so that the waits on memory are exact and the optimizer state
-  // really is in flight TB_STATE_AHEAD tiles ahead: the in x out tiles of the layer are numbered in-tile-major
-  // and each wave takes one contiguous eighth of them (its state is one contiguous stream per array, its
-  // activation operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the
-  // bias tiles (ones operand) are dealt round-robin and their state is fetched before anything else.  Pad
+  // blocks are contracted: rows past a ragged chunk carry zero deltas (backward_data) and finite activations.
+  // Straight-line code per tile, so that the waits on memory are exact and the optimizer state really is in
+  // flight TB_STATE_AHEAD tiles ahead: the in x out tiles of the layer are numbered in-tile-major and each
+  // wave takes one contiguous eighth of them (its state is one contiguous stream per array, its activation
+  // operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the bias
+  // tiles (ones operand) are dealt round-robin and their state is fetched before anything else.  Pad
   // elements of edge tiles keep their zeros through selects, not branches.
   template <bool ADAM, bool FROM_X>
   __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
