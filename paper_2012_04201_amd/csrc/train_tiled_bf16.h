@@ -413,19 +413,28 @@ struct Tiled {
   // half's results stay in registers until every wave has read that half, and are written while the other
   // half is read.  The ReLU pattern of the wave's units goes to `bits` (bit 4*(16*ub + jb) + r).  Called by
   // all waves.
-  __device__ __forceinline__ void forward_hidden(int l, int par, int njb, uint32_t (&bits)[4]) const {
-    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
-    const bool active = 32 * w < y.UP[l + 1];
-    const int kbn = y.UP[l] / 32;
-    const float* bias = fp(y.bias[l]);
-    const size_t tile_bytes = (size_t)16 * TB_S * 2;
-    i32x4 ar[8][2];
-    f32x4 bv[2];
-    if (active) {
-      gemm_operands<false>(bp(y.oi[l][par]), kbn, 0, ar);
+  // The wave's weight operands and biases of hidden layer l (forward), requested, not waited for.
+  __device__ __forceinline__ void fetch_hidden(int l, int par, i32x4 (&ar)[8][2], f32x4 (&bv)[2]) const {
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, q = lane >> 4;
+    if (32 * w < y.UP[l + 1]) {
+      gemm_operands<false>(bp(y.oi[l][par]), y.UP[l] / 32, 0, ar);
+      const float* bias = fp(y.bias[l]);
 #pragma unroll
       for (int ub = 0; ub < 2; ub++) bv[ub] = *(const f32x4*)(bias + 32 * w + 16 * ub + 4 * q);
     }
+  }
+
+  // The operands (ar, bv) come from fetch_hidden.  `next` is called once, after the wave's last products, when
+  // ar is dead: it requests the operands of the phase that follows into ar, so that their latency passes
+  // behind this layer's last epilogue and barrier.
+  template <class Next>
+  __device__ __forceinline__ void forward_hidden(int l, int njb, uint32_t (&bits)[4], i32x4 (&ar)[8][2], const f32x4 (&bv_in)[2],
+                                                 Next next) const {
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
+    const bool active = 32 * w < y.UP[l + 1];
+    const int kbn = y.UP[l] / 32;
+    const size_t tile_bytes = (size_t)16 * TB_S * 2;
+    const f32x4 bv[2] = {bv_in[0], bv_in[1]};
 #pragma unroll
     for (int i = 0; i < 4; i++) bits[i] = 0;
 #pragma unroll
@@ -433,6 +442,7 @@ struct Tiled {
       if (half * 8 < njb) {
         f32x4 acc[2][8];
         if (active) gemm_half(ar, kbn, half, acc);
+        if (half == 1 || njb <= 8) next();
         __syncthreads();
         if (active) {
           char* b = buf() + ((size_t)li * TB_S + 32 * w + 4 * q) * 2 + half * 8 * tile_bytes;
@@ -525,8 +535,18 @@ struct Tiled {
   }
 
   // Output layer + loss over the wave's rows (wave w: rows 32w..32w+31).  TRAIN: output delta -> dbuf.
+  // The output layer's weight operand (the same 8 KB for every wave), requested, not waited for.
+  __device__ __forceinline__ void fetch_out(int par, i32x4 (&ar)[8][2]) const {
+    const int l = y.L - 1, lane = tid() & 63, li = lane & 15, q = lane >> 4;
+    const int kbn = y.UP[l] / 32;
+    const __bf16* Ap = bp(y.oi[l][par]) + opnd_lane(li, q);
+#pragma unroll
+    for (int kb = 0; kb < 8; kb++)
+      if (kb < kbn) ar[kb][0] = *(const i32x4*)(Ap + kb * 512);
+  }
+
   template <bool TRAIN>
-  __device__ __forceinline__ void forward_out(int par, int rows, float inv_mb, double& lsum, double& hits) const {
+  __device__ __forceinline__ void forward_out(const i32x4 (&ar)[8][2], int rows, float inv_mb, double& lsum, double& hits) const {
     const int l = y.L - 1, c = y.U[y.L];
     const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const float* bias = fp(y.bias[l]);
@@ -534,22 +554,17 @@ struct Tiled {
     const int32_t* tg = targets();
     char* db = dbuf();
     const bool cls = P.n_classes >= 2;
-    const __bf16* A = bp(y.oi[l][par]);
     {
       const int kbn = y.UP[l] / 32;
       f32x4 accs[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-      const __bf16* Ap = A + opnd_lane(li, q);
       const char* bq = buf() + ((size_t)(32 * w + li) * TB_S + q * 8) * 2;
       const size_t tile_bytes = (size_t)16 * TB_S * 2;
-      bf16x8 a[8];
-#pragma unroll
-      for (int kb = 0; kb < 8; kb++)
-        if (kb < kbn) a[kb] = *(const bf16x8*)(Ap + kb * 512);
 #pragma unroll
       for (int kb = 0; kb < 8; kb++)
         if (kb < kbn) {
-          accs[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], *(const bf16x8*)(bq + kb * 64), accs[0], 0, 0, 0);
-          accs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb], *(const bf16x8*)(bq + tile_bytes + kb * 64), accs[1], 0, 0, 0);
+          const bf16x8 a = as_bf16x8(ar[kb][0]);
+          accs[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + kb * 64), accs[0], 0, 0, 0);
+          accs[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *(const bf16x8*)(bq + tile_bytes + kb * 64), accs[1], 0, 0, 0);
         }
 #pragma unroll
       for (int jb = 0; jb < 2; jb++) {
@@ -1243,10 +1258,22 @@ struct Tiled {
                                               double& hits, bool spill_inputs = true) const {
     const int w = threadIdx.x >> 6;
     const int KB = (rows + 31) / 32;  // row blocks in use; whole blocks are computed
+    // One operand set for the whole pass: each layer requests the next one's (or the output layer's) weights
+    // into it after its own last products.
+    i32x4 ar[8][2];
+    f32x4 bv[2], bvn[2];
+    fetch_hidden(0, par, ar, bv);
     for (int l = 0; l + 1 < y.L; l++) {
       if (TRAIN && w < KB && (l > 0 || spill_inputs)) spill_transposed(l);
       uint32_t bl[4];
-      forward_hidden(l, par, 2 * KB, bl);
+      forward_hidden(l, 2 * KB, bl, ar, bv, [&]() {
+        if (l + 2 < y.L)
+          fetch_hidden(l + 1, par, ar, bvn);
+        else
+          fetch_out(par, ar);
+      });
+      bv[0] = bvn[0];
+      bv[1] = bvn[1];
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         if (l & 1)
@@ -1256,7 +1283,7 @@ struct Tiled {
       }
     }
     if (w < KB)
-      forward_out<TRAIN>(par, rows, inv_mb, lsum, hits);
+      forward_out<TRAIN>(ar, rows, inv_mb, lsum, hits);
     else if (TRAIN)  // no output delta for the rows of this wave: zeros (see backward_data)
       *(uint4*)(dbuf() + (32 * w) * 32 + (threadIdx.x & 63) * 16) = uint4{0, 0, 0, 0};
   }
