@@ -982,8 +982,8 @@ struct Tiled {
       int mt = t0 / Ne, nt = t0 - mt * Ne;  // the tile being worked on
       int pm = mt, pn = nt, pt = t0;        // the tile whose state is fetched next
       auto load_st = [&](St& s) {
-        // also out of range: the lanes whose four in units are all pad (whole 256-byte segments of the tile)
-        const uint32_t vo = lane16 + (pt >= t1 || pm * 16 + 4 * q >= fi ? OUT_OF_RANGE : 0u);
+        // also out of range: the lanes whose elements are all pad (their in units or their out unit)
+        const uint32_t vo = lane16 + (pt >= t1 || pm * 16 + 4 * q >= fi || pn * 16 + li >= fo ? OUT_OF_RANGE : 0u);
         const int so = (pm * Nt + pn) * 1024;
         s.w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, so, NT_HINT));
         s.m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, so, NT_HINT));
@@ -1037,7 +1037,7 @@ struct Tiled {
           update(std::true_type{});
         else
           update(std::false_type{});
-        const uint32_t vs = lane16 + (i0 >= fi ? OUT_OF_RANGE : 0u);  // all-pad lanes: nothing to write back
+        const uint32_t vs = lane16 + (i0 >= fi || j >= fo ? OUT_OF_RANGE : 0u);  // all-pad lanes: nothing to write back
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, wv), rW, vs, tb, NT_HINT);
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, mv), rM, vs, tb, NT_HINT);
         if (ADAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vv), rV, vs, tb, NT_HINT);
