@@ -337,7 +337,7 @@ struct Tiled {
   __device__ __forceinline__ void spill_transposed(int l) const {
     const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     __bf16* T = bp(y.T[l]);
-    const int mta = y.UP[l] / 16;
+    const int mta = (y.U[l] + 15) / 16;  // unit tiles that hold real units: the others are never read back
     for (int mt = 0; mt < mta; mt++) {
       const bf16x8 v = lds_operand_tr(buf(), TB_S, 32 * w, mt * 16, li, q);
       *(bf16x8*)(T + (((size_t)mt * 8 + w) * 16 + li) * 32 + q * 8) = v;
@@ -1140,7 +1140,8 @@ struct Tiled {
 #pragma unroll
     for (int k = 0; k < 2; k++) {
       const int mt = w + 8 * k;
-      const uint32_t vo = lane16 + (mt < Mr ? 0u : OUT_OF_RANGE);
+      // out of range: tiles past the layer, and the lanes whose elements are all pad (out unit or in units)
+      const uint32_t vo = lane16 + (mt < Mr && li < fo && mt * 16 + 4 * q < fi ? 0u : OUT_OF_RANGE);
       st[k].w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, mt * 1024, NT_HINT));
       st[k].m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, mt * 1024, NT_HINT));
       st[k].v = ADAM ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, mt * 1024, NT_HINT)) : zero4;
@@ -1176,9 +1177,10 @@ struct Tiled {
           vv[r] = real ? vr : vv[r];
           pk[r] = (__bf16)wv[r];
         }
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, wv), rW, lane16, mt * 1024, NT_HINT);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, mv), rM, lane16, mt * 1024, NT_HINT);
-        if (ADAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vv), rV, lane16, mt * 1024, NT_HINT);
+        const uint32_t vs = lane16 + (li < fo && i0 < fi ? 0u : OUT_OF_RANGE);  // all-pad lanes: nothing to write back
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, wv), rW, vs, mt * 1024, NT_HINT);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, mv), rM, vs, mt * 1024, NT_HINT);
+        if (ADAM) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vv), rV, vs, mt * 1024, NT_HINT);
         __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, pk), rO, lane_oi, mt * 512, 0);
         // [out][in] -> [in][out] through the wave's LDS patch and the transposing read
         *(bf16x4*)(trp + (li * 16 + 4 * q) * 2) = pk;
