@@ -222,7 +222,81 @@ struct Small {
   }
 
   // ---- phase 1: hidden layer forward; the wave's share of the outputs -> zp ----
+  // A full chunk (all four row tiles): one straight-line block per unit tile of the wave, with the input
+  // operands of all row tiles in registers, so that the ReLU and output-layer arithmetic of one row tile can
+  // be issued while the MFMAs of the next are in flight.  Same order of every accumulation as forward().
+  __device__ __forceinline__ void forward_full(f32x4 (&acc)[4][4]) const {
+    const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
+    const int nut = y.HP / 16, ldw = y.ldw;
+    const float* s = f(y.o_xs);
+    const float* w1 = f(y.o_w1);
+    constexpr bool c2 = CO >= 2, c4 = CO >= 4;
+    f32x4 a[4][KT];
+#pragma unroll
+    for (int r = 0; r < 4; r++)
+#pragma unroll
+      for (int kk = 0; kk < KT; kk++) a[r][kk] = *(const f32x4*)(s + (r * 16 + li) * ldw + kk * 16 + 4 * q);
+    float pz[4][4][CO];  // [row tile][row 4q+e][output]
+#pragma unroll
+    for (int r = 0; r < 4; r++)
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+#pragma unroll
+        for (int cc = 0; cc < CO; cc++) pz[r][e][cc] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+#pragma unroll
+      for (int r = 0; r < 4; r++) acc[i][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (w + 4 * i < nut) {
+        f32x4 b[KT];
+#pragma unroll
+        for (int kk = 0; kk < KT; kk++) b[kk] = *(const f32x4*)(w1 + ((w + 4 * i) * 16 + li) * ldw + kk * 16 + 4 * q);
+        const f32x4 w2 = *(const f32x4*)(f(y.o_w2) + ((w + 4 * i) * 16 + li) * 4);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+#pragma unroll
+          for (int kk = 0; kk < KT; kk++)
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              acc[i][r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][kk][e], b[kk][e], acc[i][r], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const float av = fmaxf(acc[i][r][e], 0.f);
+            acc[i][r][e] = av;
+            pz[r][e][0] += av * w2[0];
+            if (c2) pz[r][e][1] += av * w2[1];
+            if (c4) {
+              pz[r][e][2] += av * w2[2];
+              pz[r][e][3] += av * w2[3];
+            }
+          }
+      }
+    }
+    float* zp = f(y.o_zp) + w * SM_RC * 4;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      f32x4 o[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        o[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < CO; cc++) o[e][cc] = row16_sum(pz[r][e][cc]);
+      }
+      if (li == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) *(f32x4*)(zp + (r * 16 + 4 * q + e) * 4) = o[e];
+      }
+    }
+  }
+
   __device__ __forceinline__ void forward(int nrt, f32x4 (&acc)[4][4]) const {
+    if (KT <= 2 && nrt == 4) {
+      forward_full(acc);
+      return;
+    }
     const int t_ = tid(), lane = t_ & 63, w = t_ >> 6, li = lane & 15, q = lane >> 4;
     const int nut = y.HP / 16, ldw = y.ldw;
     const float* s = f(y.o_xs);
