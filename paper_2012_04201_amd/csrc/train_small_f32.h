@@ -293,7 +293,7 @@ struct Small {
   }
 
   __device__ __forceinline__ void forward(int nrt, f32x4 (&acc)[4][4]) const {
-    if (KT <= 2 && nrt == 4) {
+    if (KT <= 2 && CO <= 2 && nrt == 4) {
       forward_full(acc);
       return;
     }
