@@ -14,7 +14,10 @@
  * (scikit-learn-style conventions) are:
  *   - layers z_l = a_{l-1} W_l + b_l, ReLU on hidden layers, identity output
  *     for regression, softmax over n_classes outputs for classification
- *     (binary included);
+ *     (binary included); n_classes == 1 is the other binary form, the one
+ *     scikit-learn-style MLPs use: ONE output z, labels 0/1, p = 1/(1+e^-z),
+ *     loss log(1 + e^z) - y z (the cross-entropy of p against y), output
+ *     delta p - y, accuracy = mean[(z > 0) == y];
  *   - training loss = mean cross-entropy, or half the mean squared error,
  *     plus alpha/(2 m) * sum of squared weights (biases unpenalised), m being
  *     the number of rows of the minibatch actually used (a short last
@@ -312,6 +315,17 @@ static double data_loss(const net_t* net, const data_t* D, const int32_t* rows, 
           double g = rnd(p - (j == yr ? 1.0 : 0.0), prec);
           dl[j] = opnd(rnd(g / (double)m, prec), D->dtype); /* BF: deltas */
         }
+    } else if (net->n_classes == 1) {
+      /* single-logit binary head: log(1 + e^z) - y z in the form that cannot overflow */
+      double yr = (double)((const int32_t*)D->y)[rows[r]];
+      double az = z[0] < 0.0 ? -z[0] : z[0];
+      double sp = (z[0] > 0.0 ? z[0] : 0.0) + log1p(exp(-az));
+      total += rnd(sp - yr * z[0], prec);
+      if (want_delta) {
+        double p = rnd(1.0 / (1.0 + exp(-z[0])), prec);
+        double g = rnd(p - yr, prec);
+        dl[0] = opnd(rnd(g / (double)m, prec), D->dtype); /* BF: deltas */
+      }
     } else {
       double yr = (double)((const float*)D->y)[rows[r]];
       double e = rnd(z[0] - yr, prec);
@@ -566,6 +580,11 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
         hit += best == ((const int32_t*)D->y)[va[r]];
       }
       out[1] = rnd((double)hit / (double)n_va, prec);
+    } else if (net->n_classes == 1) {
+      int64_t hit = 0;
+      for (int64_t r = 0; r < n_va; r++)
+        hit += (s.a[net->L][r] > 0.0 ? 1 : 0) == ((const int32_t*)D->y)[va[r]];
+      out[1] = rnd((double)hit / (double)n_va, prec);
     } else {
       /* mean absolute error, the other regression metric of Section 2 */
       double sa = 0.0;
@@ -615,7 +634,7 @@ int oracle_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32
                        const int32_t* fold_idx, int32_t n_folds, const oracle_hparams* hp,
                        int32_t B, int32_t dtype, int32_t prec, float* scores, int32_t* status,
                        double* per_fold, int32_t n_threads) {
-  if (n < 0 || d < 1 || n_folds < 1 || B < 0 || n_classes == 1 || n_classes < 0) return -1;
+  if (n < 0 || d < 1 || n_folds < 1 || B < 0 || n_classes < 0) return -1;
   for (int b = 0; b < B; b++) {
     net_t net;
     if (net_build(&net, d, n_classes, &hp[b])) return -1;
@@ -671,7 +690,7 @@ int oracle_mlp_holdout_eval(const void* X, const void* y, int64_t n, int32_t d, 
                             const int32_t* fold_idx, const oracle_hparams* hp, int32_t B,
                             int32_t dtype, int32_t prec, float* scores, int32_t* status,
                             int32_t n_threads) {
-  if (n < 0 || d < 1 || B < 0 || n_classes == 1 || n_classes < 0) return -1;
+  if (n < 0 || d < 1 || B < 0 || n_classes < 0) return -1;
   for (int b = 0; b < B; b++) {
     net_t net;
     if (net_build(&net, d, n_classes, &hp[b])) return -1;

@@ -100,7 +100,7 @@ def _p(a):
 
 def _xy(X, y, n_classes, dtype):
     X = np.ascontiguousarray(X, dtype=np.uint16 if dtype else np.float32)
-    y = np.ascontiguousarray(y, dtype=np.int32 if n_classes >= 2 else np.float32)
+    y = np.ascontiguousarray(y, dtype=np.int32 if n_classes >= 1 else np.float32)  # 1: single-logit binary head
     return X, y
 
 

@@ -18,8 +18,8 @@ M64 = 2**64 - 1
 def tiny_problem(seed, n=40, d=4, n_classes=3):
     rng = np.random.default_rng(seed)
     X = rng.normal(size=(n, d)).astype(np.float32)
-    if n_classes >= 2:
-        y = rng.integers(0, n_classes, size=n).astype(np.int32)
+    if n_classes >= 1:  # 1: labels 0/1 for the single-logit binary head
+        y = rng.integers(0, max(n_classes, 2), size=n).astype(np.int32)
     else:
         y = (X[:, 0] - 0.5 * X[:, 1] + 0.1 * rng.normal(size=n)).astype(np.float32)
     return X, y
@@ -57,6 +57,8 @@ def torch_loss(theta_t, dims, Xb, yb, n_classes, alpha):
     m = Xb.shape[0]
     if n_classes >= 2:
         data = torch.nn.functional.cross_entropy(a, yb, reduction="mean")
+    elif n_classes == 1:
+        data = torch.nn.functional.binary_cross_entropy_with_logits(a[:, 0], yb.to(torch.float64), reduction="mean")
     else:
         data = 0.5 * torch.nn.functional.mse_loss(a[:, 0], yb, reduction="mean")
     return data + 0.5 * alpha * pen / m
@@ -184,6 +186,9 @@ CASES = [
     (0, [], 0.0),
     (4, [5, 3], 0.5),
     (0, [4, 4, 3], 0.1),
+    (1, [5], 0.3),      # single-logit binary head
+    (1, [], 0.0),
+    (1, [4, 3], 0.6),
 ]
 
 
@@ -200,7 +205,7 @@ def test_gradient_matches_autograd_and_finite_differences(oracle, n_classes, hid
     # library autograd on the textbook objective
     tt = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
     Xb = torch.tensor(X[rows], dtype=torch.float64)
-    yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 2 else torch.tensor(y[rows], dtype=torch.float64)
+    yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 1 else torch.tensor(y[rows], dtype=torch.float64)
     tl = torch_loss(tt, dims, Xb, yb, n_classes, float(np.float32(alpha)))
     tl.backward()
     assert abs(loss - tl.item()) < 1e-12 * max(1, abs(loss))
@@ -232,6 +237,48 @@ def test_softmax_gradient_invariants_and_binary_equals_logistic(oracle):
     z = a1 @ W2 + b2
     s = (2 * y[rows] - 1) * (z[:, 1] - z[:, 0])
     assert abs(loss - np.mean(np.log1p(np.exp(-s)))) < 1e-13
+
+
+def test_single_logit_head_is_the_two_class_softmax_with_a_fixed_zero_logit(oracle):
+    """One output z with labels 0/1 is the two-class softmax model whose class-0 logit is pinned to 0: same
+    loss, same gradient on the shared parameters, same accuracy; and the loss does not overflow for large |z|."""
+    X, y = tiny_problem(9, n=34, d=4, n_classes=1)
+    hp = {"hidden": [6], "alpha": 0.2, "seed": 3}
+    rng = np.random.default_rng(2)
+    th1 = oracle.init_params(4, 1, hp, 0) + 0.4 * rng.normal(size=oracle.param_count(4, 1, hp))
+    rows = np.arange(5, 27, dtype=np.int32)
+    l1, g1 = oracle.loss_grad(X, y, 1, rows, hp, th1, prec=1)
+    (W1, b1), (W2, b2) = unpack(th1, [4, 6, 1])
+    # the softmax twin: output weights (0, w), output biases (0, b); the zero column adds nothing to the penalty
+    th2 = np.concatenate([W1.ravel(), b1, np.stack([np.zeros(6), W2[:, 0]], axis=1).ravel(), [0.0, b2[0]]])
+    l2, g2 = oracle.loss_grad(X, y, 2, rows, hp, th2, prec=1)
+    assert abs(l1 - l2) < 1e-13
+    (gW1, gb1), (gW2, gb2) = unpack(g1, [4, 6, 1])
+    (hW1, hb1), (hW2, hb2) = unpack(g2, [4, 6, 2])
+    np.testing.assert_allclose(gW1, hW1, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(gb1, hb1, rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(gW2[:, 0], hW2[:, 1], rtol=1e-11, atol=1e-14)
+    assert abs(gb2[0] - hb2[1]) < 1e-13
+    # by hand: mean of log(1 + e^z) - y z, plus the penalty
+    a1 = np.maximum(X[rows].astype(np.float64) @ W1 + b1, 0)
+    z = (a1 @ W2 + b2)[:, 0]
+    want = np.mean(np.logaddexp(0.0, z) - y[rows] * z) + 0.5 * float(np.float32(0.2)) * ((W1 ** 2).sum() + (W2 ** 2).sum()) / len(rows)
+    assert abs(l1 - want) < 1e-13
+    # scores of a trained model: nll and accuracy recomputed by hand from the final parameters
+    fold = (np.arange(34) % 5).astype(np.int32)
+    hp2 = dict(hp, epochs=3, lr=0.01, batch_size=8, solver="adam")
+    out = oracle.train_one(X, y, 1, fold, hp2, 2, prec=1)
+    (W1, b1), (W2, b2) = unpack(out["theta"], [4, 6, 1])
+    held = np.where(fold == 2)[0]
+    z = (np.maximum(X[held].astype(np.float64) @ W1 + b1, 0) @ W2 + b2)[:, 0]
+    assert abs(out["scores"][0] - np.mean(np.logaddexp(0.0, z) - y[held] * z)) < 1e-12
+    assert abs(out["scores"][1] - np.mean((z > 0).astype(np.int32) == y[held])) < 1e-12
+    # huge logits: finite loss, saturated gradient
+    big = th1.copy()
+    big[-1] = 800.0  # output bias
+    lb, gb = oracle.loss_grad(X, y, 1, rows, dict(hp, alpha=0.0), big, prec=1)
+    assert np.isfinite(lb) and np.isfinite(gb).all()
+    assert abs(unpack(gb, [4, 6, 1])[1][1][0] - np.mean(1.0 - y[rows])) < 1e-9
 
 
 def test_fp32_mode_tracks_fp64_mode(oracle):
@@ -320,7 +367,7 @@ def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov,
             rows = oracle.minibatch_rows(fold, hp, f, ep, s)
             assert len(rows) == (16 if s < 2 else 8)
             Xb = torch.tensor(X[rows], dtype=torch.float64)
-            yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 2 else torch.tensor(y[rows], dtype=torch.float64)
+            yb = torch.tensor(y[rows].astype(np.int64)) if n_classes >= 1 else torch.tensor(y[rows], dtype=torch.float64)
             opt.zero_grad()
             loss = torch_loss(tt, dims, Xb, yb, n_classes, float(np.float32(0.05)))
             loss.backward()
