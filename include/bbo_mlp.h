@@ -82,7 +82,8 @@ int bbo_mlp_workspace_bytes(int64_t n, int32_t d, int32_t n_classes, int32_t n_f
  *
  *   X         device, row-major [n][d]; float32 (BBO_F32) or bfloat16 (BBO_BF16)
  *   y         device, [n]; int32 class ids 0..n_classes-1 if n_classes >= 2,
- *             float32 targets if n_classes == 0 (regression)
+ *             int32 labels 0/1 if n_classes == 1 (one logit), float32 targets
+ *             if n_classes == 0 (regression)
  *   fold_idx  device, int32 [n]; row i validates in fold fold_idx[i] and trains
  *             in every other fold; a negative value leaves the row unused
  *   hp        host, [B] suggestions
@@ -95,7 +96,9 @@ int bbo_mlp_workspace_bytes(int64_t n, int32_t d, int32_t n_classes, int32_t n_f
  *   stream    hipStream_t (NULL = default stream)
  *
  * Model: layers z = a W + b with ReLU between them; softmax cross-entropy over
- * n_classes outputs (binary included) or half squared error; penalty
+ * n_classes outputs (n_classes >= 2), the logistic loss log(1 + e^z) - y z on
+ * a single output (n_classes == 1; the second score is the accuracy of the
+ * rule z > 0), or half squared error (n_classes == 0); penalty
  * alpha/(2 m) * |W|^2 with m the rows of the step; Adam (bias corrections in
  * the step size, eps added to sqrt(v)) or SGD with (Nesterov) momentum;
  * constant learning rate; exactly `epochs` passes in a seeded order; a short
@@ -103,7 +106,7 @@ int bbo_mlp_workspace_bytes(int64_t n, int32_t d, int32_t n_classes, int32_t n_f
  * hidden activations, deltas) to bfloat16 and keeps master weights, moments
  * and accumulation in float32.
  *
- * Errors: BBO_INVALID_ARG (null pointer, n < 0, d < 1, n_classes == 1 or < 0,
+ * Errors: BBO_INVALID_ARG (null pointer, n < 0, d < 1, n_classes < 0,
  * n_folds < 1, bad hparams), BBO_UNSUPPORTED, BBO_WORKSPACE_TOO_SMALL,
  * BBO_DEVICE_ERROR (a HIP call failed).  B == 0 is a no-op returning BBO_OK.
  */

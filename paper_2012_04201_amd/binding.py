@@ -111,7 +111,7 @@ def to_device(cfg, device="cuda:0"):
         Xt = torch.from_numpy(np.ascontiguousarray(X).view(np.int16)).to(device).view(torch.bfloat16)
     else:
         Xt = torch.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).to(device)
-    ydt = np.int32 if cfg["n_classes"] >= 2 else np.float32
+    ydt = np.int32 if cfg["n_classes"] >= 1 else np.float32
     yt = torch.from_numpy(np.ascontiguousarray(cfg["y"], dtype=ydt)).to(device)
     ft = torch.from_numpy(np.ascontiguousarray(cfg["fold_idx"], dtype=np.int32)).to(device)
     return Xt, yt, ft

@@ -153,6 +153,13 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
       for (int j = 0; j < c; j++) delta[j] = (expf(z[j] - lse) - (j == yr ? 1.f : 0.f)) * inv_den;
     *aux = best == yr ? 1.f : 0.f;  // a correct prediction
     return lse - z[yr];
+  } else if (n_classes == 1) {
+    // one logit, labels 0/1: log(1 + e^z) - y z, delta (sigmoid(z) - y)/m
+    const int yr = ((const int32_t*)yv)[row];
+    const float zz = z[0];
+    if (WANT_DELTA) delta[0] = (1.f / (1.f + expf(-zz)) - (float)yr) * inv_den;
+    *aux = (zz > 0.f) == (yr != 0) ? 1.f : 0.f;
+    return fmaxf(zz, 0.f) + log1pf(expf(-fabsf(zz))) - (yr ? zz : 0.f);
   } else {
     const float e = z[0] - ((const float*)yv)[row];
     if (WANT_DELTA) delta[0] = e * inv_den;
@@ -361,6 +368,13 @@ struct Trainer {
             D[r * kpL + j] = gv;
             DT[(size_t)j * rows + r] = gv;
           }
+        } else if (P.n_classes == 1) {
+          const int yr = ((const int32_t*)P.y)[row];
+          const float zz = z[0];
+          lsum += (double)(fmaxf(zz, 0.f) + log1pf(expf(-fabsf(zz))) - (yr ? zz : 0.f));
+          const OpT gv = O::cvt((1.f / (1.f + expf(-zz)) - (float)yr) / (float)mb);
+          D[r * kpL] = gv;
+          DT[r] = gv;
         } else {
           const float e = z[0] - ((const float*)P.y)[row];
           lsum += 0.5 * (double)e * (double)e;
@@ -685,7 +699,7 @@ int check_problem(int64_t n, int d, int n_classes, int n_folds, int dtype) {
   if (n > 0x3fffffff) return fail(BBO_UNSUPPORTED, "n too large");
   if (d < 1) return fail(BBO_INVALID_ARG, "d < 1");
   if (d > BBO_MAX_FEATURES) return fail(BBO_UNSUPPORTED, "d > BBO_MAX_FEATURES");
-  if (n_classes == 1 || n_classes < 0) return fail(BBO_INVALID_ARG, "n_classes must be 0 (regression) or >= 2");
+  if (n_classes < 0) return fail(BBO_INVALID_ARG, "n_classes must be 0 (regression), 1 (one logit) or >= 2");
   if (n_classes > BBO_MAX_CLASSES) return fail(BBO_UNSUPPORTED, "n_classes > BBO_MAX_CLASSES");
   if (n_folds < 1) return fail(BBO_INVALID_ARG, "n_folds < 1");
   if (n_folds > 1024) return fail(BBO_UNSUPPORTED, "n_folds > 1024");

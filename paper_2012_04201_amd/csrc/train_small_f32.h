@@ -204,7 +204,7 @@ struct Small {
     yv = 0.f;
     if ((int)threadIdx.x < SM_RC) {
       const int row = rl[threadIdx.x];
-      if (row >= 0) yv = P.n_classes >= 2 ? __int_as_float(((const int32_t*)P.y)[row]) : ((const float*)P.y)[row];
+      if (row >= 0) yv = P.n_classes >= 1 ? __int_as_float(((const int32_t*)P.y)[row]) : ((const float*)P.y)[row];
     }
   }
   // (3) registers -> the LDS tiles (the input-major tile and the labels of parity par)
@@ -416,6 +416,13 @@ struct Small {
           for (int cc = 0; cc < CO; cc++)
             if (cc < c) dl[cc] = (expf(z[cc] - lse) - (cc == yr ? 1.f : 0.f)) * inv_mb;
         }
+      } else if (P.n_classes == 1) {
+        // one logit, labels 0/1: log(1 + e^z) - y z, delta (sigmoid(z) - y)/m
+        const int yr = __float_as_int(yv);
+        const float zz = z[0];
+        l = (double)(fmaxf(zz, 0.f) + log1pf(expf(-fabsf(zz))) - (yr ? zz : 0.f));
+        hit = (zz > 0.f) == (yr != 0) ? 1.0 : 0.0;
+        if (TRAIN) dl[0] = (1.f / (1.f + expf(-zz)) - (float)yr) * inv_mb;
       } else {
         const float e0 = z[0] - yv;
         l = TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;

@@ -619,12 +619,22 @@ struct Tiled {
               if (4 * q + e < c) delta[e] = (expf(z[e] - lse) - (4 * q + e == yr ? 1.f : 0.f)) * inv_mb;
           }
         } else {
-          const float e0 = valid ? z[0] - __builtin_bit_cast(float, tg[r]) : 0.f;
+          // one output: a logit with labels 0/1 (log(1 + e^z) - y z, delta (sigmoid(z) - y)/m), or a
+          // regression value (half squared error, delta (z - y)/m)
+          const bool logit = P.n_classes == 1;
+          const int tv = valid ? tg[r] : 0;
+          const float zz = valid ? z[0] : 0.f;
+          const float e0 = logit ? 1.f / (1.f + expf(-zz)) - (float)tv : zz - __builtin_bit_cast(float, tv);
           if (valid && q == 0) {
-            lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
-            hits += (double)fabsf(e0);  // the absolute error
+            if (logit) {
+              lsum += (double)(fmaxf(zz, 0.f) + log1pf(expf(-fabsf(zz))) - (tv ? zz : 0.f));
+              hits += (zz > 0.f) == (tv != 0);
+            } else {
+              lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+              hits += (double)fabsf(e0);  // the absolute error
+            }
           }
-          if (TRAIN && q == 0) delta[0] = e0 * inv_mb;
+          if (TRAIN && valid && q == 0) delta[0] = e0 * inv_mb;
         }
         if (TRAIN) {
           bf16x4 pk;

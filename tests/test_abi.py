@@ -46,11 +46,13 @@ def test_argument_validation_without_gpu(bb):
     rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(0), C.c_int32(3), C.c_int32(5), hp, C.c_int32(1),
                                    C.c_int32(0), C.byref(out))
     assert rc == bb.INVALID_ARG and b"d < 1" in L.bbo_mlp_last_error()
-    rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(4), C.c_int32(1), C.c_int32(5), hp, C.c_int32(1),
+    rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(4), C.c_int32(-1), C.c_int32(5), hp, C.c_int32(1),
                                    C.c_int32(0), C.byref(out))
     assert rc == bb.INVALID_ARG
     bad = bb.make_hparams([{"hidden": [100000]}])
     rc = L.bbo_mlp_workspace_bytes(C.c_int64(10), C.c_int32(4), C.c_int32(3), C.c_int32(5), bad, C.c_int32(1),
                                    C.c_int32(0), C.byref(out))
     assert rc == bb.UNSUPPORTED
-    assert L.bbo_mlp_param_count(C.c_int32(4), C.c_int32(1), hp) < 0
+    assert L.bbo_mlp_param_count(C.c_int32(4), C.c_int32(-2), hp) < 0
+    # one logit (n_classes = 1) has one output unit, like regression
+    assert bb.bbo_mlp_param_count(4, 1, {"hidden": [8, 9]}) == 4 * 8 + 8 + 8 * 9 + 9 + 9 + 1

@@ -75,7 +75,7 @@ def test_minibatch_rows_bit_exact(bb, oracle, n, bs):
                 assert np.array_equal(got, want), (f, ep, st)
 
 
-@pytest.mark.parametrize("d,hidden,c", [(4, [8], 3), (64, [200], 10), (13, [57], 0), (30, [], 2), (128, [256, 128], 10),
+@pytest.mark.parametrize("d,hidden,c", [(4, [8], 3), (64, [200], 10), (13, [57], 0), (30, [], 2), (128, [256, 128], 10), (11, [7], 1),
                                         (5, [3, 4, 5, 6], 7)])
 def test_init_params_bit_exact(bb, oracle, d, hidden, c):
     hp = {"hidden": hidden, "seed": 987654321012345678}
@@ -93,6 +93,8 @@ def small_problem(seed, n, d, n_classes, bf16=False):
     if n_classes >= 2:
         W = rng.normal(size=(d, n_classes))
         y = (X @ W + 0.5 * rng.normal(size=(n, n_classes))).argmax(1).astype(np.int32)
+    elif n_classes == 1:  # one logit: labels 0/1
+        y = (X @ rng.normal(size=d) + 0.5 * rng.normal(size=n) > 0.2).astype(np.int32)
     else:
         y = (X @ rng.normal(size=d) / np.sqrt(d) + 0.1 * rng.normal(size=n)).astype(np.float32)
     fold = inputs.make_folds(n, 5, seed)
@@ -300,6 +302,60 @@ def test_random_shapes_fp32_steps(bb, oracle, seed):
         for name, sl in layer_slices(d, hidden, c_out):
             assert relerr(g1[sl], rg[sl]) < REL_F32, (case, t, name, "grad")
             assert relerr(th1[sl], rth[sl]) < REL_F32, (case, t, name, "theta")
+
+
+# ------------------------------------------------ single-logit binary head ----
+
+LOGIT_SHAPES = [
+    # n, d, hidden, solver, batch, dtype: every training kernel, one and several chunks of rows
+    (300, 20, [40], "adam", 50, 0),         # LDS-resident fp32
+    (210, 9, [130], "sgd", 0, 0),           # LDS-resident fp32, full batch, ragged row tiles
+    (150, 6, [], "adam", 32, 0),            # no hidden layer
+    (260, 70, [33, 21], "adam", 64, 0),     # generic fp32
+    (400, 64, [96, 80], "adam", 128, 1),    # LDS-tiled bf16, one chunk
+    (640, 128, [200], "sgd", 300, 1),       # LDS-tiled bf16, two chunks
+    (330, 36, [50, 40, 30], "adam", 77, 1), # generic bf16 (three hidden layers)
+]
+
+
+@pytest.mark.parametrize("n,d,hidden,solver,bs,dtype", LOGIT_SHAPES)
+def test_single_logit_head_steps_and_scores(bb, oracle, n, d, hidden, solver, bs, dtype):
+    """n_classes = 1: one output with labels 0/1 and the logistic loss.  Per-step gradients and
+    parameters, the traced loss, both fold scores (loss and accuracy of the rule z > 0)."""
+    cfg = small_problem(1500 + n, n, d, 1, bf16=bool(dtype))
+    assert set(np.unique(cfg["y"])) == {0, 1}
+    hp = {"hidden": hidden, "solver": solver, "nesterov": True, "momentum": 0.8, "batch_size": bs, "alpha": 0.02,
+          "lr": 0.004, "epochs": 5, "seed": 808 + d}
+    f = 3
+    tol = REL_BF16 if dtype else REL_F32
+    n_tr, n_va = int((cfg["fold_idx"] != f).sum()), int((cfg["fold_idx"] == f).sum())
+    spe = -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(10, 5 * spe)
+    X, y, ft = bb.to_device(cfg)
+    assert y.dtype == torch.int32
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, 1, ft, 5, [hp], dtype, want_per_fold=True, trace=(0, f, 0, 2))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], 1, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=2)
+    g, th, ls = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy(), tr["loss"].cpu().numpy()
+    for t in range(2):
+        assert abs(ls[t] - ref["loss"][t]) <= (2e-3 if dtype else 1e-5) * max(1.0, abs(ref["loss"][t])), t
+        for name, sl in layer_slices(d, hidden, 1):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < tol, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < tol, (t, name, "theta")
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, dtype, [t for t in (1, 4, 9) if t < T], T):
+        for name, sl in layer_slices(d, hidden, 1):
+            assert relerr(g1[sl], rg[sl]) < tol, (t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < tol, (t, name, "theta")
+    # scores of all five folds after the free run
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], 1, cfg["fold_idx"], 5, [hp], dtype=dtype)
+    wide = 5 if dtype else 1
+    assert status[0].item() == 0 and rst[0] == 0
+    assert abs(scores[0, 0].item() - rs[0, 0]) < wide * ABS_SCORE
+    got = pf.cpu().numpy()
+    assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 2 * wide * ABS_SCORE
+    for k in range(5):
+        assert 0.0 <= got[0, k, 1] <= 1.0
+        assert abs(got[0, k, 1] - rpf[0, k, 1]) <= (2.0 if dtype else 1.0) / n_va + 1e-6, k
 
 
 # -------------------------------------------- schedule and plateau stop ----
@@ -658,7 +714,7 @@ def test_error_codes(bb):
     X, y, ft = bb.to_device(cfg)
     hp = {"hidden": [8], "epochs": 1}
     with pytest.raises(bb.BboError) as e:
-        bb.bbo_mlp_cv_eval(X, y, 1, ft, 5, [hp], 0)
+        bb.bbo_mlp_cv_eval(X, y, -1, ft, 5, [hp], 0)
     assert e.value.code == bb.INVALID_ARG
     with pytest.raises(bb.BboError) as e:
         bb.bbo_mlp_cv_eval(X, y, 3, ft, 5, [dict(hp, hidden=[5000])], 0)
