@@ -38,6 +38,7 @@
 #include "common.h"
 #include "train_tiled_bf16.h"
 #include "train_small_f32.h"
+#include "train_linear_f32.h"
 
 static_assert(sizeof(bbo_mlp_hparams) == 80, "the hyper-parameter record is part of the ABI");
 
@@ -720,6 +721,8 @@ struct Plan {
   int n_slots = 0;
   bool tiled = false;     // every item fits the LDS-tiled bf16 kernel
   bool small = false;     // every item fits the LDS-resident fp32 kernel
+  bool linear = false;    // no item has a hidden layer: the wavefront-per-model fp32 kernel
+  int waves = 0;          // linear kernel: wavefronts per workgroup
   uint32_t lds_bytes = 0; // dynamic LDS of the chosen kernel
   // workspace byte offsets
   uint64_t o_items = 0, o_queue = 0, o_out = 0, o_train = 0, o_val = 0, o_counts = 0, o_slots = 0, total = 0;
@@ -764,6 +767,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
   // the tiled kernel addresses the input matrix with 32-bit byte offsets
   bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic() && (uint64_t)n * (uint64_t)d * 2 < (1ull << 31);
   bool small = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
+  bool linear = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
   uint64_t tslot = 0;
   uint32_t tlds = 0, slds = 0;
   uint64_t sslot = 256;
@@ -823,6 +827,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
     } else {
       small = false;
     }
+    if (!linear_eligible(it.dims, it.L)) linear = false;
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
@@ -839,16 +844,27 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
   pl.items.swap(sorted);
 
   int max_slots = 0;
-  int rc = (tiled || small) ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
+  int rc = (tiled || small || linear) ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
   if (rc) return rc;
   if (small) max_slots *= 2;  // the kernel's LDS footprint is capped at half a CU's LDS
   pl.tiled = tiled;
   pl.small = small;
+  pl.linear = linear;
   pl.lds_bytes = tiled ? tlds : slds;
   if (tiled) slot = tslot;
   if (small) slot = sslot;  // only the hidden layer's moments live in global memory
+  size_t units = pl.items.size();
+  if (linear) {
+    // a model per wavefront, nothing kept in global memory; as many workgroups as the LDS lets a CU hold
+    const int c_out = n_classes >= 2 ? n_classes : 1;
+    pl.waves = ln_waves(d, c_out);
+    pl.lds_bytes = (uint32_t)pl.waves * ln_wave_bytes(d, c_out);
+    slot = 0;
+    max_slots *= std::max(1, std::min(8, (int)(160u * 1024u / pl.lds_bytes)));
+    units = (pl.items.size() + pl.waves - 1) / pl.waves;
+  }
   pl.slot_bytes = (slot + 255) & ~(uint64_t)255;
-  pl.n_slots = (int)std::min<size_t>(pl.items.size(), (size_t)max_slots);
+  pl.n_slots = (int)std::min<size_t>(units, (size_t)max_slots);
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint64_t o = off;
@@ -997,6 +1013,17 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
     HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
     hipLaunchKernelGGL(fn, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
+  } else if (pl.linear) {
+    const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), np = ((d + 1) * c_out + 63) / 64;
+    typedef void (*linear_fn)(const TrainParams);
+    static const linear_fn fns[4][3] = {
+        {k_train_linear<1, 1>, k_train_linear<1, 4>, k_train_linear<1, 16>},
+        {k_train_linear<2, 1>, k_train_linear<2, 4>, k_train_linear<2, 16>},
+        {k_train_linear<4, 1>, k_train_linear<4, 4>, k_train_linear<4, 16>},
+        {k_train_linear<16, 1>, k_train_linear<16, 4>, k_train_linear<16, 16>}};
+    const linear_fn fn = fns[co == 1 ? 0 : (co == 2 ? 1 : (co == 4 ? 2 : 3))][np <= 1 ? 0 : (np <= 4 ? 1 : 2)];
+    HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
+    hipLaunchKernelGGL(fn, dim3(pl.n_slots), dim3(64 * pl.waves), pl.lds_bytes, s, P);
   } else if (dtype == BBO_F32)
     hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
   else

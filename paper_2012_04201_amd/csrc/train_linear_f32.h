@@ -1,0 +1,371 @@
+// Training / scoring kernel for fp32 models WITHOUT a hidden layer (linear and
+// logistic regression trained like the MLPs: same minibatch order, losses,
+// penalty and optimizers; Section 2, Table 1's linear models).
+//
+// Such a model has (d + 1) * c parameters, a few dozen to a thousand: far too
+// little work for a workgroup.  ONE WAVEFRONT trains one model, several
+// independent wavefronts per workgroup, each taking models from the shared
+// work queue, and the model never leaves the wavefront:
+//   * lane t owns the parameters p = t + 64 i (the packed W[in][out], b[out]
+//     order, so p = k * c + j with k = d for the bias) with their optimizer
+//     moments and the step's gradient, all in registers for the whole run;
+//   * a minibatch is taken in chunks of 64 rows.  The chunk's input rows are
+//     gathered into LDS (row stride odd, so that both access patterns below are
+//     conflict-free) with a ones column for the bias;
+//   * forward: lane = row; the outputs are d + 1 multiply-adds per output from
+//     the lane's LDS row and an LDS copy of the weights (broadcast reads), then
+//     softmax / logistic / squared loss and the output deltas, written to LDS;
+//   * gradient: lane = parameter (k, j): sum over the chunk's rows of
+//     x[row][k] * delta[row][j], accumulated over the chunks of the step;
+//   * the optimizer update runs in the owning lane, which refreshes the LDS copy.
+// No workgroup barrier anywhere: a wavefront's LDS accesses execute in order.
+//
+// LDS per wavefront (floats): xs[64][S] (S = d + 1 made odd), ws[d + 1][CO]
+// (CO = outputs padded to 1, 2, 4 or 16), ds[64][CO].
+#pragma once
+#include "common.h"
+#include "train_tiled_bf16.h"  // OptC, opt_update
+
+namespace {
+
+constexpr int LN_MAX_D = 255;         // inputs
+constexpr int LN_MAX_OUT = 16;        // outputs
+constexpr int LN_MAX_P = 1024;        // parameters: 16 per lane
+constexpr uint32_t LN_LDS_PER_WG = 64 * 1024;
+
+__host__ __device__ inline int ln_stride(int d) { return (d + 1) | 1; }
+__host__ __device__ inline int ln_co(int c) { return c <= 1 ? 1 : (c <= 2 ? 2 : (c <= 4 ? 4 : 16)); }
+__host__ __device__ inline uint32_t ln_wave_bytes(int d, int c) {
+  const int co = ln_co(c);
+  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co) * 4 + 15) & ~15);
+}
+__host__ __device__ inline bool linear_eligible(const int32_t* dims, int L) {
+  return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && (dims[0] + 1) * dims[1] <= LN_MAX_P;
+}
+// wavefronts per workgroup for a problem shape
+__host__ __device__ inline int ln_waves(int d, int c) {
+  const int w = (int)(LN_LDS_PER_WG / ln_wave_bytes(d, c));
+  return w < 1 ? 1 : (w > 4 ? 4 : w);
+}
+
+__device__ __forceinline__ void ln_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ inline double wave_sum(double v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+template <int CO, int NP>
+struct Linear {
+  const TrainParams& P;
+  float* xs;
+  float* ws;
+  float* ds;
+  int lane, d, c, S, Pn;
+  int r0, k0, q64, r64;  // element `lane` of a chunk's row-major block, and the step of 64 elements
+
+  // rows of the chunk -> xs (with the ones column); `row` is the lane's row or -1
+  __device__ __forceinline__ void stage(int row, int mbc) const {
+    const float* X = (const float*)P.X;
+    const int total = mbc * d;
+    int r = r0, k = k0;
+    // eight loads in flight, then their eight LDS stores
+    for (int e0 = 0; e0 < total; e0 += 64 * 8) {
+      float v[8];
+      int at[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int rr = __shfl(row, r & 63);
+        const bool in = e0 + 64 * u + lane < total;
+        v[u] = X[in ? rr * d + k : 0];  // n * d < 2^31 (checked by the host)
+        at[u] = in ? r * S + k : -1;
+        k += r64;
+        r += q64;
+        if (k >= d) {
+          k -= d;
+          r++;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++)
+        if (at[u] >= 0) xs[at[u]] = v[u];
+    }
+    xs[lane * S + d] = row >= 0 ? 1.f : 0.f;
+    ln_lds_fence();
+  }
+
+  // the label (class id or target, as stored) of a row, 0 for no row
+  __device__ __forceinline__ uint32_t label(int row) const { return row >= 0 ? ((const uint32_t*)P.y)[row] : 0u; }
+
+  // outputs of the lane's row
+  __device__ __forceinline__ void forward(float (&z)[CO]) const {
+    const float* xr = xs + lane * S;
+#pragma unroll
+    for (int j = 0; j < CO; j++) z[j] = ws[d * CO + j];
+#pragma unroll 8
+    for (int k = 0; k < d; k++) {
+      const float x = xr[k];
+#pragma unroll
+      for (int j = 0; j < CO; j++) z[j] += x * ws[k * CO + j];
+    }
+  }
+
+  // loss, prediction statistic and (TRAIN) output delta of the lane's row
+  template <bool TRAIN>
+  __device__ __forceinline__ void outputs(const float (&z)[CO], int row, uint32_t yraw, float inv_mb, double& lsum,
+                                          double& hits) const {
+    float dl[CO];
+#pragma unroll
+    for (int j = 0; j < CO; j++) dl[j] = 0.f;
+    if (row >= 0) {
+      if (P.n_classes >= 2) {
+        const int yr = (int)yraw;
+        float mx = z[0], zy = z[0];
+        int best = 0;
+#pragma unroll
+        for (int j = 1; j < CO; j++)
+          if (j < c) {
+            if (z[j] > mx) {
+              mx = z[j];
+              best = j;
+            }
+            zy = j == yr ? z[j] : zy;
+          }
+        float se = 0.f;
+#pragma unroll
+        for (int j = 0; j < CO; j++)
+          if (j < c) se += expf(z[j] - mx);
+        const float lse = mx + logf(se);
+        lsum += (double)(lse - zy);
+        hits += best == yr ? 1.0 : 0.0;
+        if (TRAIN) {
+#pragma unroll
+          for (int j = 0; j < CO; j++)
+            if (j < c) dl[j] = (expf(z[j] - lse) - (j == yr ? 1.f : 0.f)) * inv_mb;
+        }
+      } else if (P.n_classes == 1) {
+        const int yr = (int)yraw;
+        const float zz = z[0];
+        lsum += (double)(fmaxf(zz, 0.f) + log1pf(expf(-fabsf(zz))) - (yr ? zz : 0.f));
+        hits += (zz > 0.f) == (yr != 0) ? 1.0 : 0.0;
+        if (TRAIN) dl[0] = (1.f / (1.f + expf(-zz)) - (float)yr) * inv_mb;
+      } else {
+        const float e0 = z[0] - __uint_as_float(yraw);
+        lsum += TRAIN ? 0.5 * (double)e0 * (double)e0 : (double)e0 * (double)e0;
+        hits += (double)fabsf(e0);  // the absolute error
+        if (TRAIN) dl[0] = e0 * inv_mb;
+      }
+    }
+    if (TRAIN) {
+#pragma unroll
+      for (int j = 0; j < CO; j++) ds[lane * CO + j] = dl[j];
+      ln_lds_fence();
+    }
+  }
+
+  __device__ void run(const ItemDesc& it, int np, const int (&xo)[NP], const int (&jo)[NP]) const {
+    const int f = it.fold, fl = f - P.fold_base;
+    const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
+    const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
+    const int32_t* va = P.val_idx + (int64_t)fl * P.n;
+    const int bs = eff_batch(it.batch_size, n_tr);
+    const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
+    const int epochs = it.epochs, patience = it.patience;
+    const float lr0 = it.lr, alpha = it.alpha, power_t = it.power_t, tol = it.tol, beta1 = it.beta1, beta2 = it.beta2;
+    const uint64_t km = key_model(it.seed, f);
+    const bool traced = P.trace_item == it.b * P.n_folds + fl;
+
+    OptC oc;
+    oc.adam = it.solver == BBO_ADAM;
+    oc.nest = it.nesterov != 0;
+    oc.b1 = beta1;
+    oc.b2 = beta2;
+    oc.omb1 = 1.f - beta1;
+    oc.omb2 = 1.f - beta2;
+    oc.eps = it.eps;
+    oc.mu = it.momentum;
+    oc.lr = lr0;
+    oc.lr_t = lr0;
+    oc.am = 0.f;
+
+    // the lane's parameters and moments
+    float w[NP], m[NP], v[NP];
+    double b1t = 1.0, b2t = 1.0;
+    int64_t gstep = 0;
+    int e0 = 0, st0 = 0;
+    const bool resume = traced && P.state_in && steps > 0;
+    if (resume) {
+      gstep = P.step_begin;
+      e0 = (int)(gstep / steps);
+      st0 = (int)(gstep % steps);
+      for (int64_t i = 0; i < gstep; i++) {  // beta^gstep by repeated products, as the free run builds it
+        b1t *= (double)beta1;
+        b2t *= (double)beta2;
+      }
+    }
+    {
+      const uint64_t kw = key_fold(km, 16), kb = key_fold(km, 17);
+      const float bound = it.bound[0];
+#pragma unroll
+      for (int i = 0; i < NP; i++) {
+        w[i] = m[i] = v[i] = 0.f;
+        const int p = lane + 64 * i;
+        if (i < np && p < Pn) {
+          if (resume) {
+            w[i] = P.state_in[p];
+            m[i] = P.state_in[Pn + p];
+            v[i] = P.state_in[2 * Pn + p];
+          } else {
+            const bool isb = p >= d * c;
+            const uint32_t k24 = (uint32_t)(key_fold(isb ? kb : kw, (uint64_t)(isb ? p - d * c : p)) >> 40);
+            w[i] = bound * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
+          }
+          ws[xo[i] * CO + jo[i]] = w[i];
+        }
+      }
+      ln_lds_fence();
+    }
+
+    Plateau plateau;
+    const bool watch = patience > 0 && steps > 0 && !resume;
+    for (int e = e0; e < epochs; e++) {
+      const uint64_t ke = key_epoch(km, e);
+      if (!oc.adam) oc.lr = epoch_lr(lr0, power_t, e, n_tr);
+      double esum = 0.0;  // the lane's share of the epoch's summed data loss
+      // The lane's row of a chunk and its label are fetched one chunk ahead within the epoch.
+      const int st_first = e == e0 ? st0 : 0;
+      int nrow = -1;
+      if (st_first < steps) {
+        const int lo = st_first * bs, mb = min(bs, n_tr - lo);
+        nrow = lane < min(64, mb) ? tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(lo + lane))] : -1;
+      }
+      uint32_t nlab = label(nrow);
+      for (int st = st_first; st < steps; st++, gstep++) {
+        const int lo = st * bs, mb = min(bs, n_tr - lo);
+        const float inv_mb = 1.f / (float)mb;
+        float g[NP];
+#pragma unroll
+        for (int i = 0; i < NP; i++) g[i] = 0.f;
+        double lstep = 0.0, unused = 0.0;
+        for (int c0 = 0; c0 < mb; c0 += 64) {
+          const int mbc = min(64, mb - c0);
+          const int row = nrow;
+          const uint32_t lab = nlab;
+          {  // the next chunk of the epoch: the rest of this step, else the start of the next one
+            const bool same = c0 + 64 < mb;
+            const int nlo = same ? lo + c0 + 64 : lo + mb;
+            const int nleft = same ? mb - c0 - 64 : (st + 1 < steps ? min(bs, n_tr - nlo) : 0);
+            nrow = lane < min(64, nleft) ? tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(nlo + lane))] : -1;
+          }
+          stage(row, mbc);
+          float z[CO];
+          forward(z);
+          outputs<true>(z, row, lab, inv_mb, lstep, unused);
+          // gradient: the lane's parameters over the chunk's rows
+#pragma unroll 4
+          for (int r = 0; r < mbc; r++) {
+#pragma unroll
+            for (int i = 0; i < NP; i++)
+              if (i < np) g[i] += xs[r * S + xo[i]] * ds[r * CO + jo[i]];
+          }
+          ln_lds_fence();  // the next chunk overwrites xs and ds
+          nlab = label(nrow);
+        }
+        esum += lstep;
+        float* rec = nullptr;
+        if (traced && gstep >= P.step_begin && gstep < P.step_end) {
+          rec = P.trace_out + (gstep - P.step_begin) * (1 + 2 * (int64_t)Pn);
+          double pen = 0.0;
+#pragma unroll
+          for (int i = 0; i < NP; i++)
+            if (i < np && lane + 64 * i < d * c) pen += (double)w[i] * (double)w[i];
+          const double data = wave_sum(lstep) / (double)mb;
+          pen = wave_sum(pen);
+          if (lane == 0) rec[0] = (float)(data + 0.5 * (double)alpha * pen / (double)mb);
+        }
+        oc.am = alpha / (float)mb;
+        if (oc.adam) {
+          b1t *= (double)beta1;
+          b2t *= (double)beta2;
+          oc.lr_t = (float)((double)lr0 * sqrt(1.0 - b2t) / (1.0 - b1t));
+        }
+#pragma unroll
+        for (int i = 0; i < NP; i++) {
+          const int p = lane + 64 * i;
+          if (i < np && p < Pn) {
+            const float gg = p < d * c ? g[i] + oc.am * w[i] : g[i];
+            opt_update(oc, gg, w[i], m[i], v[i]);
+            if (rec) {
+              rec[1 + p] = gg;
+              rec[1 + Pn + p] = w[i];
+            }
+            ws[xo[i] * CO + jo[i]] = w[i];
+          }
+        }
+        ln_lds_fence();
+      }
+      if (watch && plateau.stop_after((float)(wave_sum(esum) / (double)n_tr), tol, patience)) break;
+    }
+
+    // validation score on the held rows
+    double lsum = 0.0, hits = 0.0;
+    int vrow = lane < n_va ? va[lane] : -1;
+    uint32_t vlab = label(vrow);
+    for (int off = 0; off < n_va; off += 64) {
+      const int mbc = min(64, n_va - off);
+      const int row = vrow;
+      const uint32_t lab = vlab;
+      vrow = off + 64 + lane < n_va ? va[off + 64 + lane] : -1;
+      stage(row, mbc);
+      float z[CO];
+      forward(z);
+      outputs<false>(z, row, lab, 0.f, lsum, hits);
+      ln_lds_fence();
+      vlab = label(vrow);
+    }
+    lsum = wave_sum(lsum);
+    hits = wave_sum(hits);
+    if (lane == 0) {
+      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
+      out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
+      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
+    }
+  }
+};
+
+// CO: outputs padded to 1, 2, 4 or 16; NP: parameters per lane (1, 4 or 16).  The launch gives
+// blockDim.x / 64 wavefronts ln_wave_bytes() of dynamic LDS each.
+template <int CO, int NP>
+__global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
+  extern __shared__ __align__(16) char ln_lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = P.d, c = P.n_classes >= 2 ? P.n_classes : 1, S = ln_stride(d), Pn = (d + 1) * c;
+  float* xs = (float*)(ln_lds + (size_t)wave * ln_wave_bytes(d, c));
+  float* ws = xs + 64 * S;
+  float* ds = ws + (d + 1) * CO;
+  Linear<CO, NP> T{P, xs, ws, ds, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
+  // the (in, out) pair of each parameter the lane owns
+  const int np = (Pn + 63) / 64;
+  int xo[NP], jo[NP];
+#pragma unroll
+  for (int i = 0; i < NP; i++) {
+    const int p = lane + 64 * i, pp = p < Pn ? p : 0;
+    xo[i] = pp / c;
+    jo[i] = pp - xo[i] * c;
+  }
+  // columns of ws beyond the model's outputs stay zero
+  for (int i = lane; i < (d + 1) * CO; i += 64) ws[i] = 0.f;
+  ln_lds_fence();
+  for (;;) {
+    // Every lane takes part in the pop (lane 0 adds one, the others nothing) and lane 0's result is the
+    // wavefront's item.  A pop under `if (lane == 0)` must not be used here: the loop body ends with
+    // another branch on the same condition, and the compiler joins the two across the back edge, which
+    // sends lanes 1..63 round the loop on their own, past the pop.
+    __builtin_amdgcn_wave_barrier();
+    const int item = __builtin_amdgcn_readfirstlane(atomicAdd(P.queue, lane == 0 ? 1 : 0));
+    if (item >= P.n_items) break;
+    T.run(((const ItemDesc*)P.items)[item], np, xo, jo);
+  }
+}
+
+}  // namespace

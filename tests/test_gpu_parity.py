@@ -358,6 +358,89 @@ def test_single_logit_head_steps_and_scores(bb, oracle, n, d, hidden, solver, bs
         assert abs(got[0, k, 1] - rpf[0, k, 1]) <= (2.0 if dtype else 1.0) / n_va + 1e-6, k
 
 
+# ----------------------------------------- models without a hidden layer ----
+
+LINEAR_SHAPES = [
+    # n, d, classes, solver, batch: the wavefront-per-model kernel's variants (outputs padded to 1, 2, 4, 16;
+    # 1, 4 or 16 parameters per lane), one and several 64-row chunks per step, ragged last chunk
+    (300, 30, 2, "adam", 57),      # 62 parameters: one per lane
+    (250, 13, 0, "sgd", 0),        # regression, full batch of 200 rows: four chunks
+    (200, 6, 1, "adam", 64),       # one logit
+    (320, 40, 3, "adam", 65),      # 123 parameters
+    (400, 64, 10, "adam", 100),    # 650 parameters
+    (260, 100, 5, "sgd", 1),       # batches of one row
+    (330, 255, 4, "adam", 128),    # the widest input: 1024 parameters, one wavefront per workgroup
+    (270, 63, 16, "sgd", 200),     # the most outputs: 1024 parameters
+    (150, 1, 2, "adam", 33),       # a single feature
+]
+
+
+@pytest.mark.parametrize("n,d,c,solver,bs", LINEAR_SHAPES)
+def test_linear_models_steps_and_scores(bb, oracle, n, d, c, solver, bs):
+    cfg = small_problem(1700 + n, n, d, c)
+    hp = {"hidden": [], "solver": solver, "nesterov": True, "momentum": 0.85, "batch_size": bs, "alpha": 0.03,
+          "lr": 0.004, "epochs": 4, "seed": 606 + d}
+    other = dict(hp, seed=5, lr=0.02, batch_size=17)
+    f = 4
+    c_out = c if c >= 2 else 1
+    n_tr, n_va = int((cfg["fold_idx"] != f).sum()), int((cfg["fold_idx"] == f).sum())
+    spe = -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(12, 4 * spe)
+    X, y, ft = bb.to_device(cfg)
+    t3 = min(3, T)
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [other, hp, other], 0, want_per_fold=True,
+                                                trace=(1, f, 0, t3))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, step_begin=0, step_end=t3)
+    g, th, ls = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy(), tr["loss"].cpu().numpy()
+    for t in range(t3):
+        assert abs(ls[t] - ref["loss"][t]) <= 1e-5 * max(1.0, abs(ref["loss"][t])), t
+        for name, sl in layer_slices(d, [], c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_F32, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_F32, (t, name, "theta")
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 0, [t for t in (1, 5, 11) if t < T], T):
+        for name, sl in layer_slices(d, [], c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_F32, (t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_F32, (t, name, "theta")
+    # both scores of every fold of the three models (two of them equal), against the oracle
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, [other, hp, other])
+    got, sc = pf.cpu().numpy(), scores.cpu().numpy()
+    assert np.array_equal(got[0], got[2]) and np.array_equal(status.cpu().numpy(), rst)
+    assert np.abs(sc[:, 0] - rs[:, 0]).max() < ABS_SCORE
+    assert np.abs(got[:, :, 0] - rpf[:, :, 0]).max() < 2 * ABS_SCORE
+    if c == 0:
+        assert np.abs(got[:, :, 1] - rpf[:, :, 1]).max() < 2 * ABS_SCORE
+    else:
+        assert np.abs(got[:, :, 1] - rpf[:, :, 1]).max() <= 1.0 / n_va + 1e-6
+
+
+def test_linear_models_many_on_one_launch(bb, oracle):
+    """More models than wavefronts in flight, with the plateau stop and the inverse-scaling rate among
+    them: every wavefront takes several models from the queue, one after the other."""
+    cfg = inputs.make_config(3, B=1)
+    rng = np.random.default_rng(77)
+    hps = []
+    for b in range(3000):
+        h = inputs.suggest(rng, n_hidden=0, width=(1, 1), solver="adam" if b % 3 else "sgd", epochs=3, batch=(16, 256),
+                           lr=(1e-4, 1e-2))
+        if b % 5 == 0:
+            h.update(tol=1e-3, n_iter_no_change=1, epochs=12)
+        if b % 3 == 0:
+            h.update(power_t=0.5, nesterov=bool(b % 2))
+        hps.append(h)
+    X, y, ft = bb.to_device(cfg)
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, 2, ft, 5, hps, 0, want_per_fold=True)
+    torch.cuda.synchronize()
+    sc, st, got = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
+    assert np.all(st == 0) and np.all(np.isfinite(sc))
+    pick = [0, 1, 2, 5, 15, 1499, 2998, 2999]
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], 2, cfg["fold_idx"], 5, [hps[b] for b in pick])
+    n_va = len(cfg["y"]) // 5
+    for i, b in enumerate(pick):
+        assert np.abs(got[b, :, 0] - rpf[i, :, 0]).max() < 2 * ABS_SCORE, b
+        assert np.abs(got[b, :, 1] - rpf[i, :, 1]).max() <= 1.0 / n_va + 1e-6, b
+
+
 # -------------------------------------------- schedule and plateau stop ----
 
 CONTROL_SHAPES = [
