@@ -6,41 +6,44 @@
 // little work for a workgroup.  ONE WAVEFRONT trains one model, several
 // independent wavefronts per workgroup, each taking models from the shared
 // work queue, and the model never leaves the wavefront:
-//   * lane t owns the parameters p = t + 64 i (the packed W[in][out], b[out]
-//     order, so p = k * c + j with k = d for the bias) with their optimizer
-//     moments and the step's gradient, all in registers for the whole run;
+//   * lane t owns the rows k = t + 64 i of W[in][out], and lane j < c the bias
+//     of output j, with their optimizer moments and the step's gradient, all in
+//     registers for the whole run;
 //   * a minibatch is taken in chunks of 64 rows.  The chunk's input rows are
 //     gathered into LDS (row stride odd, so that both access patterns below are
-//     conflict-free) with a ones column for the bias;
+//     conflict-free);
 //   * forward: lane = row; the outputs are d + 1 multiply-adds per output from
 //     the lane's LDS row and an LDS copy of the weights (broadcast reads), then
 //     softmax / logistic / squared loss and the output deltas, written to LDS;
-//   * gradient: lane = parameter (k, j): sum over the chunk's rows of
-//     x[row][k] * delta[row][j], accumulated over the chunks of the step;
+//   * gradient: lane = input k: sum over the chunk's rows of x[row][k] *
+//     delta[row][:] (one conflict-free read of x and one broadcast vector read
+//     of the deltas per row; the bias lanes sum their delta column),
+//     accumulated over the chunks of the step;
 //   * the optimizer update runs in the owning lane, which refreshes the LDS copy.
 // No workgroup barrier anywhere: a wavefront's LDS accesses execute in order.
 //
 // LDS per wavefront (floats): xs[64][S] (S = d + 1 made odd), ws[d + 1][CO]
-// (CO = outputs padded to 1, 2, 4 or 16), ds[64][CO].
+// (CO = outputs padded to 1, 2, 4, 8 or 16), ds[64][CO].
 #pragma once
 #include "common.h"
 #include "train_tiled_bf16.h"  // OptC, opt_update
 
 namespace {
 
-constexpr int LN_MAX_D = 255;         // inputs
+constexpr int LN_MAX_D = 256;         // inputs: at most 4 rows of W per lane
 constexpr int LN_MAX_OUT = 16;        // outputs
-constexpr int LN_MAX_P = 1024;        // parameters: 16 per lane
+constexpr int LN_MAX_PER_LANE = 16;   // (rows of W per lane) x (padded outputs)
 constexpr uint32_t LN_LDS_PER_WG = 64 * 1024;
 
 __host__ __device__ inline int ln_stride(int d) { return (d + 1) | 1; }
-__host__ __device__ inline int ln_co(int c) { return c <= 1 ? 1 : (c <= 2 ? 2 : (c <= 4 ? 4 : 16)); }
+__host__ __device__ inline int ln_co(int c) { return c <= 1 ? 1 : (c <= 2 ? 2 : (c <= 4 ? 4 : (c <= 8 ? 8 : 16))); }
+__host__ __device__ inline int ln_ki(int d) { return d <= 64 ? 1 : (d <= 128 ? 2 : 4); }  // rows of W per lane
 __host__ __device__ inline uint32_t ln_wave_bytes(int d, int c) {
   const int co = ln_co(c);
   return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co) * 4 + 15) & ~15);
 }
 __host__ __device__ inline bool linear_eligible(const int32_t* dims, int L) {
-  return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && (dims[0] + 1) * dims[1] <= LN_MAX_P;
+  return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && ln_ki(dims[0]) * ln_co(dims[1]) <= LN_MAX_PER_LANE;
 }
 // wavefronts per workgroup for a problem shape
 __host__ __device__ inline int ln_waves(int d, int c) {
@@ -50,12 +53,42 @@ __host__ __device__ inline int ln_waves(int d, int c) {
 
 __device__ __forceinline__ void ln_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// CO consecutive floats of LDS (16-byte aligned for CO >= 4, 8-byte for CO = 2) as vector accesses
+template <int CO>
+__device__ __forceinline__ void lds_get(const float* p, float (&o)[CO]) {
+  if constexpr (CO >= 4) {
+#pragma unroll
+    for (int q = 0; q < CO / 4; q++) {
+      const f32x4 t = *(const f32x4*)(p + 4 * q);
+#pragma unroll
+      for (int e = 0; e < 4; e++) o[4 * q + e] = t[e];
+    }
+  } else if constexpr (CO == 2) {
+    const float2 t = *(const float2*)p;
+    o[0] = t.x;
+    o[1] = t.y;
+  } else {
+    o[0] = p[0];
+  }
+}
+template <int CO>
+__device__ __forceinline__ void lds_put(float* p, const float (&o)[CO]) {
+  if constexpr (CO >= 4) {
+#pragma unroll
+    for (int q = 0; q < CO / 4; q++) *(f32x4*)(p + 4 * q) = f32x4{o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]};
+  } else if constexpr (CO == 2) {
+    *(float2*)p = float2{o[0], o[1]};
+  } else {
+    p[0] = o[0];
+  }
+}
+
 __device__ inline double wave_sum(double v) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   return v;
 }
 
-template <int CO, int NP>
+template <int CO, int KI>
 struct Linear {
   const TrainParams& P;
   float* xs;
@@ -64,7 +97,7 @@ struct Linear {
   int lane, d, c, S, Pn;
   int r0, k0, q64, r64;  // element `lane` of a chunk's row-major block, and the step of 64 elements
 
-  // rows of the chunk -> xs (with the ones column); `row` is the lane's row or -1
+  // rows of the chunk -> xs; `row` is the lane's row or -1
   __device__ __forceinline__ void stage(int row, int mbc) const {
     const float* X = (const float*)P.X;
     const int total = mbc * d;
@@ -90,7 +123,6 @@ struct Linear {
       for (int u = 0; u < 8; u++)
         if (at[u] >= 0) xs[at[u]] = v[u];
     }
-    xs[lane * S + d] = row >= 0 ? 1.f : 0.f;
     ln_lds_fence();
   }
 
@@ -100,13 +132,14 @@ struct Linear {
   // outputs of the lane's row
   __device__ __forceinline__ void forward(float (&z)[CO]) const {
     const float* xr = xs + lane * S;
-#pragma unroll
-    for (int j = 0; j < CO; j++) z[j] = ws[d * CO + j];
-#pragma unroll 8
+    lds_get<CO>(ws + d * CO, z);
+#pragma unroll 4
     for (int k = 0; k < d; k++) {
       const float x = xr[k];
+      float wk[CO];
+      lds_get<CO>(ws + k * CO, wk);
 #pragma unroll
-      for (int j = 0; j < CO; j++) z[j] += x * ws[k * CO + j];
+      for (int j = 0; j < CO; j++) z[j] += x * wk[j];
     }
   }
 
@@ -157,13 +190,12 @@ struct Linear {
       }
     }
     if (TRAIN) {
-#pragma unroll
-      for (int j = 0; j < CO; j++) ds[lane * CO + j] = dl[j];
+      lds_put<CO>(ds + lane * CO, dl);
       ln_lds_fence();
     }
   }
 
-  __device__ void run(const ItemDesc& it, int np, const int (&xo)[NP], const int (&jo)[NP]) const {
+  __device__ void run(const ItemDesc& it) const {
     const int f = it.fold, fl = f - P.fold_base;
     const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
     const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
@@ -189,7 +221,8 @@ struct Linear {
     oc.am = 0.f;
 
     // the lane's parameters and moments
-    float w[NP], m[NP], v[NP];
+    float w[KI][CO], m[KI][CO], v[KI][CO];
+    float bw = 0.f, bm = 0.f, bv = 0.f;  // lane j < c: the bias of output j
     double b1t = 1.0, b2t = 1.0;
     int64_t gstep = 0;
     int e0 = 0, st0 = 0;
@@ -207,22 +240,36 @@ struct Linear {
       const uint64_t kw = key_fold(km, 16), kb = key_fold(km, 17);
       const float bound = it.bound[0];
 #pragma unroll
-      for (int i = 0; i < NP; i++) {
-        w[i] = m[i] = v[i] = 0.f;
-        const int p = lane + 64 * i;
-        if (i < np && p < Pn) {
-          if (resume) {
-            w[i] = P.state_in[p];
-            m[i] = P.state_in[Pn + p];
-            v[i] = P.state_in[2 * Pn + p];
-          } else {
-            const bool isb = p >= d * c;
-            const uint32_t k24 = (uint32_t)(key_fold(isb ? kb : kw, (uint64_t)(isb ? p - d * c : p)) >> 40);
-            w[i] = bound * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
+      for (int i = 0; i < KI; i++) {
+        const int k = lane + 64 * i;
+#pragma unroll
+        for (int j = 0; j < CO; j++) {
+          w[i][j] = m[i][j] = v[i][j] = 0.f;
+          if (k < d && j < c) {
+            const int p = k * c + j;  // the packed W[in][out], b[out] order
+            if (resume) {
+              w[i][j] = P.state_in[p];
+              m[i][j] = P.state_in[Pn + p];
+              v[i][j] = P.state_in[2 * Pn + p];
+            } else {
+              const uint32_t k24 = (uint32_t)(key_fold(kw, (uint64_t)p) >> 40);
+              w[i][j] = bound * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
+            }
           }
-          ws[xo[i] * CO + jo[i]] = w[i];
+        }
+        if (k < d) lds_put<CO>(ws + k * CO, w[i]);
+      }
+      if (lane < c) {
+        if (resume) {
+          bw = P.state_in[d * c + lane];
+          bm = P.state_in[Pn + d * c + lane];
+          bv = P.state_in[2 * Pn + d * c + lane];
+        } else {
+          const uint32_t k24 = (uint32_t)(key_fold(kb, (uint64_t)lane) >> 40);
+          bw = bound * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
         }
       }
+      if (lane < CO) ws[d * CO + lane] = bw;
       ln_lds_fence();
     }
 
@@ -243,9 +290,12 @@ struct Linear {
       for (int st = st_first; st < steps; st++, gstep++) {
         const int lo = st * bs, mb = min(bs, n_tr - lo);
         const float inv_mb = 1.f / (float)mb;
-        float g[NP];
+        float g[KI][CO];
 #pragma unroll
-        for (int i = 0; i < NP; i++) g[i] = 0.f;
+        for (int i = 0; i < KI; i++)
+#pragma unroll
+          for (int j = 0; j < CO; j++) g[i][j] = 0.f;
+        float bg = 0.f;
         double lstep = 0.0, unused = 0.0;
         for (int c0 = 0; c0 < mb; c0 += 64) {
           const int mbc = min(64, mb - c0);
@@ -261,12 +311,18 @@ struct Linear {
           float z[CO];
           forward(z);
           outputs<true>(z, row, lab, inv_mb, lstep, unused);
-          // gradient: the lane's parameters over the chunk's rows
+          // gradient: the lane's rows of W over the chunk's rows
 #pragma unroll 4
           for (int r = 0; r < mbc; r++) {
+            float dr[CO];
+            lds_get<CO>(ds + r * CO, dr);
 #pragma unroll
-            for (int i = 0; i < NP; i++)
-              if (i < np) g[i] += xs[r * S + xo[i]] * ds[r * CO + jo[i]];
+            for (int i = 0; i < KI; i++) {
+              const float x = xs[r * S + min(lane + 64 * i, d - 1)];
+#pragma unroll
+              for (int j = 0; j < CO; j++) g[i][j] += x * dr[j];
+            }
+            bg += ds[r * CO + min(lane, CO - 1)];
           }
           ln_lds_fence();  // the next chunk overwrites xs and ds
           nlab = label(nrow);
@@ -277,8 +333,10 @@ struct Linear {
           rec = P.trace_out + (gstep - P.step_begin) * (1 + 2 * (int64_t)Pn);
           double pen = 0.0;
 #pragma unroll
-          for (int i = 0; i < NP; i++)
-            if (i < np && lane + 64 * i < d * c) pen += (double)w[i] * (double)w[i];
+          for (int i = 0; i < KI; i++)
+#pragma unroll
+            for (int j = 0; j < CO; j++)
+              if (lane + 64 * i < d && j < c) pen += (double)w[i][j] * (double)w[i][j];
           const double data = wave_sum(lstep) / (double)mb;
           pen = wave_sum(pen);
           if (lane == 0) rec[0] = (float)(data + 0.5 * (double)alpha * pen / (double)mb);
@@ -290,17 +348,29 @@ struct Linear {
           oc.lr_t = (float)((double)lr0 * sqrt(1.0 - b2t) / (1.0 - b1t));
         }
 #pragma unroll
-        for (int i = 0; i < NP; i++) {
-          const int p = lane + 64 * i;
-          if (i < np && p < Pn) {
-            const float gg = p < d * c ? g[i] + oc.am * w[i] : g[i];
-            opt_update(oc, gg, w[i], m[i], v[i]);
-            if (rec) {
-              rec[1 + p] = gg;
-              rec[1 + Pn + p] = w[i];
-            }
-            ws[xo[i] * CO + jo[i]] = w[i];
+        for (int i = 0; i < KI; i++) {
+          const int k = lane + 64 * i;
+          if (k < d) {
+#pragma unroll
+            for (int j = 0; j < CO; j++)
+              if (j < c) {
+                const float gg = g[i][j] + oc.am * w[i][j];
+                opt_update(oc, gg, w[i][j], m[i][j], v[i][j]);
+                if (rec) {
+                  rec[1 + k * c + j] = gg;
+                  rec[1 + Pn + k * c + j] = w[i][j];
+                }
+              }
+            lds_put<CO>(ws + k * CO, w[i]);
           }
+        }
+        if (lane < c) {
+          opt_update(oc, bg, bw, bm, bv);
+          if (rec) {
+            rec[1 + d * c + lane] = bg;
+            rec[1 + Pn + d * c + lane] = bw;
+          }
+          ws[d * CO + lane] = bw;
         }
         ln_lds_fence();
       }
@@ -333,9 +403,9 @@ struct Linear {
   }
 };
 
-// CO: outputs padded to 1, 2, 4 or 16; NP: parameters per lane (1, 4 or 16).  The launch gives
+// CO: outputs padded to 1, 2, 4, 8 or 16; KI: rows of W per lane (1, 2 or 4).  The launch gives
 // blockDim.x / 64 wavefronts ln_wave_bytes() of dynamic LDS each.
-template <int CO, int NP>
+template <int CO, int KI>
 __global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
   extern __shared__ __align__(16) char ln_lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -343,19 +413,7 @@ __global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
   float* xs = (float*)(ln_lds + (size_t)wave * ln_wave_bytes(d, c));
   float* ws = xs + 64 * S;
   float* ds = ws + (d + 1) * CO;
-  Linear<CO, NP> T{P, xs, ws, ds, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
-  // the (in, out) pair of each parameter the lane owns
-  const int np = (Pn + 63) / 64;
-  int xo[NP], jo[NP];
-#pragma unroll
-  for (int i = 0; i < NP; i++) {
-    const int p = lane + 64 * i, pp = p < Pn ? p : 0;
-    xo[i] = pp / c;
-    jo[i] = pp - xo[i] * c;
-  }
-  // columns of ws beyond the model's outputs stay zero
-  for (int i = lane; i < (d + 1) * CO; i += 64) ws[i] = 0.f;
-  ln_lds_fence();
+  Linear<CO, KI> T{P, xs, ws, ds, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
   for (;;) {
     // Every lane takes part in the pop (lane 0 adds one, the others nothing) and lane 0's result is the
     // wavefront's item.  A pop under `if (lane == 0)` must not be used here: the loop body ends with
@@ -364,7 +422,7 @@ __global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
     __builtin_amdgcn_wave_barrier();
     const int item = __builtin_amdgcn_readfirstlane(atomicAdd(P.queue, lane == 0 ? 1 : 0));
     if (item >= P.n_items) break;
-    T.run(((const ItemDesc*)P.items)[item], np, xo, jo);
+    T.run(((const ItemDesc*)P.items)[item]);
   }
 }
 

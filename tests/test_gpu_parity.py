@@ -361,16 +361,18 @@ def test_single_logit_head_steps_and_scores(bb, oracle, n, d, hidden, solver, bs
 # ----------------------------------------- models without a hidden layer ----
 
 LINEAR_SHAPES = [
-    # n, d, classes, solver, batch: the wavefront-per-model kernel's variants (outputs padded to 1, 2, 4, 16;
-    # 1, 4 or 16 parameters per lane), one and several 64-row chunks per step, ragged last chunk
-    (300, 30, 2, "adam", 57),      # 62 parameters: one per lane
+    # n, d, classes, solver, batch: the wavefront-per-model kernel's variants (outputs padded to 1, 2, 4, 8,
+    # 16; 1, 2 or 4 rows of W per lane), one and several 64-row chunks per step, ragged last chunk
+    (300, 30, 2, "adam", 57),
     (250, 13, 0, "sgd", 0),        # regression, full batch of 200 rows: four chunks
     (200, 6, 1, "adam", 64),       # one logit
-    (320, 40, 3, "adam", 65),      # 123 parameters
-    (400, 64, 10, "adam", 100),    # 650 parameters
+    (320, 40, 3, "adam", 65),
+    (400, 64, 10, "adam", 100),
     (260, 100, 5, "sgd", 1),       # batches of one row
-    (330, 255, 4, "adam", 128),    # the widest input: 1024 parameters, one wavefront per workgroup
-    (270, 63, 16, "sgd", 200),     # the most outputs: 1024 parameters
+    (330, 256, 4, "adam", 128),    # the widest input: four rows of W per lane, one wavefront per workgroup
+    (270, 64, 16, "sgd", 200),     # the most outputs
+    (240, 128, 8, "adam", 70),     # two rows of W per lane x 8 outputs
+    (220, 65, 9, "adam", 50),      # one too many for the wavefront kernel: the generic kernel takes it
     (150, 1, 2, "adam", 33),       # a single feature
 ]
 
