@@ -857,8 +857,8 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
   if (linear) {
     // a model per wavefront, nothing kept in global memory; as many workgroups as the LDS lets a CU hold
     const int c_out = n_classes >= 2 ? n_classes : 1;
-    pl.waves = ln_waves(d, c_out);
-    pl.lds_bytes = (uint32_t)pl.waves * ln_wave_bytes(d, c_out);
+    pl.waves = ln_waves(d, c_out, n);
+    pl.lds_bytes = (uint32_t)pl.waves * ln_wave_bytes(d, c_out, n);
     slot = 0;
     max_slots *= std::max(1, std::min(8, (int)(160u * 1024u / pl.lds_bytes)));
     units = (pl.items.size() + pl.waves - 1) / pl.waves;

@@ -23,7 +23,11 @@
 // No workgroup barrier anywhere: a wavefront's LDS accesses execute in order.
 //
 // LDS per wavefront (floats): xs[64][S] (S = d + 1 made odd), ws[d + 1][CO]
-// (CO = outputs padded to 1, 2, 4, 8 or 16), ds[64][CO].
+// (CO = outputs padded to 1, 2, 4, 8 or 16), ds[64][CO], and, for data sets of
+// up to LN_EPOCH_CAP rows, the epoch's row order ep[n]: the seeded permutation
+// is walked for all positions of the epoch at once (a lane that finishes a
+// position's walk starts its next one, so the lanes stay busy), instead of per
+// chunk, where every chunk would wait for its slowest lane.
 #pragma once
 #include "common.h"
 #include "train_tiled_bf16.h"  // OptC, opt_update
@@ -34,20 +38,22 @@ constexpr int LN_MAX_D = 256;         // inputs: at most 4 rows of W per lane
 constexpr int LN_MAX_OUT = 16;        // outputs
 constexpr int LN_MAX_PER_LANE = 16;   // (rows of W per lane) x (padded outputs)
 constexpr uint32_t LN_LDS_PER_WG = 64 * 1024;
+constexpr int LN_EPOCH_CAP = 4096;    // rows whose epoch order is tabled in LDS
 
 __host__ __device__ inline int ln_stride(int d) { return (d + 1) | 1; }
 __host__ __device__ inline int ln_co(int c) { return c <= 1 ? 1 : (c <= 2 ? 2 : (c <= 4 ? 4 : (c <= 8 ? 8 : 16))); }
 __host__ __device__ inline int ln_ki(int d) { return d <= 64 ? 1 : (d <= 128 ? 2 : 4); }  // rows of W per lane
-__host__ __device__ inline uint32_t ln_wave_bytes(int d, int c) {
+__host__ __device__ inline int ln_epoch_rows(int64_t n) { return n <= LN_EPOCH_CAP ? (int)n : 0; }
+__host__ __device__ inline uint32_t ln_wave_bytes(int d, int c, int64_t n) {
   const int co = ln_co(c);
-  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co) * 4 + 15) & ~15);
+  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co + ln_epoch_rows(n)) * 4 + 15) & ~15);
 }
 __host__ __device__ inline bool linear_eligible(const int32_t* dims, int L) {
   return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && ln_ki(dims[0]) * ln_co(dims[1]) <= LN_MAX_PER_LANE;
 }
 // wavefronts per workgroup for a problem shape
-__host__ __device__ inline int ln_waves(int d, int c) {
-  const int w = (int)(LN_LDS_PER_WG / ln_wave_bytes(d, c));
+__host__ __device__ inline int ln_waves(int d, int c, int64_t n) {
+  const int w = (int)(LN_LDS_PER_WG / ln_wave_bytes(d, c, n));
   return w < 1 ? 1 : (w > 4 ? 4 : w);
 }
 
@@ -94,6 +100,7 @@ struct Linear {
   float* xs;
   float* ws;
   float* ds;
+  int32_t* ep;  // the epoch's rows in visiting order, or null: permuted on the fly
   int lane, d, c, S, Pn;
   int r0, k0, q64, r64;  // element `lane` of a chunk's row-major block, and the step of 64 elements
 
@@ -124,6 +131,46 @@ struct Linear {
         if (at[u] >= 0) xs[at[u]] = v[u];
     }
     ln_lds_fence();
+  }
+
+  // ep[p] = row visited at position p of the epoch with key ke
+  __device__ __forceinline__ void epoch_order(uint64_t ke, const int32_t* tr, int n_tr) const {
+    if (n_tr <= 1) {
+      if (lane < n_tr) ep[lane] = 0;
+    } else {
+      const PermDomain dm = perm_domain((uint32_t)n_tr);
+      int p = lane;
+      uint32_t x = (uint32_t)p;
+      while (p < n_tr) {
+        x = perm_step(ke, dm, x);
+        if (x < (uint32_t)n_tr) {
+          ep[p] = (int32_t)x;
+          p += 64;
+          x = (uint32_t)p;
+        }
+      }
+    }
+    ln_lds_fence();
+    // positions in the training list -> rows, eight loads in flight
+    for (int p0 = 0; p0 < n_tr; p0 += 64 * 8) {
+      int32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int q = p0 + 64 * u + lane;
+        v[u] = tr[q < n_tr ? ep[q] : 0];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int q = p0 + 64 * u + lane;
+        if (q < n_tr) ep[q] = v[u];
+      }
+    }
+    ln_lds_fence();
+  }
+  // the lane's row of the chunk of `left` rows that starts at position `pos` of the epoch
+  __device__ __forceinline__ int chunk_row(uint64_t ke, const int32_t* tr, int n_tr, int pos, int left) const {
+    if (lane >= min(64, left)) return -1;
+    return ep ? ep[pos + lane] : tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(pos + lane))];
   }
 
   // the label (class id or target, as stored) of a row, 0 for no row
@@ -283,8 +330,9 @@ struct Linear {
       const int st_first = e == e0 ? st0 : 0;
       int nrow = -1;
       if (st_first < steps) {
-        const int lo = st_first * bs, mb = min(bs, n_tr - lo);
-        nrow = lane < min(64, mb) ? tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(lo + lane))] : -1;
+        if (ep) epoch_order(ke, tr, n_tr);
+        const int lo = st_first * bs;
+        nrow = chunk_row(ke, tr, n_tr, lo, min(bs, n_tr - lo));
       }
       uint32_t nlab = label(nrow);
       for (int st = st_first; st < steps; st++, gstep++) {
@@ -305,7 +353,7 @@ struct Linear {
             const bool same = c0 + 64 < mb;
             const int nlo = same ? lo + c0 + 64 : lo + mb;
             const int nleft = same ? mb - c0 - 64 : (st + 1 < steps ? min(bs, n_tr - nlo) : 0);
-            nrow = lane < min(64, nleft) ? tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(nlo + lane))] : -1;
+            nrow = chunk_row(ke, tr, n_tr, nlo, nleft);
           }
           stage(row, mbc);
           float z[CO];
@@ -410,10 +458,11 @@ __global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
   extern __shared__ __align__(16) char ln_lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = P.d, c = P.n_classes >= 2 ? P.n_classes : 1, S = ln_stride(d), Pn = (d + 1) * c;
-  float* xs = (float*)(ln_lds + (size_t)wave * ln_wave_bytes(d, c));
+  float* xs = (float*)(ln_lds + (size_t)wave * ln_wave_bytes(d, c, P.n));
   float* ws = xs + 64 * S;
   float* ds = ws + (d + 1) * CO;
-  Linear<CO, KI> T{P, xs, ws, ds, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
+  int32_t* ep = ln_epoch_rows(P.n) ? (int32_t*)(ds + 64 * CO) : nullptr;
+  Linear<CO, KI> T{P, xs, ws, ds, ep, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
   for (;;) {
     // Every lane takes part in the pop (lane 0 adds one, the others nothing) and lane 0's result is the
     // wavefront's item.  A pop under `if (lane == 0)` must not be used here: the loop body ends with
