@@ -6,6 +6,7 @@ A "step" is one full evaluation call (fold lists, training of every
 synthetic workload already resident in HBM.  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+    python bench.py --workload cfg3 --linear   # the same suggestions without hidden layers
     python bench.py --copy-probe BYTES     # plain device copy, to calibrate HBM counters
 """
 import argparse
@@ -20,10 +21,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}  # MI355X dense MFMA peaks
+PEAK_VALU_TFLOPS = 157.3  # fp32 vector: 256 CUs x 128 lanes x 2 flop (multiply-add) x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # the sources each workload's training kernel is built from (the host code in bbo_mlp.hip does not count)
 KERNEL_SOURCES = {"k_train_tiled": ["common.h", "train_tiled_bf16.h"], "k_train_small": ["common.h", "train_small_f32.h"],
-                  "k_train": ["common.h", "bbo_mlp.hip"]}
+                  "k_train_linear": ["common.h", "train_linear_f32.h"], "k_train": ["common.h", "bbo_mlp.hip"]}
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
@@ -107,10 +109,12 @@ def cpu_baseline(cfg, seconds_hint=20.0):
             "sample": "first %d suggestions x %d folds x %d epoch(s) of the same workload, %.1f s" % (n_sugg, K, epochs, dt)}
 
 
-def run_workload(idx, steps, warmup, suggestions=0, epochs=0):
+def run_workload(idx, steps, warmup, suggestions=0, epochs=0, linear=False):
     import torch
     from paper_2012_04201_amd import binding, inputs
     cfg = inputs.make_config(idx, B=suggestions or None, epochs=epochs or None)
+    if linear:  # the same suggestions without their hidden layers: linear / logistic regression
+        cfg = dict(cfg, name=cfg["name"] + "_linear", hparams=[dict(h, hidden=[]) for h in cfg["hparams"]])
     flops, model_epochs = inputs.workload_flops(cfg)
     dev = torch.device("cuda:0")
     X, y, ft = binding.to_device(cfg, dev)
@@ -140,13 +144,17 @@ def run_workload(idx, steps, warmup, suggestions=0, epochs=0):
     kern_s = sum(a.elapsed_time(b) for a, b in ev) / len(ev) / 1e3
     per_step = wall / steps
     dname = "bf16" if dt else "f32"
-    kernel = "k_train_tiled" if dt else ("k_train_small" if idx in (0, 2, 3) else "k_train")
+    kernel = "k_train_tiled" if dt else ("k_train_linear" if linear else ("k_train_small" if idx in (0, 2, 3) else "k_train"))
     tflops = flops / per_step / 1e12
     abytes = algorithmic_bytes(cfg)
     traffic = measured_traffic(cfg["name"], kernel)
     mfma = {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_TFLOPS[dname], "unit": "TFLOP/s",
             "frac": flops / kern_s / 1e12 / PEAK_TFLOPS[dname], "traffic": traffic, "kernel": kernel,
             "kernel_ms": kern_s * 1e3}
+    if linear:  # no matrix instructions in this kernel: vector multiply-adds fed from LDS
+        mfma = {"bound": "alu", "achieved": flops / kern_s / 1e12, "peak": PEAK_VALU_TFLOPS, "unit": "TFLOP/s",
+                "frac": flops / kern_s / 1e12 / PEAK_VALU_TFLOPS, "traffic": traffic, "kernel": kernel,
+                "kernel_ms": kern_s * 1e3}
     hbm = {"bound": "hbm", "achieved": abytes / kern_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
            "frac": abytes / kern_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic, "kernel": kernel,
            "kernel_ms": kern_s * 1e3, "algorithmic_bytes": abytes}
@@ -169,6 +177,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--suggestions", type=int, default=0, help="debug: evaluate only the first B suggestions")
     ap.add_argument("--epochs", type=int, default=0, help="debug: override the epoch count")
+    ap.add_argument("--linear", action="store_true",
+                    help="drop the hidden layers of the workload's suggestions (fp32 workloads cfg0..cfg3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true", help="skip the extra cfg3 measurement")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -191,7 +201,9 @@ def main():
         return
 
     idx = int(args.workload[3])
-    cfg, res, mfma, hbm = run_workload(idx, args.steps, args.warmup, args.suggestions, args.epochs)
+    if args.linear and idx == 4:
+        sys.exit("bench.py: --linear goes with the fp32 workloads cfg0..cfg3")
+    cfg, res, mfma, hbm = run_workload(idx, args.steps, args.warmup, args.suggestions, args.epochs, args.linear)
     # cfg4 cannot keep its optimizer state on chip (0.9 MB of fp32 state per model, 256 models in flight):
     # the training kernel is bound by streaming that state, so its roofline is HBM; the MFMA view is kept too.
     # The small fp32 models live in LDS and are bound by MFMA issue and latency.
