@@ -100,6 +100,8 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     budget = seconds_hint * cores * 4e9
     n_sugg = max(1, min(len(hps), -(-cores // K)))
     epochs = int(max(1, min(hps[0]["epochs"], budget / (per_model_epoch * n_sugg * K))))
+    if epochs == hps[0]["epochs"]:  # cheap models at their full epoch count: more suggestions instead
+        n_sugg = int(max(n_sugg, min(len(hps), budget / (per_model_epoch * K * epochs))))
     sample = [dict(h, epochs=epochs) for h in hps[:n_sugg]]
     t0 = time.perf_counter()
     O.cv_eval(cfg["X"], cfg["y"], cfg["n_classes"], cfg["fold_idx"], K, sample, dtype=cfg["dtype"], n_threads=cores)
