@@ -692,6 +692,27 @@ def test_holdout_scores_match_oracle(bb, oracle, idx, kw):
     assert held >= 1
 
 
+@pytest.mark.parametrize("idx,c", [(3, 2), (3, 1), (2, 0), (1, 10)])
+def test_holdout_scores_of_linear_models(bb, oracle, idx, c):
+    """The hold-out split on models without a hidden layer (the wavefront-per-model kernel; idx 1: two rows
+    of outputs per lane is too many, so the generic kernel), with the one-logit head among them."""
+    cfg = with_holdout(inputs.make_config(idx, B=6, epochs=8))
+    assert c == cfg["n_classes"] or (c == 1 and cfg["n_classes"] == 2)
+    hps = [dict(h, hidden=[]) for h in cfg["hparams"]]
+    X, y, ft = bb.to_device(dict(cfg, n_classes=c))
+    scores, status = bb.bbo_mlp_holdout_eval(X, y, c, ft, hps, 0)
+    torch.cuda.synchronize()
+    scores, status = scores.cpu().numpy(), status.cpu().numpy()
+    rs, rst = oracle.holdout_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], hps, dtype=0)
+    n_va = int((cfg["fold_idx"] < 0).sum())
+    assert np.array_equal(status, rst) and np.all(rst == 0)
+    assert np.abs(scores[:, 0] - rs[:, 0]).max() < ABS_SCORE
+    if c == 0:
+        assert np.abs(scores[:, 1] - rs[:, 1]).max() < ABS_SCORE
+    else:
+        assert np.abs(scores[:, 1] - rs[:, 1]).max() <= 1.0 / n_va + 1e-6
+
+
 def test_holdout_without_held_rows_flags_itself(bb):
     cfg = inputs.make_config(0)
     X, y, ft = bb.to_device(cfg)
