@@ -8,7 +8,8 @@
 // the held fold without returning to the host.  Every contraction (forward,
 // data gradient, weight gradient) runs on MFMA with fp32 accumulation; the
 // optimizer update is fused into the weight-gradient epilogue, so the weight
-// gradient is never stored.
+// gradient is never stored.  (Models without a hidden layer are the exception:
+// a wavefront each, on the vector ALU; see train_linear_f32.h.)
 //
 // Operand layout.  MFMA operands are read straight from memory as 16-byte
 // vectors along the contracted index, so every tensor is kept in the layout

@@ -374,6 +374,7 @@ LINEAR_SHAPES = [
     (240, 128, 8, "adam", 70),     # two rows of W per lane x 8 outputs
     (220, 65, 9, "adam", 50),      # one too many for the wavefront kernel: the generic kernel takes it
     (150, 1, 2, "adam", 33),       # a single feature
+    (5000, 20, 3, "adam", 700),    # more rows than the epoch table holds: rows permuted on the fly
 ]
 
 
