@@ -57,28 +57,17 @@ __device__ inline uint32_t perm_index(uint64_t key, uint32_t n, uint32_t p) {
   return x;
 }
 
-// The same permutation one network application at a time, for callers that walk many positions at
-// once: x = p; do x = perm_step(key, dm, x); while (x >= n).
+// The permutation's domain for callers that walk many positions at once with a table of the
+// round function (which sees the round and one half of the position only): n >= 2.
 struct PermDomain {
   int hb;
   uint32_t mask;
 };
-__device__ inline PermDomain perm_domain(uint32_t n) {  // n >= 2
+__device__ inline PermDomain perm_domain(uint32_t n) {
   int bits = 32 - __builtin_clz(n - 1);
   bits += bits & 1;
   if (bits < 2) bits = 2;
   return PermDomain{bits >> 1, (1u << (bits >> 1)) - 1};
-}
-__device__ inline uint32_t perm_step(uint64_t key, PermDomain dm, uint32_t x) {
-  uint32_t Lh = x >> dm.hb, Rh = x & dm.mask;
-#pragma unroll
-  for (uint32_t r = 0; r < 4; r++) {
-    uint32_t F = (uint32_t)key_fold(key, ((uint64_t)r << 32) | Rh) & dm.mask;
-    uint32_t t = Lh ^ F;
-    Lh = Rh;
-    Rh = t;
-  }
-  return (Lh << dm.hb) | Rh;
 }
 
 // ---------------------------------------------------------------------------

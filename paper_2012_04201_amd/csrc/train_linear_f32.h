@@ -27,7 +27,10 @@
 // up to LN_EPOCH_CAP rows, the epoch's row order ep[n]: the seeded permutation
 // is walked for all positions of the epoch at once (a lane that finishes a
 // position's walk starts its next one, so the lanes stay busy), instead of per
-// chunk, where every chunk would wait for its slowest lane.
+// chunk, where every chunk would wait for its slowest lane.  The network's
+// round function depends on the round and on one half of the position only
+// (at most 6 bits here), so its 4 x 2^hb values are tabled first (ft[256]) and a
+// network evaluation costs four LDS reads instead of twelve 64-bit multiplies.
 #pragma once
 #include "common.h"
 #include "train_tiled_bf16.h"  // OptC, opt_update
@@ -46,7 +49,8 @@ __host__ __device__ inline int ln_ki(int d) { return d <= 64 ? 1 : (d <= 128 ? 2
 __host__ __device__ inline int ln_epoch_rows(int64_t n) { return n <= LN_EPOCH_CAP ? (int)n : 0; }
 __host__ __device__ inline uint32_t ln_wave_bytes(int d, int c, int64_t n) {
   const int co = ln_co(c);
-  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co + ln_epoch_rows(n)) * 4 + 15) & ~15);
+  const int epoch_words = ln_epoch_rows(n) ? ln_epoch_rows(n) + 256 : 0;  // the row order and the round-function table
+  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co + epoch_words) * 4 + 15) & ~15);
 }
 __host__ __device__ inline bool linear_eligible(const int32_t* dims, int L) {
   return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && ln_ki(dims[0]) * ln_co(dims[1]) <= LN_MAX_PER_LANE;
@@ -138,11 +142,24 @@ struct Linear {
     if (n_tr <= 1) {
       if (lane < n_tr) ep[lane] = 0;
     } else {
-      const PermDomain dm = perm_domain((uint32_t)n_tr);
+      const PermDomain dm = perm_domain((uint32_t)n_tr);  // n_tr <= 4096: halves of at most 6 bits
+      uint32_t* ft = (uint32_t*)(ep + ln_epoch_rows(P.n));
+      for (int i = lane; i < (4 << dm.hb); i += 64)
+        ft[i] = (uint32_t)key_fold(ke, ((uint64_t)(i >> dm.hb) << 32) | ((uint32_t)i & dm.mask)) & dm.mask;
+      ln_lds_fence();
       int p = lane;
       uint32_t x = (uint32_t)p;
       while (p < n_tr) {
-        x = perm_step(ke, dm, x);
+        {  // one application of the network (the loop body of perm_index) from the table
+          uint32_t Lh = x >> dm.hb, Rh = x & dm.mask;
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            const uint32_t t = Lh ^ ft[(r << dm.hb) + Rh];
+            Lh = Rh;
+            Rh = t;
+          }
+          x = (Lh << dm.hb) | Rh;
+        }
         if (x < (uint32_t)n_tr) {
           ep[p] = (int32_t)x;
           p += 64;
