@@ -596,6 +596,28 @@ def test_full_size_many_studies_launch_sampled(bb, oracle):
     assert np.all((status == 0) == np.isfinite(scores[:, 0]))
 
 
+def test_full_size_linear_launch_sampled(bb, oracle):
+    """The linear-model workload at its full size (the 2,048 suggestions of the many-studies workload
+    without their hidden layers x 5 folds, 100 epochs) as the benchmark launches it; the oracle recomputes
+    a sample (a linear model's run is far less sensitive to rounding than an MLP's: most of the sample
+    is held to the plain score bar)."""
+    cfg = inputs.make_config(3)
+    hps = [dict(h, hidden=[]) for h in cfg["hparams"]]
+    X, y, ft = bb.to_device(cfg)
+    K, c = cfg["n_folds"], cfg["n_classes"]
+    hp_arr = bb.make_hparams(hps)
+    ws = bb.alloc_workspace(bb.bbo_mlp_workspace_bytes(len(cfg["y"]), X.shape[1], c, K, hps, 0, hp_arr), X.device)
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, 0, workspace=ws, hp_arr=hp_arr, want_per_fold=True)
+    again, st2 = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, 0, workspace=ws, hp_arr=hp_arr)
+    torch.cuda.synchronize()
+    assert torch.equal(again, scores) and torch.equal(st2, status)  # which wavefront trains a model does not matter
+    scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
+    assert np.all((status == 0) == np.isfinite(scores[:, 0]))
+    pick = [0, 1, 255, 256, 777, 1024, 1500, 2047]
+    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick])
+    assert n_strict >= 6
+
+
 def test_full_size_scale_up_launch(bb, oracle):
     """The scale-up workload at its full size (1,640 suggestions x 5 folds, 20,000 rows, 50 epochs) in the
     benchmark's launch configuration.  A 50-epoch bf16 run of one model costs the oracle minutes, so the
