@@ -417,6 +417,38 @@ def test_linear_models_steps_and_scores(bb, oracle, n, d, c, solver, bs):
         assert np.abs(got[:, :, 1] - rpf[:, :, 1]).max() <= 1.0 / n_va + 1e-6
 
 
+@pytest.mark.parametrize("n,d,alpha", [(60, 3, 0.0), (60, 3, 3.0), (700, 40, 5.0), (300, 100, 1.0)])
+def test_linear_regression_reaches_the_ridge_solution(bb, n, d, alpha):
+    """A property the oracle has no part in: full-batch gradient descent on a linear model with the
+    squared loss converges to the closed-form ridge solution (intercept unpenalised), and the two
+    scores are the mean squared and mean absolute error of that model on the held rows.  Several
+    chunks of rows per step, one and two rows of W per lane."""
+    rng = np.random.default_rng(40 + d)
+    X = rng.normal(size=(n, d)).astype(np.float32)
+    y = (X @ rng.normal(size=d) / np.sqrt(d) + 0.7 + 0.1 * rng.normal(size=n)).astype(np.float32)
+    fold = np.full(n, 1, dtype=np.int32)
+    fold[: n // 5] = 0
+    tr = np.arange(n // 5, n)
+    Xd, yd = X[tr].astype(np.float64), y[tr].astype(np.float64)
+    E = 600
+    hp = {"hidden": [], "solver": "sgd", "momentum": 0.0, "lr": 0.3, "alpha": alpha, "batch_size": 0, "epochs": E,
+          "seed": 2}
+    cfg = {"X": X, "y": y, "n_classes": 0, "dtype": 0, "fold_idx": fold}
+    Xg, yg, ft = bb.to_device(cfg)
+    scores, status, pf, trc = bb.bbo_mlp_cv_eval(Xg, yg, 0, ft, 2, [hp], 0, want_per_fold=True, trace=(0, 0, E - 1, E))
+    torch.cuda.synchronize()
+    th = trc["theta_after"][0].cpu().numpy().astype(np.float64)
+    w, b = th[:d], th[d]
+    Xc, yc = Xd - Xd.mean(0), yd - yd.mean()
+    w_ref = np.linalg.solve(Xc.T @ Xc + alpha * np.eye(d), Xc.T @ yc)
+    b_ref = yd.mean() - Xd.mean(0) @ w_ref
+    assert np.abs(w - w_ref).max() < 2e-5 and abs(b - b_ref) < 2e-5
+    pred = X[: n // 5].astype(np.float64) @ w_ref + b_ref
+    got = pf.cpu().numpy()[0, 0]
+    assert abs(got[0] - np.mean((pred - y[: n // 5]) ** 2)) < 1e-5
+    assert abs(got[1] - np.mean(np.abs(pred - y[: n // 5]))) < 1e-5
+
+
 def test_linear_models_many_on_one_launch(bb, oracle):
     """More models than wavefronts in flight, with the plateau stop and the inverse-scaling rate among
     them: every wavefront takes several models from the queue, one after the other."""
