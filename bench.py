@@ -182,7 +182,7 @@ def main():
     ap.add_argument("--linear", action="store_true",
                     help="drop the hidden layers of the workload's suggestions (fp32 workloads cfg0..cfg3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-secondary", action="store_true", help="skip the extra cfg3 measurement")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the extra cfg3 measurements")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="only run a plain device-to-device copy of BYTES (HBM counter calibration)")
     args = ap.parse_args()
@@ -225,6 +225,10 @@ def main():
         out["secondary"] = {"config": r3["config"], "value": r3["value"], "unit": "model-epochs/s",
                             "ms_per_step": r3["ms_per_step"], "dtype": r3["dtype"], "tflops": r3["tflops"],
                             "roofline": m3}
+        _, rl, ml, _ = run_workload(3, 3, 1, linear=True)
+        out["secondary_linear"] = {"config": rl["config"], "value": rl["value"], "unit": "model-epochs/s",
+                                   "ms_per_step": rl["ms_per_step"], "dtype": rl["dtype"], "tflops": rl["tflops"],
+                                   "roofline": ml}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
