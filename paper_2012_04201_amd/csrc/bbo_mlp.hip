@@ -170,8 +170,12 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
   }
 }
 
+// The training kernels.  Every suggestion of a call goes to the fastest kernel that takes its shape, so
+// a suggestion's scores do not depend on which other suggestions share its call.
+enum { KC_TILED = 0, KC_SMALL = 1, KC_LINEAR = 2, KC_GENERIC = 3, KC_N = 4 };
+
 // ---------------------------------------------------------------------------
-// Fold lists (ascending), one workgroup per list; also resets the work queue.
+// Fold lists (ascending), one workgroup per list; also resets the work queues.
 // List k is fold fold_base + k.  Fold -1 is the hold-out split: rows of every
 // fold train, rows of none are scored.
 // ---------------------------------------------------------------------------
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(NTHREADS) void k_fold_lists(const int32_t* __restri
   __shared__ int wtr[NTHREADS / 64], wva[NTHREADS / 64];
   __shared__ int base_tr, base_va;
   const int f = blockIdx.x, fold = (int)blockIdx.x + fold_base, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (f == 0 && tid == 0 && queue) *queue = 0;
+  if (f == 0 && tid < KC_N && queue) queue[tid] = 0;  // one work-queue counter per training kernel
   if (tid == 0) base_tr = base_va = 0;
   __syncthreads();
   for (int64_t c0 = 0; c0 < n; c0 += NTHREADS) {
@@ -716,17 +720,22 @@ void fill_dims(const bbo_mlp_hparams& h, int d, int n_classes, int32_t* dims, in
   dims[*L] = n_classes >= 2 ? n_classes : 1;
 }
 
+struct SubPlan {
+  std::vector<ItemDesc> items;  // this kernel's items, most expensive first
+  uint64_t slot_bytes = 0;      // global memory per resident workgroup
+  int n_slots = 0;              // workgroups to launch
+  uint32_t lds_bytes = 0;       // dynamic LDS per workgroup
+  int waves = 0;                // linear kernel: wavefronts per workgroup
+  size_t item_bytes = 0;        // size of its item record
+  uint64_t o_items = 0;         // workspace byte offset of its item array
+};
+
 struct Plan {
-  std::vector<ItemDesc> items;  // sorted, most expensive first
-  uint64_t slot_bytes = 0;
-  int n_slots = 0;
-  bool tiled = false;     // every item fits the LDS-tiled bf16 kernel
-  bool small = false;     // every item fits the LDS-resident fp32 kernel
-  bool linear = false;    // no item has a hidden layer: the wavefront-per-model fp32 kernel
-  int waves = 0;          // linear kernel: wavefronts per workgroup
-  uint32_t lds_bytes = 0; // dynamic LDS of the chosen kernel
-  // workspace byte offsets
-  uint64_t o_items = 0, o_queue = 0, o_out = 0, o_train = 0, o_val = 0, o_counts = 0, o_slots = 0, total = 0;
+  SubPlan sub[KC_N];
+  size_t n_items = 0;
+  // workspace byte offsets; the kernels run one after the other and share the slot region
+  uint64_t o_items = 0, items_bytes = 0, o_queue = 0, o_out = 0, o_train = 0, o_val = 0, o_counts = 0, o_slots = 0,
+           total = 0;
 };
 
 int device_slots(int dtype, int* out) {
@@ -765,19 +774,22 @@ bool force_generic() {
 int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_base, const bbo_mlp_hparams* hp, int B,
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
-  // the tiled kernel addresses the input matrix with 32-bit byte offsets
-  bool tiled = dtype == BBO_BF16 && B > 0 && !force_generic() && (uint64_t)n * (uint64_t)d * 2 < (1ull << 31);
-  bool small = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
-  bool linear = dtype == BBO_F32 && B > 0 && !force_generic() && n * (int64_t)d < 0x7fffffff;
-  uint64_t tslot = 0;
-  uint32_t tlds = 0, slds = 0;
-  uint64_t sslot = 256;
-  pl.items.clear();
-  pl.items.reserve((size_t)B * n_folds);
-  std::vector<double> cost;
-  cost.reserve((size_t)B * n_folds);
+  const bool fast = !force_generic();
+  // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
+  const bool tiled_ok = fast && dtype == BBO_BF16 && (uint64_t)n * (uint64_t)d * 2 < (1ull << 31);
+  const bool f32_ok = fast && dtype == BBO_F32 && n * (int64_t)d < 0x7fffffff;
   const double n_tr_est = n_folds > 1 && fold_base >= 0 ? (double)n * (n_folds - 1) / n_folds : (double)n;
-  uint64_t slot = 0;
+  std::vector<double> cost[KC_N];
+  for (int k = 0; k < KC_N; k++) {
+    pl.sub[k] = SubPlan();
+    pl.sub[k].items.reserve((size_t)B * n_folds);
+    cost[k].reserve((size_t)B * n_folds);
+  }
+  pl.sub[KC_TILED].item_bytes = sizeof(TItem);
+  pl.sub[KC_SMALL].item_bytes = sizeof(SItem);
+  pl.sub[KC_LINEAR].item_bytes = sizeof(ItemDesc);
+  pl.sub[KC_GENERIC].item_bytes = sizeof(ItemDesc);
+  pl.sub[KC_SMALL].slot_bytes = 256;
   for (int b = 0; b < B; b++) {
     const bbo_mlp_hparams& h = hp[b];
     ItemDesc it;
@@ -807,65 +819,69 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
       fps += 2.0 * it.dims[l] * it.dims[l + 1] * (l == 0 ? 2 : 3);
       params += (double)it.dims[l] * it.dims[l + 1];
     }
-    Layout y;
-    make_layout(y, it.dims, it.L, it.rows_cap, kstep, opsz);
-    slot = std::max<uint64_t>(slot, y.total);
-    if (tiled && tiled_eligible(it.dims, it.L)) {
+    // the fastest kernel that takes this shape
+    int k = KC_GENERIC;
+    if (tiled_ok && tiled_eligible(it.dims, it.L)) {
       TLay ty;
       make_tlay(ty, it.dims, it.L);
-      tslot = std::max<uint64_t>(tslot, ty.total);
-      tlds = std::max<uint32_t>(tlds, ty.lds_total);
-      if (ty.lds_total > TB_LDS_LIMIT) tiled = false;
-    } else {
-      tiled = false;
-    }
-    if (small && small_eligible(it.dims, it.L)) {
+      if (ty.lds_total <= TB_LDS_LIMIT) {
+        k = KC_TILED;
+        pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, ty.total);
+        pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, ty.lds_total);
+      }
+    } else if (f32_ok && small_eligible(it.dims, it.L)) {
       SLay sy;
       make_slay(sy, it.dims, n);
-      slds = std::max<uint32_t>(slds, sy.lds_total);
-      sslot = std::max<uint64_t>(sslot, 2ull * sy.HP * sy.ldw * 4);
-      if (sy.lds_total > SM_LDS_LIMIT) small = false;
-    } else {
-      small = false;
+      if (sy.lds_total <= SM_LDS_LIMIT) {
+        k = KC_SMALL;  // only the hidden layer's moments live in global memory
+        pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, 2ull * sy.HP * sy.ldw * 4);
+        pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, sy.lds_total);
+      }
+    } else if (f32_ok && linear_eligible(it.dims, it.L)) {
+      k = KC_LINEAR;  // a model per wavefront, nothing kept in global memory
     }
-    if (!linear_eligible(it.dims, it.L)) linear = false;
+    if (k == KC_GENERIC) {
+      Layout y;
+      make_layout(y, it.dims, it.L, it.rows_cap, kstep, opsz);
+      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, y.total);
+    }
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
       it.fold = f + fold_base;
-      pl.items.push_back(it);
-      cost.push_back(c);
+      pl.sub[k].items.push_back(it);
+      cost[k].push_back(c);
     }
   }
-  std::vector<int> order(pl.items.size());
-  for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b2) { return cost[a] > cost[b2]; });
-  std::vector<ItemDesc> sorted(pl.items.size());
-  for (size_t i = 0; i < order.size(); i++) sorted[i] = pl.items[order[i]];
-  pl.items.swap(sorted);
-
-  int max_slots = 0;
-  int rc = (tiled || small || linear) ? device_cus(&max_slots) : device_slots(dtype, &max_slots);
-  if (rc) return rc;
-  if (small) max_slots *= 2;  // the kernel's LDS footprint is capped at half a CU's LDS
-  pl.tiled = tiled;
-  pl.small = small;
-  pl.linear = linear;
-  pl.lds_bytes = tiled ? tlds : slds;
-  if (tiled) slot = tslot;
-  if (small) slot = sslot;  // only the hidden layer's moments live in global memory
-  size_t units = pl.items.size();
-  if (linear) {
-    // a model per wavefront, nothing kept in global memory; as many workgroups as the LDS lets a CU hold
-    const int c_out = n_classes >= 2 ? n_classes : 1;
-    pl.waves = ln_waves(d, c_out, n);
-    pl.lds_bytes = (uint32_t)pl.waves * ln_wave_bytes(d, c_out, n);
-    slot = 0;
-    max_slots *= std::max(1, std::min(8, (int)(160u * 1024u / pl.lds_bytes)));
-    units = (pl.items.size() + pl.waves - 1) / pl.waves;
+  pl.n_items = (size_t)B * n_folds;
+  uint64_t slots_region = 0;
+  for (int k = 0; k < KC_N; k++) {
+    SubPlan& sp = pl.sub[k];
+    if (sp.items.empty()) continue;
+    std::vector<int> order(sp.items.size());
+    for (size_t i = 0; i < order.size(); i++) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b2) { return cost[k][a] > cost[k][b2]; });
+    std::vector<ItemDesc> sorted(sp.items.size());
+    for (size_t i = 0; i < order.size(); i++) sorted[i] = sp.items[order[i]];
+    sp.items.swap(sorted);
+    int max_slots = 0;
+    int rc = k == KC_GENERIC ? device_slots(dtype, &max_slots) : device_cus(&max_slots);
+    if (rc) return rc;
+    size_t units = sp.items.size();
+    if (k == KC_SMALL) max_slots *= 2;  // the kernel's LDS footprint is capped at half a CU's LDS
+    if (k == KC_LINEAR) {
+      // as many workgroups as the LDS lets a CU hold, each of `waves` wavefronts with a model apiece
+      const int c_out = n_classes >= 2 ? n_classes : 1;
+      sp.waves = ln_waves(d, c_out, n);
+      sp.lds_bytes = (uint32_t)sp.waves * ln_wave_bytes(d, c_out, n);
+      max_slots *= std::max(1, std::min(8, (int)(160u * 1024u / sp.lds_bytes)));
+      units = (sp.items.size() + sp.waves - 1) / sp.waves;
+    }
+    sp.slot_bytes = (sp.slot_bytes + 255) & ~(uint64_t)255;
+    if (k == KC_LINEAR) sp.slot_bytes = 0;
+    sp.n_slots = (int)std::min<size_t>(units, (size_t)max_slots);
+    slots_region = std::max<uint64_t>(slots_region, sp.slot_bytes * (uint64_t)sp.n_slots);
   }
-  pl.slot_bytes = (slot + 255) & ~(uint64_t)255;
-  pl.n_slots = (int)std::min<size_t>(units, (size_t)max_slots);
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint64_t o = off;
@@ -873,17 +889,19 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
     return o;
   };
   const uint64_t nn = (uint64_t)std::max<int64_t>(n, 1);
-  pl.o_items = take((tiled ? sizeof(TItem) : small ? sizeof(SItem) : sizeof(ItemDesc)) *
-                    std::max<size_t>(pl.items.size(), 1));
-  pl.o_queue = take(256);
-  pl.o_out = take(8ull * std::max<size_t>(pl.items.size(), 1));
+  pl.o_items = off;
+  for (int k = 0; k < KC_N; k++) pl.sub[k].o_items = take(pl.sub[k].item_bytes * pl.sub[k].items.size());
+  pl.items_bytes = off - pl.o_items;
+  pl.o_queue = take(256);  // one counter per kernel
+  pl.o_out = take(8ull * std::max<size_t>(pl.n_items, 1));
   pl.o_train = take(4ull * nn * n_folds);
   pl.o_val = take(4ull * nn * n_folds);
   pl.o_counts = take(8ull * n_folds);
-  pl.o_slots = take(pl.slot_bytes * (uint64_t)std::max(pl.n_slots, 1));
+  pl.o_slots = take(std::max<uint64_t>(slots_region, 256));
   pl.total = off;
   return BBO_OK;
 }
+
 
 // Pinned staging for the item list: one buffer per host thread, reused once
 // the previous call's copy has completed.
@@ -953,24 +971,33 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   if (workspace_bytes < pl.total) return fail(BBO_WORKSPACE_TOO_SMALL, "workspace too small");
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  if (pl.tiled) {
-    std::vector<TItem> ti(pl.items.size());
-    for (size_t i = 0; i < ti.size(); i++) {
-      ti[i].d = pl.items[i];
-      make_tlay(ti[i].y, pl.items[i].dims, pl.items[i].L);
+  {
+    // the item arrays of all kernels, laid out as in the workspace, in one staged copy
+    std::vector<char> blob(pl.items_bytes, 0);
+    for (int k = 0; k < KC_N; k++) {
+      const SubPlan& sp = pl.sub[k];
+      char* at = blob.data() + (sp.o_items - pl.o_items);
+      for (size_t i = 0; i < sp.items.size(); i++) {
+        if (k == KC_TILED) {
+          TItem ti;
+          memset(&ti, 0, sizeof(ti));
+          ti.d = sp.items[i];
+          make_tlay(ti.y, sp.items[i].dims, sp.items[i].L);
+          memcpy(at + i * sizeof(TItem), &ti, sizeof(TItem));
+        } else if (k == KC_SMALL) {
+          SItem si;
+          memset(&si, 0, sizeof(si));
+          si.d = sp.items[i];
+          make_slay(si.y, sp.items[i].dims, n);
+          memcpy(at + i * sizeof(SItem), &si, sizeof(SItem));
+        } else {
+          memcpy(at + i * sizeof(ItemDesc), &sp.items[i], sizeof(ItemDesc));
+        }
+      }
     }
-    rc = stage_items(ti.data(), ti.size() * sizeof(TItem), ws + pl.o_items, s);
-  } else if (pl.small) {
-    std::vector<SItem> si(pl.items.size());
-    for (size_t i = 0; i < si.size(); i++) {
-      si[i].d = pl.items[i];
-      make_slay(si[i].y, pl.items[i].dims, n);
-    }
-    rc = stage_items(si.data(), si.size() * sizeof(SItem), ws + pl.o_items, s);
-  } else {
-    rc = stage_items(pl.items.data(), pl.items.size() * sizeof(ItemDesc), ws + pl.o_items, s);
+    rc = stage_items(blob.data(), blob.size(), ws + pl.o_items, s);
+    if (rc) return rc;
   }
-  if (rc) return rc;
 
   TrainParams P;
   memset(&P, 0, sizeof(P));
@@ -979,60 +1006,68 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   P.train_idx = (const int32_t*)(ws + pl.o_train);
   P.val_idx = (const int32_t*)(ws + pl.o_val);
   P.counts = (const int32_t*)(ws + pl.o_counts);
-  P.items = ws + pl.o_items;
-  P.queue = (int32_t*)(ws + pl.o_queue);
   P.item_out = (float*)(ws + pl.o_out);
   P.slots = ws + pl.o_slots;
-  P.slot_bytes = pl.slot_bytes;
   P.n = n;
   P.d = d;
   P.n_classes = n_classes;
   P.n_folds = n_folds;
   P.fold_base = fold_base;
-  P.n_items = (int)pl.items.size();
   P.trace_item = traced ? trace_b * n_folds + trace_fold : -1;
   P.step_begin = step_begin;
   P.step_end = step_end;
   P.trace_out = trace_out;
   P.state_in = traced ? state_in : nullptr;
 
+  int32_t* queues = (int32_t*)(ws + pl.o_queue);  // one work-queue counter per kernel, reset by k_fold_lists
   hipLaunchKernelGGL(k_fold_lists, dim3(n_folds), dim3(NTHREADS), 0, s, fold_idx, n, (int32_t*)(ws + pl.o_train),
-                     (int32_t*)(ws + pl.o_val), (int32_t*)(ws + pl.o_counts), P.queue, fold_base);
+                     (int32_t*)(ws + pl.o_val), (int32_t*)(ws + pl.o_counts), queues, fold_base);
   HIP_TRY(hipGetLastError());
-  if (pl.tiled) {
-    HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)pl.lds_bytes));
-    hipLaunchKernelGGL(k_train_tiled, dim3(pl.n_slots), dim3(TB_THREADS), pl.lds_bytes, s, P);
-  } else if (pl.small) {
-    const int kt = d + 1 <= 16 ? 1 : (d + 1 <= 32 ? 2 : 4);
-    const int c_out = n_classes >= 2 ? n_classes : 1, co = c_out <= 2 ? c_out : 4;
-    typedef void (*small_fn)(const TrainParams);
-    static const small_fn fns[3][3] = {
-        {k_train_small<1, 1>, k_train_small<1, 2>, k_train_small<1, 4>},
-        {k_train_small<2, 1>, k_train_small<2, 2>, k_train_small<2, 4>},
-        {k_train_small<4, 1>, k_train_small<4, 2>, k_train_small<4, 4>}};
-    const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
-    HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
-    hipLaunchKernelGGL(fn, dim3(pl.n_slots), dim3(SM_THREADS), pl.lds_bytes, s, P);
-  } else if (pl.linear) {
-    const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), ki = ln_ki(d);
-    typedef void (*linear_fn)(const TrainParams);
-    // [padded outputs 1, 2, 4, 8, 16][rows of W per lane 1, 2, 4], at most 16 parameters per lane
-    static const linear_fn fns[5][3] = {
-        {k_train_linear<1, 1>, k_train_linear<1, 2>, k_train_linear<1, 4>},
-        {k_train_linear<2, 1>, k_train_linear<2, 2>, k_train_linear<2, 4>},
-        {k_train_linear<4, 1>, k_train_linear<4, 2>, k_train_linear<4, 4>},
-        {k_train_linear<8, 1>, k_train_linear<8, 2>, nullptr},
-        {k_train_linear<16, 1>, nullptr, nullptr}};
-    const linear_fn fn = fns[co == 1 ? 0 : (co == 2 ? 1 : (co == 4 ? 2 : (co == 8 ? 3 : 4)))][ki == 1 ? 0 : (ki == 2 ? 1 : 2)];
-    if (!fn) return fail(BBO_DEVICE_ERROR, "no kernel for this linear shape");  // ruled out by linear_eligible()
-    HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes));
-    hipLaunchKernelGGL(fn, dim3(pl.n_slots), dim3(64 * pl.waves), pl.lds_bytes, s, P);
-  } else if (dtype == BBO_F32)
-    hipLaunchKernelGGL(k_train<float>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
-  else
-    hipLaunchKernelGGL(k_train<__bf16>, dim3(pl.n_slots), dim3(NTHREADS), 0, s, P);
-  HIP_TRY(hipGetLastError());
+  // one launch per kernel that has items, one after the other on the caller's stream
+  for (int k = 0; k < KC_N; k++) {
+    const SubPlan& sp = pl.sub[k];
+    if (sp.items.empty()) continue;
+    P.items = ws + sp.o_items;
+    P.queue = queues + k;
+    P.slot_bytes = sp.slot_bytes;
+    P.n_items = (int)sp.items.size();
+    if (k == KC_TILED) {
+      HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)sp.lds_bytes));
+      hipLaunchKernelGGL(k_train_tiled, dim3(sp.n_slots), dim3(TB_THREADS), sp.lds_bytes, s, P);
+    } else if (k == KC_SMALL) {
+      const int kt = d + 1 <= 16 ? 1 : (d + 1 <= 32 ? 2 : 4);
+      const int c_out = n_classes >= 2 ? n_classes : 1, co = c_out <= 2 ? c_out : 4;
+      typedef void (*small_fn)(const TrainParams);
+      static const small_fn fns[3][3] = {
+          {k_train_small<1, 1>, k_train_small<1, 2>, k_train_small<1, 4>},
+          {k_train_small<2, 1>, k_train_small<2, 2>, k_train_small<2, 4>},
+          {k_train_small<4, 1>, k_train_small<4, 2>, k_train_small<4, 4>}};
+      const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
+      HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes));
+      hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(SM_THREADS), sp.lds_bytes, s, P);
+    } else if (k == KC_LINEAR) {
+      const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), ki = ln_ki(d);
+      typedef void (*linear_fn)(const TrainParams);
+      // [padded outputs 1, 2, 4, 8, 16][rows of W per lane 1, 2, 4], at most 16 parameters per lane
+      static const linear_fn fns[5][3] = {
+          {k_train_linear<1, 1>, k_train_linear<1, 2>, k_train_linear<1, 4>},
+          {k_train_linear<2, 1>, k_train_linear<2, 2>, k_train_linear<2, 4>},
+          {k_train_linear<4, 1>, k_train_linear<4, 2>, k_train_linear<4, 4>},
+          {k_train_linear<8, 1>, k_train_linear<8, 2>, nullptr},
+          {k_train_linear<16, 1>, nullptr, nullptr}};
+      const linear_fn fn =
+          fns[co == 1 ? 0 : (co == 2 ? 1 : (co == 4 ? 2 : (co == 8 ? 3 : 4)))][ki == 1 ? 0 : (ki == 2 ? 1 : 2)];
+      if (!fn) return fail(BBO_DEVICE_ERROR, "no kernel for this linear shape");  // ruled out by linear_eligible()
+      HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes));
+      hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(64 * sp.waves), sp.lds_bytes, s, P);
+    } else if (dtype == BBO_F32) {
+      hipLaunchKernelGGL(k_train<float>, dim3(sp.n_slots), dim3(NTHREADS), 0, s, P);
+    } else {
+      hipLaunchKernelGGL(k_train<__bf16>, dim3(sp.n_slots), dim3(NTHREADS), 0, s, P);
+    }
+    HIP_TRY(hipGetLastError());
+  }
   hipLaunchKernelGGL(k_reduce, dim3((B + 255) / 256), dim3(256), 0, s, P.item_out, B, n_folds, scores, status,
                      per_fold);
   HIP_TRY(hipGetLastError());

@@ -789,6 +789,36 @@ def test_batch_composition_invariance_and_determinism(bb):
     assert torch.equal(s3, s1[order])
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_mixed_shapes_in_one_call_keep_their_kernels(bb, oracle, dtype):
+    """Suggestions whose shapes go to different training kernels in ONE call: every suggestion's scores are
+    bit-identical to those of a call that holds it alone (so the kernel it runs on does not depend on its
+    companions), the traced item is found in whichever kernel has it, and the scores agree with the oracle."""
+    n, d, c = 300, 24, 3
+    cfg = small_problem(77 + dtype, n, d, c, bf16=bool(dtype))
+    base = {"solver": "adam", "batch_size": 64, "alpha": 0.01, "lr": 0.003, "epochs": 3}
+    shapes = [[20], [], [40, 24], [300], [], [33], [50, 40, 30], [96, 80]]
+    hps = [dict(base, hidden=h, seed=900 + i, solver="sgd" if i % 3 == 2 else "adam") for i, h in enumerate(shapes)]
+    X, y, ft = bb.to_device(cfg)
+    f, tb = 1, 2
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, hps, dtype, want_per_fold=True, trace=(tb, f, 0, 2))
+    torch.cuda.synchronize()
+    for i, h in enumerate(hps):
+        s1, st1, pf1 = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [h], dtype, want_per_fold=True)
+        torch.cuda.synchronize()
+        assert torch.equal(pf1[0], pf[i]) and torch.equal(s1[0], scores[i]) and st1[0] == status[i], (i, h["hidden"])
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hps[tb], f, dtype=dtype, step_begin=0, step_end=2)
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    tol = REL_BF16 if dtype else REL_F32
+    for t in range(2):
+        for name, sl in layer_slices(d, hps[tb]["hidden"], c):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < tol, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < tol, (t, name, "theta")
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, hps, dtype=dtype)
+    assert np.array_equal(status.cpu().numpy(), rst)
+    assert np.abs(pf.cpu().numpy()[:, :, 0] - rpf[:, :, 0]).max() < (10 if dtype else 2) * ABS_SCORE
+
+
 def test_divergent_neighbours_on_the_same_workgroup_bf16(bb):
     """More models than resident workgroups, every other one divergent, ragged minibatches: a workgroup
     that has just trained a model full of NaNs goes on to a healthy one, whose score must be bit-identical
