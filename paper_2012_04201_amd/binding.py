@@ -19,7 +19,8 @@ ADAM, SGD = 0, 1
 F32, BF16 = 0, 1
 
 EXPORTS = ["bbo_mlp_workspace_bytes", "bbo_mlp_cv_eval", "bbo_mlp_cv_eval_traced", "bbo_mlp_fold_lists",
-           "bbo_mlp_holdout_eval", "bbo_mlp_holdout_lists", "bbo_mlp_minibatch_rows", "bbo_mlp_init_params", "bbo_mlp_param_count", "bbo_mlp_last_error"]
+           "bbo_mlp_holdout_eval", "bbo_mlp_holdout_lists", "bbo_mlp_minibatch_rows", "bbo_mlp_init_params", "bbo_mlp_param_count", "bbo_mlp_kernel_class",
+           "bbo_mlp_last_error"]
 
 
 class HParams(C.Structure):
@@ -120,6 +121,14 @@ def to_device(cfg, device="cuda:0"):
 def bbo_mlp_param_count(d, n_classes, hp):
     h = make_hparams([hp])
     return int(lib().bbo_mlp_param_count(C.c_int32(d), C.c_int32(n_classes), h))
+
+
+KERNEL_TILED, KERNEL_SMALL, KERNEL_LINEAR, KERNEL_GENERIC = range(4)
+
+
+def bbo_mlp_kernel_class(n, d, n_classes, hp, dtype=F32):
+    h = make_hparams([hp])
+    return int(lib().bbo_mlp_kernel_class(C.c_int64(n), C.c_int32(d), C.c_int32(n_classes), h, C.c_int32(dtype)))
 
 
 def bbo_mlp_workspace_bytes(n, d, n_classes, n_folds, hps, dtype, hp_arr=None):

@@ -771,13 +771,31 @@ bool force_generic() {
   return e && e[0] == '1';
 }
 
+// The fastest kernel that takes a model of these layer sizes on a data set of n rows.
+int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
+  if (force_generic()) return KC_GENERIC;
+  const int d = dims[0];
+  // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
+  if (dtype == BBO_BF16) {
+    if ((uint64_t)n * (uint64_t)d * 2 < (1ull << 31) && tiled_eligible(dims, L)) {
+      TLay ty;
+      make_tlay(ty, dims, L);
+      if (ty.lds_total <= TB_LDS_LIMIT) return KC_TILED;
+    }
+    return KC_GENERIC;
+  }
+  if (n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
+  if (small_eligible(dims, L)) {
+    SLay sy;
+    make_slay(sy, dims, n);
+    return sy.lds_total <= SM_LDS_LIMIT ? KC_SMALL : KC_GENERIC;
+  }
+  return linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
+}
+
 int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_base, const bbo_mlp_hparams* hp, int B,
               int dtype) {
   const int kstep = dtype == BBO_F32 ? 16 : 32, opsz = dtype == BBO_F32 ? 4 : 2;
-  const bool fast = !force_generic();
-  // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
-  const bool tiled_ok = fast && dtype == BBO_BF16 && (uint64_t)n * (uint64_t)d * 2 < (1ull << 31);
-  const bool f32_ok = fast && dtype == BBO_F32 && n * (int64_t)d < 0x7fffffff;
   const double n_tr_est = n_folds > 1 && fold_base >= 0 ? (double)n * (n_folds - 1) / n_folds : (double)n;
   std::vector<double> cost[KC_N];
   for (int k = 0; k < KC_N; k++) {
@@ -819,32 +837,22 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
       fps += 2.0 * it.dims[l] * it.dims[l + 1] * (l == 0 ? 2 : 3);
       params += (double)it.dims[l] * it.dims[l + 1];
     }
-    // the fastest kernel that takes this shape
-    int k = KC_GENERIC;
-    if (tiled_ok && tiled_eligible(it.dims, it.L)) {
+    const int k = kernel_class(it.dims, it.L, n, dtype);
+    if (k == KC_TILED) {
       TLay ty;
       make_tlay(ty, it.dims, it.L);
-      if (ty.lds_total <= TB_LDS_LIMIT) {
-        k = KC_TILED;
-        pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, ty.total);
-        pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, ty.lds_total);
-      }
-    } else if (f32_ok && small_eligible(it.dims, it.L)) {
+      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, ty.total);
+      pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, ty.lds_total);
+    } else if (k == KC_SMALL) {
       SLay sy;
-      make_slay(sy, it.dims, n);
-      if (sy.lds_total <= SM_LDS_LIMIT) {
-        k = KC_SMALL;  // only the hidden layer's moments live in global memory
-        pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, 2ull * sy.HP * sy.ldw * 4);
-        pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, sy.lds_total);
-      }
-    } else if (f32_ok && linear_eligible(it.dims, it.L)) {
-      k = KC_LINEAR;  // a model per wavefront, nothing kept in global memory
-    }
-    if (k == KC_GENERIC) {
+      make_slay(sy, it.dims, n);  // only the hidden layer's moments live in global memory
+      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, 2ull * sy.HP * sy.ldw * 4);
+      pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, sy.lds_total);
+    } else if (k == KC_GENERIC) {
       Layout y;
       make_layout(y, it.dims, it.L, it.rows_cap, kstep, opsz);
       pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, y.total);
-    }
+    }  // KC_LINEAR: a model per wavefront, nothing kept in global memory
     const double steps = std::ceil(n_tr_est / (double)std::max<int64_t>(bs, 1));
     const double c = (double)h.epochs * (n_tr_est * fps + steps * (params * 24.0 + 2.0e4));
     for (int f = 0; f < n_folds; f++) {
@@ -1176,6 +1184,15 @@ int64_t bbo_mlp_param_count(int32_t d, int32_t n_classes, const bbo_mlp_hparams*
   g_err.clear();
   if (check_problem(0, d, n_classes, 1, BBO_F32) || check_hparams(hp, 1)) return -1;
   return param_count(d, n_classes, *hp);
+}
+
+int bbo_mlp_kernel_class(int64_t n, int32_t d, int32_t n_classes, const bbo_mlp_hparams* hp, int32_t dtype) {
+  g_err.clear();
+  if (check_problem(n, d, n_classes, 1, dtype) || check_hparams(hp, 1)) return -1;
+  int32_t dims[MAXL + 1];
+  int L;
+  fill_dims(*hp, d, n_classes, dims, &L);
+  return kernel_class(dims, L, n, dtype);
 }
 
 const char* bbo_mlp_last_error(void) { return g_err.c_str(); }

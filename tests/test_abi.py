@@ -56,3 +56,26 @@ def test_argument_validation_without_gpu(bb):
     assert L.bbo_mlp_param_count(C.c_int32(4), C.c_int32(-2), hp) < 0
     # one logit (n_classes = 1) has one output unit, like regression
     assert bb.bbo_mlp_param_count(4, 1, {"hidden": [8, 9]}) == 4 * 8 + 8 + 8 * 9 + 9 + 9 + 1
+
+
+def test_kernel_class_is_a_property_of_the_suggestion(bb):
+    """Host logic: which training kernel a shape goes to (the limits each kernel documents)."""
+    k = lambda n, d, c, hidden, dt=0: bb.bbo_mlp_kernel_class(n, d, c, {"hidden": hidden}, dt)
+    assert k(569, 30, 2, [100]) == bb.KERNEL_SMALL
+    assert k(569, 63, 4, [224]) in (bb.KERNEL_SMALL, bb.KERNEL_GENERIC)  # decided by the LDS the shape needs
+    assert k(569, 64, 2, [100]) == bb.KERNEL_GENERIC      # 64 inputs and the bias column do not fit 64 columns
+    assert k(569, 30, 5, [100]) == bb.KERNEL_GENERIC      # more than 4 outputs
+    assert k(569, 30, 2, [100, 50]) == bb.KERNEL_GENERIC  # two hidden layers in fp32
+    assert k(569, 30, 2, []) == bb.KERNEL_LINEAR
+    assert k(1797, 64, 10, []) == bb.KERNEL_LINEAR
+    assert k(500, 256, 4, []) == bb.KERNEL_LINEAR
+    assert k(500, 257, 4, []) == bb.KERNEL_GENERIC
+    assert k(500, 65, 9, []) == bb.KERNEL_GENERIC         # 2 rows of W per lane x 16 padded outputs
+    assert k(20000, 128, 10, [256, 128], 1) == bb.KERNEL_TILED
+    assert k(20000, 128, 10, [256], 1) == bb.KERNEL_TILED
+    assert k(20000, 100, 10, [256], 1) == bb.KERNEL_GENERIC    # inputs not a multiple of 8
+    assert k(20000, 128, 10, [300], 1) == bb.KERNEL_GENERIC
+    assert k(20000, 128, 10, [], 1) == bb.KERNEL_GENERIC
+    assert k(20000, 128, 10, [64, 64, 64], 1) == bb.KERNEL_GENERIC
+    assert bb.lib().bbo_mlp_kernel_class(C.c_int64(10), C.c_int32(0), C.c_int32(2), bb.make_hparams([{"hidden": []}]),
+                                         C.c_int32(0)) < 0
