@@ -799,6 +799,8 @@ def test_mixed_shapes_in_one_call_keep_their_kernels(bb, oracle, dtype):
     base = {"solver": "adam", "batch_size": 64, "alpha": 0.01, "lr": 0.003, "epochs": 3}
     shapes = [[20], [], [40, 24], [300], [], [33], [50, 40, 30], [96, 80]]
     hps = [dict(base, hidden=h, seed=900 + i, solver="sgd" if i % 3 == 2 else "adam") for i, h in enumerate(shapes)]
+    kinds = {bb.bbo_mlp_kernel_class(n, d, c, h, dtype) for h in hps}
+    assert kinds == ({bb.KERNEL_TILED, bb.KERNEL_GENERIC} if dtype else {bb.KERNEL_SMALL, bb.KERNEL_LINEAR, bb.KERNEL_GENERIC})
     X, y, ft = bb.to_device(cfg)
     f, tb = 1, 2
     scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, hps, dtype, want_per_fold=True, trace=(tb, f, 0, 2))
