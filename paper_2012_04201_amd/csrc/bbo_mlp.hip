@@ -11,6 +11,14 @@
 // gradient is never stored.  (Models without a hidden layer are the exception:
 // a wavefront each, on the vector ALU; see train_linear_f32.h.)
 //
+// Four training kernels share this scheme: the LDS-tiled bf16 kernel
+// (train_tiled_bf16.h), the LDS-resident fp32 kernel (train_small_f32.h), the
+// wavefront-per-model fp32 kernel (train_linear_f32.h) and the generic kernel
+// below, which takes every shape the header admits.  The planner gives each
+// suggestion to the fastest kernel that takes its shape and launches every
+// kernel that got items, one after the other, each with its own item array
+// and queue counter.
+//
 // Operand layout.  MFMA operands are read straight from memory as 16-byte
 // vectors along the contracted index, so every tensor is kept in the layout
 // (or layouts) in which each of its consumers contracts it:
