@@ -790,7 +790,7 @@ int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
       make_tlay(ty, dims, L);
       if (ty.lds_total <= TB_LDS_LIMIT) return KC_TILED;
     }
-    return KC_GENERIC;
+    return n * (int64_t)d < 0x7fffffff && linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
   }
   if (n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
   if (small_eligible(dims, L)) {
@@ -1034,6 +1034,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   P.step_end = step_end;
   P.trace_out = trace_out;
   P.state_in = traced ? state_in : nullptr;
+  P.x_bf16 = dtype == BBO_BF16;
 
   int32_t* queues = (int32_t*)(ws + pl.o_queue);  // one work-queue counter per kernel, reset by k_fold_lists
   hipLaunchKernelGGL(k_fold_lists, dim3(n_folds), dim3(NTHREADS), 0, s, fold_idx, n, (int32_t*)(ws + pl.o_train),

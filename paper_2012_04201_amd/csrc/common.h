@@ -164,6 +164,7 @@ struct TrainParams {
   int64_t step_begin, step_end;
   float* trace_out;
   const float* state_in;  // optional [3P]: parameters, m, v of the traced item before step_begin
+  int32_t x_bf16;         // wavefront-per-model kernel: X holds bfloat16 and the products take bfloat16 operands
 };
 
 __device__ inline double block_sum(double v, double* red) {

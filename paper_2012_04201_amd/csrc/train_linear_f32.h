@@ -1,6 +1,9 @@
-// Training / scoring kernel for fp32 models WITHOUT a hidden layer (linear and
+// Training / scoring kernel for models WITHOUT a hidden layer (linear and
 // logistic regression trained like the MLPs: same minibatch order, losses,
-// penalty and optimizers; Section 2, Table 1's linear models).
+// penalty and optimizers; Section 2, Table 1's linear models).  fp32, or the
+// bfloat16 mode of the other kernels: inputs stored as bfloat16, the weights
+// and the deltas rounded to bfloat16 where they enter a product, everything
+// else (master weights, moments, sums, the bias) in fp32.
 //
 // Such a model has (d + 1) * c parameters, a few dozen to a thousand: far too
 // little work for a workgroup.  ONE WAVEFRONT trains one model, several
@@ -108,9 +111,25 @@ struct Linear {
   int lane, d, c, S, Pn;
   int r0, k0, q64, r64;  // element `lane` of a chunk's row-major block, and the step of 64 elements
 
+  // a product's operand: rounded to bfloat16 in that mode
+  __device__ __forceinline__ float opnd(float x) const { return P.x_bf16 ? (float)(__bf16)x : x; }
+  __device__ __forceinline__ void put_weights(int k, const float (&wr)[CO]) const {
+    float o[CO];
+#pragma unroll
+    for (int j = 0; j < CO; j++) o[j] = opnd(wr[j]);
+    lds_put<CO>(ws + k * CO, o);
+  }
+
   // rows of the chunk -> xs; `row` is the lane's row or -1
   __device__ __forceinline__ void stage(int row, int mbc) const {
-    const float* X = (const float*)P.X;
+    if (P.x_bf16)
+      stage_as<__bf16>(row, mbc);
+    else
+      stage_as<float>(row, mbc);
+  }
+  template <typename XT>
+  __device__ __forceinline__ void stage_as(int row, int mbc) const {
+    const XT* X = (const XT*)P.X;
     const int total = mbc * d;
     int r = r0, k = k0;
     // eight loads in flight, then their eight LDS stores
@@ -121,7 +140,7 @@ struct Linear {
       for (int u = 0; u < 8; u++) {
         const int rr = __shfl(row, r & 63);
         const bool in = e0 + 64 * u + lane < total;
-        v[u] = X[in ? rr * d + k : 0];  // n * d < 2^31 (checked by the host)
+        v[u] = (float)X[in ? rr * d + k : 0];  // n * d < 2^31 (checked by the host)
         at[u] = in ? r * S + k : -1;
         k += r64;
         r += q64;
@@ -254,6 +273,8 @@ struct Linear {
       }
     }
     if (TRAIN) {
+#pragma unroll
+      for (int j = 0; j < CO; j++) dl[j] = opnd(dl[j]);
       lds_put<CO>(ds + lane * CO, dl);
       ln_lds_fence();
     }
@@ -321,7 +342,7 @@ struct Linear {
             }
           }
         }
-        if (k < d) lds_put<CO>(ws + k * CO, w[i]);
+        if (k < d) put_weights(k, w[i]);
       }
       if (lane < c) {
         if (resume) {
@@ -426,7 +447,7 @@ struct Linear {
                   rec[1 + Pn + k * c + j] = w[i][j];
                 }
               }
-            lds_put<CO>(ws + k * CO, w[i]);
+            put_weights(k, w[i]);
           }
         }
         if (lane < c) {

@@ -75,7 +75,9 @@ def test_kernel_class_is_a_property_of_the_suggestion(bb):
     assert k(20000, 128, 10, [256], 1) == bb.KERNEL_TILED
     assert k(20000, 100, 10, [256], 1) == bb.KERNEL_GENERIC    # inputs not a multiple of 8
     assert k(20000, 128, 10, [300], 1) == bb.KERNEL_GENERIC
-    assert k(20000, 128, 10, [], 1) == bb.KERNEL_GENERIC
+    assert k(20000, 128, 10, [], 1) == bb.KERNEL_GENERIC       # 2 rows of W per lane x 16 padded outputs
+    assert k(569, 30, 2, [], 1) == bb.KERNEL_LINEAR            # the wavefront kernel has a bfloat16 mode
+    assert k(1797, 64, 10, [], 1) == bb.KERNEL_LINEAR
     assert k(20000, 128, 10, [64, 64, 64], 1) == bb.KERNEL_GENERIC
     assert bb.lib().bbo_mlp_kernel_class(C.c_int64(10), C.c_int32(0), C.c_int32(2), bb.make_hparams([{"hidden": []}]),
                                          C.c_int32(0)) < 0

@@ -417,6 +417,45 @@ def test_linear_models_steps_and_scores(bb, oracle, n, d, c, solver, bs):
         assert np.abs(got[:, :, 1] - rpf[:, :, 1]).max() <= 1.0 / n_va + 1e-6
 
 
+@pytest.mark.parametrize("n,d,c,solver,bs", [(300, 30, 2, "adam", 57), (250, 13, 0, "sgd", 0), (200, 6, 1, "adam", 64),
+                                             (400, 64, 10, "adam", 100), (330, 256, 4, "adam", 128),
+                                             (5000, 20, 3, "sgd", 700)])
+def test_linear_models_bf16_steps_and_scores(bb, oracle, n, d, c, solver, bs):
+    """The wavefront-per-model kernel in the bfloat16 mode: inputs stored as bfloat16, weights and deltas
+    rounded to bfloat16 where they enter a product."""
+    cfg = small_problem(1900 + n, n, d, c, bf16=True)
+    hp = {"hidden": [], "solver": solver, "nesterov": True, "momentum": 0.85, "batch_size": bs, "alpha": 0.03,
+          "lr": 0.004, "epochs": 4, "seed": 707 + d}
+    assert bb.bbo_mlp_kernel_class(n, d, c, hp, 1) == bb.KERNEL_LINEAR
+    f = 2
+    c_out = c if c >= 2 else 1
+    n_tr, n_va = int((cfg["fold_idx"] != f).sum()), int((cfg["fold_idx"] == f).sum())
+    spe = -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(10, 4 * spe)
+    X, y, ft = bb.to_device(cfg)
+    t2 = min(2, T)
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 1, want_per_fold=True, trace=(0, f, 0, t2))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=1, step_begin=0, step_end=t2)
+    g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+    for t in range(t2):
+        for name, sl in layer_slices(d, [], c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_BF16, (t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (t, name, "theta")
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in (1, 5, 9) if t < T], T):
+        for name, sl in layer_slices(d, [], c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_BF16, (t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_BF16, (t, name, "theta")
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, [hp], dtype=1)
+    got = pf.cpu().numpy()
+    assert status[0].item() == 0 and rst[0] == 0
+    assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 5 * ABS_SCORE
+    if c == 0:
+        assert np.abs(got[0, :, 1] - rpf[0, :, 1]).max() < 5 * ABS_SCORE
+    else:
+        assert np.abs(got[0, :, 1] - rpf[0, :, 1]).max() <= 2.0 / n_va + 1e-6
+
+
 @pytest.mark.parametrize("n,d,alpha", [(60, 3, 0.0), (60, 3, 3.0), (700, 40, 5.0), (300, 100, 1.0)])
 def test_linear_regression_reaches_the_ridge_solution(bb, n, d, alpha):
     """A property the oracle has no part in: full-batch gradient descent on a linear model with the
@@ -800,7 +839,7 @@ def test_mixed_shapes_in_one_call_keep_their_kernels(bb, oracle, dtype):
     shapes = [[20], [], [40, 24], [300], [], [33], [50, 40, 30], [96, 80]]
     hps = [dict(base, hidden=h, seed=900 + i, solver="sgd" if i % 3 == 2 else "adam") for i, h in enumerate(shapes)]
     kinds = {bb.bbo_mlp_kernel_class(n, d, c, h, dtype) for h in hps}
-    assert kinds == ({bb.KERNEL_TILED, bb.KERNEL_GENERIC} if dtype else {bb.KERNEL_SMALL, bb.KERNEL_LINEAR, bb.KERNEL_GENERIC})
+    assert kinds == {bb.KERNEL_TILED if dtype else bb.KERNEL_SMALL, bb.KERNEL_LINEAR, bb.KERNEL_GENERIC}
     X, y, ft = bb.to_device(cfg)
     f, tb = 1, 2
     scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, hps, dtype, want_per_fold=True, trace=(tb, f, 0, 2))
