@@ -165,7 +165,7 @@ def run_studies(evaluate, space, optimizers, n_step, n_batch, seed=0):
 
 def gpu_evaluator(cfg, device="cuda:0"):
     """evaluate() backed by the HIP library: the cross-validation score (first metric) of every suggestion,
-    inputs resident on the device, one launch per call."""
+    inputs resident on the device, one library call per iteration."""
     import torch
     from . import binding
     X, y, ft = binding.to_device(cfg, torch.device(device))
