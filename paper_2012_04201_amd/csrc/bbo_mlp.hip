@@ -1066,13 +1066,13 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     } else if (k == KC_LINEAR) {
       const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), ki = ln_ki(d);
       typedef void (*linear_fn)(const TrainParams);
-      // [padded outputs 1, 2, 4, 8, 16][rows of W per lane 1, 2, 4], at most 16 parameters per lane
+      // [padded outputs 1, 2, 4, 8, 16][rows of W per lane 1, 2, 4], at most 32 parameters per lane
       static const linear_fn fns[5][3] = {
           {k_train_linear<1, 1>, k_train_linear<1, 2>, k_train_linear<1, 4>},
           {k_train_linear<2, 1>, k_train_linear<2, 2>, k_train_linear<2, 4>},
           {k_train_linear<4, 1>, k_train_linear<4, 2>, k_train_linear<4, 4>},
-          {k_train_linear<8, 1>, k_train_linear<8, 2>, nullptr},
-          {k_train_linear<16, 1>, nullptr, nullptr}};
+          {k_train_linear<8, 1>, k_train_linear<8, 2>, k_train_linear<8, 4>},
+          {k_train_linear<16, 1>, k_train_linear<16, 2>, nullptr}};
       const linear_fn fn =
           fns[co == 1 ? 0 : (co == 2 ? 1 : (co == 4 ? 2 : (co == 8 ? 3 : 4)))][ki == 1 ? 0 : (ki == 2 ? 1 : 2)];
       if (!fn) return fail(BBO_DEVICE_ERROR, "no kernel for this linear shape");  // ruled out by linear_eligible()

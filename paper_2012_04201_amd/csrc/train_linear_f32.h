@@ -42,7 +42,7 @@ namespace {
 
 constexpr int LN_MAX_D = 256;         // inputs: at most 4 rows of W per lane
 constexpr int LN_MAX_OUT = 16;        // outputs
-constexpr int LN_MAX_PER_LANE = 16;   // (rows of W per lane) x (padded outputs)
+constexpr int LN_MAX_PER_LANE = 32;   // (rows of W per lane) x (padded outputs)
 constexpr uint32_t LN_LDS_PER_WG = 64 * 1024;
 constexpr int LN_EPOCH_CAP = 4096;    // rows whose epoch order is tabled in LDS
 

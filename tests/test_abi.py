@@ -70,12 +70,14 @@ def test_kernel_class_is_a_property_of_the_suggestion(bb):
     assert k(1797, 64, 10, []) == bb.KERNEL_LINEAR
     assert k(500, 256, 4, []) == bb.KERNEL_LINEAR
     assert k(500, 257, 4, []) == bb.KERNEL_GENERIC
-    assert k(500, 65, 9, []) == bb.KERNEL_GENERIC         # 2 rows of W per lane x 16 padded outputs
+    assert k(500, 65, 9, []) == bb.KERNEL_LINEAR          # 2 rows of W per lane x 16 padded outputs: 32 per lane
+    assert k(500, 129, 9, []) == bb.KERNEL_GENERIC        # 4 rows x 16 padded outputs is too many
     assert k(20000, 128, 10, [256, 128], 1) == bb.KERNEL_TILED
     assert k(20000, 128, 10, [256], 1) == bb.KERNEL_TILED
     assert k(20000, 100, 10, [256], 1) == bb.KERNEL_GENERIC    # inputs not a multiple of 8
     assert k(20000, 128, 10, [300], 1) == bb.KERNEL_GENERIC
-    assert k(20000, 128, 10, [], 1) == bb.KERNEL_GENERIC       # 2 rows of W per lane x 16 padded outputs
+    assert k(20000, 128, 10, [], 1) == bb.KERNEL_LINEAR
+    assert k(20000, 200, 10, [], 1) == bb.KERNEL_GENERIC       # 4 rows of W per lane x 16 padded outputs
     assert k(569, 30, 2, [], 1) == bb.KERNEL_LINEAR            # the wavefront kernel has a bfloat16 mode
     assert k(1797, 64, 10, [], 1) == bb.KERNEL_LINEAR
     assert k(20000, 128, 10, [64, 64, 64], 1) == bb.KERNEL_GENERIC

@@ -372,7 +372,9 @@ LINEAR_SHAPES = [
     (330, 256, 4, "adam", 128),    # the widest input: four rows of W per lane, one wavefront per workgroup
     (270, 64, 16, "sgd", 200),     # the most outputs
     (240, 128, 8, "adam", 70),     # two rows of W per lane x 8 outputs
-    (220, 65, 9, "adam", 50),      # one too many for the wavefront kernel: the generic kernel takes it
+    (220, 65, 9, "adam", 50),      # two rows of W per lane x 16 padded outputs
+    (280, 200, 7, "adam", 90),     # four rows x 8
+    (230, 129, 9, "adam", 50),     # four rows x 16 is too many for the wavefront kernel: the generic kernel takes it
     (150, 1, 2, "adam", 33),       # a single feature
     (5000, 20, 3, "adam", 700),    # more rows than the epoch table holds: rows permuted on the fly
 ]
@@ -788,8 +790,8 @@ def test_holdout_scores_match_oracle(bb, oracle, idx, kw):
 
 @pytest.mark.parametrize("idx,c", [(3, 2), (3, 1), (2, 0), (1, 10)])
 def test_holdout_scores_of_linear_models(bb, oracle, idx, c):
-    """The hold-out split on models without a hidden layer (the wavefront-per-model kernel; idx 1: two rows
-    of outputs per lane is too many, so the generic kernel), with the one-logit head among them."""
+    """The hold-out split on models without a hidden layer (the wavefront-per-model kernel), with the
+    one-logit head among them."""
     cfg = with_holdout(inputs.make_config(idx, B=6, epochs=8))
     assert c == cfg["n_classes"] or (c == 1 and cfg["n_classes"] == 2)
     hps = [dict(h, hidden=[]) for h in cfg["hparams"]]
