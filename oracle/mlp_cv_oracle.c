@@ -34,7 +34,8 @@
  * product / batch reduction is accumulated in fp64 and rounded once to fp32;
  * elementwise operations are rounded to fp32 after each operation.  With
  * prec=1 no rounding happens anywhere (pure fp64), which the gradient and
- * closed-form pins use.  With dtype=1 the GEMM operands (inputs, weights,
+ * closed-form pins use.  prec=2 is a sensitivity probe (see accum()): fp32
+ * running sums in the four contractions, everything else as prec=0.  With dtype=1 the GEMM operands (inputs, weights,
  * hidden activations, deltas) are rounded to bfloat16 (round to nearest even)
  * at the points marked BF below; master weights, moments and accumulation
  * stay fp32.
@@ -127,7 +128,16 @@ int64_t oracle_perm_index(uint64_t seed, int32_t fold, int32_t epoch, int64_t n,
 /* rounding helpers                                                    */
 /* ------------------------------------------------------------------ */
 
-static inline double rnd(double x, int prec) { return prec ? x : (double)(float)x; }
+static inline double rnd(double x, int prec) { return prec == 1 ? x : (double)(float)x; }
+
+/* One term of a dot product.  prec 0 and 1 accumulate in fp64 (the definition).  prec 2 is a PROBE, not a
+ * definition: the running sum is rounded to fp32 after every term, the way a single-precision pipeline
+ * sums, so that comparing its final scores with those of prec 0 tells how far rounding at the level of an
+ * fp32 accumulator moves this particular training run (its sensitivity, used by the tests to tell stable
+ * runs from chaotic ones). */
+static inline double accum(double acc, double term, int prec) {
+  return prec == 2 ? (double)(float)(acc + (double)(float)term) : acc + term;
+}
 
 /* float -> bfloat16 bits, round to nearest even; NaN stays NaN (quiet). */
 uint16_t oracle_bf16_bits(float f) {
@@ -280,7 +290,7 @@ static void forward(const net_t* net, const data_t* D, const int32_t* rows, int6
     for (int64_t r = 0; r < m; r++) {
       for (int j = 0; j < fo; j++) {
         double acc = 0.0;
-        for (int k = 0; k < fi; k++) acc += s->a[l][r * fi + k] * W[(int64_t)k * fo + j];
+        for (int k = 0; k < fi; k++) acc = accum(acc, s->a[l][r * fi + k] * W[(int64_t)k * fo + j], prec);
         double z = rnd(acc + b[j], prec);
         if (l + 1 < net->L) {
           z = z > 0.0 ? z : 0.0;
@@ -363,12 +373,12 @@ static double loss_grad(const net_t* net, const data_t* D, const int32_t* rows, 
     for (int k = 0; k < fi; k++)
       for (int j = 0; j < fo; j++) {
         double acc = 0.0;
-        for (int64_t r = 0; r < m; r++) acc += s->a[l][r * fi + k] * dl[r * fo + j];
+        for (int64_t r = 0; r < m; r++) acc = accum(acc, s->a[l][r * fi + k] * dl[r * fo + j], prec);
         gW[(int64_t)k * fo + j] = rnd(acc + am * W[(int64_t)k * fo + j], prec);
       }
     for (int j = 0; j < fo; j++) {
       double acc = 0.0;
-      for (int64_t r = 0; r < m; r++) acc += dl[r * fo + j];
+      for (int64_t r = 0; r < m; r++) acc = accum(acc, dl[r * fo + j], prec);
       gb[j] = rnd(acc, prec);
     }
     if (l > 0) {
@@ -378,7 +388,7 @@ static double loss_grad(const net_t* net, const data_t* D, const int32_t* rows, 
           double v = 0.0;
           if (s->a[l][r * fi + k] > 0.0) {
             double acc = 0.0;
-            for (int j = 0; j < fo; j++) acc += dl[r * fo + j] * Wop[(int64_t)k * fo + j];
+            for (int j = 0; j < fo; j++) acc = accum(acc, dl[r * fo + j] * Wop[(int64_t)k * fo + j], prec);
             v = opnd(rnd(acc, prec), dt); /* BF: deltas */
           }
           dp[r * fi + k] = v;

@@ -151,7 +151,7 @@ MUTANTS = {
     "regression output delta": (r"dl\[0\] = opnd\(rnd\(e / \(double\)m, prec\), D->dtype\)", "dl[0] = rnd(e / (double)m, prec)"),
     "hidden deltas": (r"v = opnd\(rnd\(acc, prec\), dt\)", "v = rnd(acc, prec)"),
     "data gradient through the rounded weights": (r"dl\[r \* fo \+ j\] \* Wop\[", "dl[r * fo + j] * W["),
-    "bias gradient over the deltas as the products see them": (r"acc \+= dl\[r \* fo \+ j\];", "acc += dl[r * fo + j] * (1.0 + 1e-3);"),
+    "bias gradient over the deltas as the products see them": (r"acc = accum\(acc, dl\[r \* fo \+ j\], prec\);", "acc = accum(acc, dl[r * fo + j] * (1.0 + 1e-3), prec);"),
     "ReLU mask of the data gradient": (r"if \(s->a\[l\]\[r \* fi \+ k\] > 0\.0\)", "if (s->a[l][r * fi + k] > 0.05)"),
     "penalty on the unrounded weights": (r"pen \+= W\[i\] \* W\[i\];", "pen += opnd(W[i], dt) * opnd(W[i], dt);"),
 }

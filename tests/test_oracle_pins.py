@@ -293,6 +293,19 @@ def test_fp32_mode_tracks_fp64_mode(oracle):
     assert np.array_equal(g32, g32.astype(np.float32).astype(np.float64))
 
 
+def test_fp32_running_sum_probe_is_the_same_computation_up_to_single_precision(oracle):
+    """prec=2 (the sensitivity probe: fp32 running sums in the contractions) differs from the definition
+    by single-precision summation error only, and does differ."""
+    X, y = tiny_problem(6, n=200, d=8, n_classes=3)
+    hp = {"hidden": [32, 16], "alpha": 0.01, "seed": 4}
+    theta = oracle.init_params(8, 3, hp, 0)
+    rows = np.arange(150, dtype=np.int32)
+    l0, g0 = oracle.loss_grad(X, y, 3, rows, hp, theta, prec=0)
+    l2, g2 = oracle.loss_grad(X, y, 3, rows, hp, theta, prec=2)
+    rel = np.linalg.norm(g0 - g2) / np.linalg.norm(g0)
+    assert 0 < rel < 2e-6 and abs(l0 - l2) < 1e-6
+
+
 def test_bf16_mode_rounds_operands_only(oracle):
     """bf16 configuration == the fp32 computation run on bf16-rounded operands
     (checked for a linear model, where the only operands are X and W)."""
