@@ -100,6 +100,30 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
 
 
+def _check_inputs(X, y, fold_idx, n_classes, dtype):
+    """The library takes plain pointers: the tensors must be dense, on one device and of the types it reads."""
+    if X.dim() != 2 or not X.is_contiguous():
+        raise ValueError("X must be a contiguous [n, d] tensor")
+    if X.dtype != (torch.bfloat16 if dtype == BF16 else torch.float32):
+        raise ValueError("X must be %s for this dtype" % ("bfloat16" if dtype == BF16 else "float32"))
+    if not y.is_contiguous() or y.shape[0] != X.shape[0] or (
+            n_classes >= 0 and y.dtype != (torch.int32 if n_classes >= 1 else torch.float32)):
+        raise ValueError("y must be a contiguous [n] tensor, int32 for classification, float32 for regression")
+    if not fold_idx.is_contiguous() or fold_idx.shape[0] != X.shape[0] or fold_idx.dtype != torch.int32:
+        raise ValueError("fold_idx must be a contiguous int32 [n] tensor")
+    if not (X.device == y.device == fold_idx.device) or X.device.type != "cuda":
+        raise ValueError("X, y and fold_idx must be on the same GPU")
+
+
+def _new(stream, *args, **kw):
+    """A tensor the kernels of `stream` will use: allocated under that stream, so that the caching allocator
+    does not hand the block to other work while they run."""
+    if stream is None:
+        return torch.empty(*args, **kw)
+    with torch.cuda.stream(stream):
+        return torch.empty(*args, **kw)
+
+
 def _stream(stream):
     s = stream if stream is not None else torch.cuda.current_stream()
     return C.c_void_p(s.cuda_stream)
@@ -152,15 +176,17 @@ def bbo_mlp_cv_eval(X, y, n_classes, fold_idx, n_folds, hps, dtype=F32, workspac
     Returns (scores[B,2], status[B]) and, if asked, per_fold[B,K,2] and the
     trace dict(loss[T], grad[T,P], theta_after[T,P]) — all device tensors.
     """
+    _check_inputs(X, y, fold_idx, n_classes, dtype)
     dev = X.device
     n, d = (int(X.shape[0]), int(X.shape[1]))
     B = len(hps)
     h = hp_arr if hp_arr is not None else make_hparams(hps)
     if workspace is None:
-        workspace = alloc_workspace(bbo_mlp_workspace_bytes(n, d, n_classes, n_folds, hps, dtype, h), dev)
-    scores = torch.empty((max(B, 1), 2), dtype=torch.float32, device=dev)
-    status = torch.empty(max(B, 1), dtype=torch.int32, device=dev)
-    pf = torch.empty((max(B, 1), n_folds, 2), dtype=torch.float32, device=dev) if want_per_fold else None
+        workspace = _new(stream, max(bbo_mlp_workspace_bytes(n, d, n_classes, n_folds, hps, dtype, h), 256),
+                         dtype=torch.uint8, device=dev)
+    scores = _new(stream, (max(B, 1), 2), dtype=torch.float32, device=dev)
+    status = _new(stream, max(B, 1), dtype=torch.int32, device=dev)
+    pf = _new(stream, (max(B, 1), n_folds, 2), dtype=torch.float32, device=dev) if want_per_fold else None
     common = [_ptr(X), _ptr(y), C.c_int64(n), C.c_int32(d), C.c_int32(n_classes), _ptr(fold_idx), C.c_int32(n_folds),
               h, C.c_int32(B), C.c_int32(dtype), _ptr(scores), _ptr(status), _ptr(pf), _ptr(workspace),
               C.c_size_t(workspace.numel()), _stream(stream)]
@@ -185,14 +211,16 @@ def bbo_mlp_cv_eval(X, y, n_classes, fold_idx, n_folds, hps, dtype=F32, workspac
 def bbo_mlp_holdout_eval(X, y, n_classes, fold_idx, hps, dtype=F32, workspace=None, stream=None, hp_arr=None):
     """Hold-out scores of a list of suggestions: trained on the rows with fold_idx >= 0, scored on the
     rows with fold_idx < 0.  Returns (scores[B,2], status[B]) device tensors."""
+    _check_inputs(X, y, fold_idx, n_classes, dtype)
     dev = X.device
     n, d = (int(X.shape[0]), int(X.shape[1]))
     B = len(hps)
     h = hp_arr if hp_arr is not None else make_hparams(hps)
     if workspace is None:
-        workspace = alloc_workspace(bbo_mlp_workspace_bytes(n, d, n_classes, 1, hps, dtype, h), dev)
-    scores = torch.empty((max(B, 1), 2), dtype=torch.float32, device=dev)
-    status = torch.empty(max(B, 1), dtype=torch.int32, device=dev)
+        workspace = _new(stream, max(bbo_mlp_workspace_bytes(n, d, n_classes, 1, hps, dtype, h), 256), dtype=torch.uint8,
+                         device=dev)
+    scores = _new(stream, (max(B, 1), 2), dtype=torch.float32, device=dev)
+    status = _new(stream, max(B, 1), dtype=torch.int32, device=dev)
     _check(lib().bbo_mlp_holdout_eval(_ptr(X), _ptr(y), C.c_int64(n), C.c_int32(d), C.c_int32(n_classes),
                                       _ptr(fold_idx), h, C.c_int32(B), C.c_int32(dtype), _ptr(scores), _ptr(status),
                                       _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))

@@ -162,7 +162,7 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
     if (WANT_DELTA)
       for (int j = 0; j < c; j++) delta[j] = (expf(z[j] - lse) - (j == yr ? 1.f : 0.f)) * inv_den;
     *aux = best == yr ? 1.f : 0.f;  // a correct prediction
-    return lse - z[yr];
+    return lse - (yr >= 0 && yr < c ? z[yr] : 0.f);  // a label outside [0, c) matches no class
   } else if (n_classes == 1) {
     // one logit, labels 0/1: log(1 + e^z) - y z, delta (sigmoid(z) - y)/m
     const int yr = ((const int32_t*)yv)[row];
@@ -375,7 +375,7 @@ struct Trainer {
           float se = 0.f;
           for (int j = 0; j < c; j++) se += expf(z[j] - mx);
           const float lse = mx + logf(se);
-          lsum += (double)(lse - z[yr]);
+          lsum += (double)(lse - (yr >= 0 && yr < c ? z[yr] : 0.f));  // a label outside [0, c) matches no class
           for (int j = 0; j < c; j++) {
             const float g = (expf(z[j] - lse) - (j == yr ? 1.f : 0.f)) / (float)mb;
             const OpT gv = O::cvt(g);
@@ -774,14 +774,31 @@ int device_cus(int* out) {
   return BBO_OK;
 }
 
-bool force_generic() {
-  const char* e = getenv("BBO_MLP_FORCE_GENERIC");
-  return e && e[0] == '1';
+// The dynamic-LDS limit of a kernel is a property of the kernel on a device: it is set when first needed and
+// raised when a later call needs more, not on every call.
+int ensure_dynamic_lds(const void* fn, uint32_t bytes) {
+  struct Seen {
+    int dev;
+    const void* fn;
+    uint32_t bytes;
+  };
+  static thread_local std::vector<Seen> seen;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  for (Seen& e : seen)
+    if (e.dev == dev && e.fn == fn) {
+      if (e.bytes >= bytes) return BBO_OK;
+      HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+      e.bytes = bytes;
+      return BBO_OK;
+    }
+  HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  seen.push_back(Seen{dev, fn, bytes});
+  return BBO_OK;
 }
 
 // The fastest kernel that takes a model of these layer sizes on a data set of n rows.
 int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
-  if (force_generic()) return KC_GENERIC;
   const int d = dims[0];
   // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
   if (dtype == BBO_BF16) {
@@ -989,7 +1006,8 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   char* ws = (char*)workspace;
   {
     // the item arrays of all kernels, laid out as in the workspace, in one staged copy
-    std::vector<char> blob(pl.items_bytes, 0);
+    static thread_local std::vector<char> blob;  // kept between calls
+    blob.assign(pl.items_bytes, 0);
     for (int k = 0; k < KC_N; k++) {
       const SubPlan& sp = pl.sub[k];
       char* at = blob.data() + (sp.o_items - pl.o_items);
@@ -1049,8 +1067,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
     P.slot_bytes = sp.slot_bytes;
     P.n_items = (int)sp.items.size();
     if (k == KC_TILED) {
-      HIP_TRY(hipFuncSetAttribute((const void*)k_train_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)sp.lds_bytes));
+      if ((rc = ensure_dynamic_lds((const void*)k_train_tiled, sp.lds_bytes))) return rc;
       hipLaunchKernelGGL(k_train_tiled, dim3(sp.n_slots), dim3(TB_THREADS), sp.lds_bytes, s, P);
     } else if (k == KC_SMALL) {
       const int kt = d + 1 <= 16 ? 1 : (d + 1 <= 32 ? 2 : 4);
@@ -1061,7 +1078,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
           {k_train_small<2, 1>, k_train_small<2, 2>, k_train_small<2, 4>},
           {k_train_small<4, 1>, k_train_small<4, 2>, k_train_small<4, 4>}};
       const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
-      HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes));
+      if ((rc = ensure_dynamic_lds((const void*)fn, sp.lds_bytes))) return rc;
       hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(SM_THREADS), sp.lds_bytes, s, P);
     } else if (k == KC_LINEAR) {
       const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), ki = ln_ki(d);
@@ -1076,7 +1093,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
       const linear_fn fn =
           fns[co == 1 ? 0 : (co == 2 ? 1 : (co == 4 ? 2 : (co == 8 ? 3 : 4)))][ki == 1 ? 0 : (ki == 2 ? 1 : 2)];
       if (!fn) return fail(BBO_DEVICE_ERROR, "no kernel for this linear shape");  // ruled out by linear_eligible()
-      HIP_TRY(hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes));
+      if ((rc = ensure_dynamic_lds((const void*)fn, sp.lds_bytes))) return rc;
       hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(64 * sp.waves), sp.lds_bytes, s, P);
     } else if (dtype == BBO_F32) {
       hipLaunchKernelGGL(k_train<float>, dim3(sp.n_slots), dim3(NTHREADS), 0, s, P);
