@@ -41,6 +41,66 @@ def layer_slices(d, hidden, c_out):
     return out
 
 
+# The one rule for final scores.  A training run amplifies rounding differences by a factor that depends on
+# the run (Adam with a large learning rate turns the sign of a gradient element that is nearly zero into a
+# full step).  The oracle measures that factor itself: the run is repeated (a) with no fp32 rounding of the
+# state, (b, c) with the learning rate moved by one fp32 ulp either way, (d) with fp32 running sums in the
+# contractions; the largest change of a fold's first score is the run's "noise".
+#   noise < 1e-4          "strict":   held to 1e-3
+#   1e-4 <= noise < 1e-3  "widened":  held to 1e-3 + 2 x noise
+#   noise >= 1e-3         "chaotic":  the oracle cannot say which score is right to 1e-3; status and
+#                                     finiteness are compared, the deviation is reported, not asserted
+def score_bar(noise):
+    if not np.isfinite(noise) or noise >= ABS_SCORE:
+        return None
+    return ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
+
+
+def lr_ulp(hp, up):
+    lr = np.float32(hp.get("lr", 1e-3))
+    return dict(hp, lr=float(np.nextafter(lr, np.float32(1e9) if up else np.float32(0))))
+
+
+PROBES = (("fp64_state", None, 1), ("lr_up", True, 0), ("lr_down", False, 0), ("fp32_sums", None, 2))
+
+
+def fold_noise(oracle, cfg, c, hp, f, dtype, ref_score):
+    """Noise of ONE model's first fold score."""
+    worst = 0.0
+    for _, up, prec in PROBES:
+        h = hp if up is None else lr_ulp(hp, up)
+        q = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], h, f, dtype=dtype, prec=prec)["scores"][0]
+        worst = max(worst, abs(q - ref_score) if np.isfinite(q) and np.isfinite(ref_score) else np.inf)
+    return worst
+
+
+def cv_noise(oracle, cfg, hps, dtype, rpf, n_folds=None):
+    """Noise per suggestion: the largest change of any fold's first score over the probes."""
+    K, c = n_folds or cfg["n_folds"], cfg["n_classes"]
+    noise = np.zeros(len(hps))
+    for _, up, prec in PROBES:
+        h = hps if up is None else [lr_ulp(x, up) for x in hps]
+        q = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, h, dtype=dtype, prec=prec)[2]
+        for b in range(len(hps)):
+            ok = np.all(np.isfinite(q[b])) and np.all(np.isfinite(rpf[b]))
+            noise[b] = max(noise[b], np.abs(rpf[b, :, 0] - q[b, :, 0]).max() if ok else np.inf)
+    return noise
+
+
+def check_fold_score(oracle, cfg, c, hp, f, dtype, got, ref_score, what):
+    """One model's first fold score against the oracle's under the rule above; returns the category."""
+    noise = fold_noise(oracle, cfg, c, hp, f, dtype, ref_score)
+    bar = score_bar(noise)
+    dev = abs(got - ref_score)
+    print("PARITY fold-score %s: |gpu - oracle| = %.2e, noise %.1e, %s" %
+          (what, dev, noise, "chaotic (not asserted)" if bar is None else "bar %.1e" % bar))
+    if bar is None:
+        assert np.isfinite(got) == np.isfinite(ref_score), what
+        return "chaotic"
+    assert dev < bar, (what, got, ref_score, noise)
+    return "strict" if noise < ABS_SCORE / 10 else "widened"
+
+
 # ------------------------------------------------------------- integers ----
 
 @pytest.mark.parametrize("n,K", [(0, 5), (1, 5), (150, 5), (569, 5), (1797, 5), (20000, 5), (1000, 3), (777, 1)])
@@ -114,6 +174,10 @@ TRACE_CASES = [
     (260, 20, 5, [40, 24], "adam", False, 64, 0.02),
     (180, 9, 0, [17, 18, 19], "sgd", True, 48, 0.01),
     (90, 3, 3, [1], "adam", False, 5, 0.0),
+    # the LDS-resident kernel without its per-epoch row table (rows permuted on the fly): more than 4,096 rows,
+    # and a hidden layer so wide that the table no longer fits beside the weights
+    (5000, 20, 3, [40], "adam", False, 700, 0.01),
+    (1500, 30, 2, [224], "adam", False, 100, 0.01),
 ]
 
 
@@ -123,6 +187,8 @@ def test_per_step_gradients_and_weights_fp32(bb, oracle, n, d, c, hidden, solver
     hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "batch_size": bs, "alpha": alpha, "lr": 0.01,
           "momentum": 0.9, "epochs": 6, "seed": 31337 + n}
     other = dict(hp, hidden=[5] * len(hidden), seed=1)
+    if n >= 1500:
+        assert bb.bbo_mlp_kernel_class(n, d, c, hp, 0) == bb.KERNEL_SMALL
     X, y, ft = bb.to_device(cfg)
     f = 2
     n_tr = int((cfg["fold_idx"] != f).sum())
@@ -248,12 +314,7 @@ def test_random_shapes_bf16_steps(bb, oracle, seed):
             assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_BF16, (case, t, name, "theta")
     # the fold score after 3 epochs of a free bf16 run, against the run's own sensitivity to rounding
     # (batches of one row take a thousand noisy steps)
-    probes = [oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], dict(hp, **kw), f, dtype=1, prec=pr)["scores"][0]
-              for kw, pr in (({}, 1), ({"lr": float(np.nextafter(np.float32(hp["lr"]), np.float32(1)))}, 0),
-                             ({"lr": float(np.nextafter(np.float32(hp["lr"]), np.float32(0)))}, 0))]
-    noise = max(abs(q - ref["scores"][0]) for q in probes)
-    if noise < 5 * ABS_SCORE:
-        assert abs(pf[0, f, 0].item() - ref["scores"][0]) < 5 * ABS_SCORE + 2 * noise, (case, noise)
+    check_fold_score(oracle, cfg, c, hp, f, 1, pf[0, f, 0].item(), ref["scores"][0], "bf16 random shape %s" % (case,))
     for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 1, [t for t in (1, 3, 5) if t < T], T):
         for name, sl in layer_slices(d, hidden, c_out):
             assert relerr(g1[sl], rg[sl]) < REL_BF16, (case, t, name, "grad")
@@ -348,11 +409,13 @@ def test_single_logit_head_steps_and_scores(bb, oracle, n, d, hidden, solver, bs
             assert relerr(th1[sl], rth[sl]) < tol, (t, name, "theta")
     # scores of all five folds after the free run
     rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], 1, cfg["fold_idx"], 5, [hp], dtype=dtype)
-    wide = 5 if dtype else 1
     assert status[0].item() == 0 and rst[0] == 0
-    assert abs(scores[0, 0].item() - rs[0, 0]) < wide * ABS_SCORE
     got = pf.cpu().numpy()
-    assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 2 * wide * ABS_SCORE
+    bar = score_bar(cv_noise(oracle, cfg, [hp], dtype, rpf)[0])
+    print("PARITY one-logit %s: |gpu - oracle| = %.2e, bar %s" % ((n, d, hidden, dtype), np.abs(got[0, :, 0] - rpf[0, :, 0]).max(), bar))
+    if bar is not None:
+        assert abs(scores[0, 0].item() - rs[0, 0]) < bar
+        assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 2 * bar
     for k in range(5):
         assert 0.0 <= got[0, k, 1] <= 1.0
         assert abs(got[0, k, 1] - rpf[0, k, 1]) <= (2.0 if dtype else 1.0) / n_va + 1e-6, k
@@ -451,9 +514,13 @@ def test_linear_models_bf16_steps_and_scores(bb, oracle, n, d, c, solver, bs):
     rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, [hp], dtype=1)
     got = pf.cpu().numpy()
     assert status[0].item() == 0 and rst[0] == 0
-    assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 5 * ABS_SCORE
+    bar = score_bar(cv_noise(oracle, cfg, [hp], 1, rpf)[0])
+    print("PARITY linear bf16 %s: |gpu - oracle| = %.2e, bar %s" % ((n, d, c, solver, bs), np.abs(got[0, :, 0] - rpf[0, :, 0]).max(), bar))
+    if bar is not None:
+        assert np.abs(got[0, :, 0] - rpf[0, :, 0]).max() < 2 * bar
     if c == 0:
-        assert np.abs(got[0, :, 1] - rpf[0, :, 1]).max() < 5 * ABS_SCORE
+        if bar is not None:
+            assert np.abs(got[0, :, 1] - rpf[0, :, 1]).max() < 2 * bar
     else:
         assert np.abs(got[0, :, 1] - rpf[0, :, 1]).max() <= 2.0 / n_va + 1e-6
 
@@ -575,7 +642,8 @@ def test_plateau_stop_epoch_and_score(bb, oracle, n, d, c, hidden, bs, dtype):
         # length of one stall run.  When it does not move, the scores must agree.
         assert abs(done - ref_done) <= (k + 1) * spe, (tol_, k, done // spe, ref_done // spe)
         if done == ref_done:
-            assert abs(pf[0, f, 0].item() - ref["scores"][0]) < (5 if dtype else 1) * ABS_SCORE, (tol_, k)
+            check_fold_score(oracle, cfg, c, hp, f, dtype, pf[0, f, 0].item(), ref["scores"][0],
+                             "plateau stop %s" % ((n, d, hidden, dtype, tol_, k),))
         stops.append(done // spe)
     assert stops[0] < E and stops[2] == E  # the first rule does stop early; the switched-off rule never does
 
@@ -589,63 +657,107 @@ def explained_flips(acc_gpu, acc_ref, n_va):
 
 
 @pytest.mark.parametrize("idx,kw", [
-    (0, {}),                                  # tiny classification, full size
     (1, {"B": 4, "epochs": 12}),              # digits-shaped, full rows, fewer epochs
-    (2, {"B": 8, "epochs": 40}),              # regression / SGD-Nesterov
     (3, {"B": 24, "epochs": 20}),             # many-studies shape, a slice of the suggestions
     (4, {"B": 2, "epochs": 2, "n": 3000}),    # bf16 two-hidden-layer shape, fewer rows
 ])
 def test_final_cv_scores_match_oracle(bb, oracle, idx, kw):
+    """Reduced forms of the configurations, the oracle run live (the stated sizes are further down)."""
     cfg = inputs.make_config(idx, **kw)
     X, y, ft = bb.to_device(cfg)
     K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
     scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, cfg["hparams"], dt, want_per_fold=True)
     torch.cuda.synchronize()
-    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, cfg["hparams"], scores.cpu().numpy(),
-                                                   status.cpu().numpy(), pf.cpu().numpy())
-    if dt == 0:
-        assert n_strict >= max(1, len(cfg["hparams"]) // 2)
-    else:
-        assert n_strict + n_wide >= 1
+    counts = check_scores_against_oracle(oracle, cfg, cfg["hparams"], scores.cpu().numpy(), status.cpu().numpy(),
+                                         pf.cpu().numpy(), "%s reduced %s" % (cfg["name"], kw))
+    assert counts["strict"] + counts["widened"] >= 1
 
 
-def check_scores_against_oracle(oracle, cfg, hps, scores, status, pf):
-    """Final scores of the suggestions `hps` against the oracle.
-
-    A training run amplifies rounding differences by a factor that depends on the run (Adam with a
-    large learning rate turns the sign of a gradient element that is nearly zero into a full step).
-    The oracle measures that factor itself: the run is repeated with no fp32 rounding of the state
-    and with the learning rate moved by one fp32 ulp either way; the largest change of a fold score
-    is the run's "noise".  Below a tenth of the 1e-3 bar the run is stable and held to the bar.  Up
-    to the bar it is held to the bar widened by twice its noise.  Beyond it the trajectory is
-    chaotic and only finiteness and the status flag are compared.  Returns (stable, widened) counts."""
-    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
-    run = lambda h, **kw: oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, h, dtype=dt, **kw)
-    rs, rst, rpf = run(hps)
-    probes = [run(hps, prec=1)[2]]
-    for toward in (np.float32(1e9), np.float32(0)):
-        probes.append(run([dict(h, lr=float(np.nextafter(np.float32(h.get("lr", 1e-3)), toward))) for h in hps])[2])
+def compare_scores(name, cfg, hps, scores, status, pf, rs, rst, rpf, noise):
+    """GPU scores of the suggestions `hps` against the oracle's (rs, rst, rpf) under the rule of score_bar().
+    Every suggestion that is not chaotic must pass; returns and prints the counts per category."""
+    K, c = cfg["n_folds"], cfg["n_classes"]
     n_va = len(cfg["y"]) // K
-    n_strict = n_wide = 0
+    counts = {"strict": 0, "widened": 0, "chaotic": 0, "nonfinite": 0}
+    worst = {"strict": 0.0, "widened": 0.0, "chaotic": 0.0}
     for b in range(len(hps)):
-        if rst[b] != 0:
-            assert status[b] == 1 and not np.isfinite(scores[b, 0])
+        if rst[b] != 0:  # the oracle's run blew up: so must the GPU's
+            assert status[b] == 1 and not np.isfinite(scores[b, 0]), b
+            counts["nonfinite"] += 1
             continue
-        noise = max(np.abs(rpf[b, :, 0] - q[b, :, 0]).max() if np.all(np.isfinite(q[b])) else np.inf for q in probes)
-        if noise >= ABS_SCORE:
+        bar = score_bar(noise[b])
+        dev = float(np.abs(pf[b, :, 0] - rpf[b, :, 0]).max())
+        if bar is None:
+            # beyond the bar the oracle's own score moves by more than 1e-3 under rounding-level changes
+            assert (status[b] == 0) == bool(np.isfinite(scores[b, 0])), b
+            counts["chaotic"] += 1
+            worst["chaotic"] = max(worst["chaotic"], dev) if np.isfinite(dev) else worst["chaotic"]
             continue
-        tol = ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
+        kind = "strict" if noise[b] < ABS_SCORE / 10 else "widened"
         assert status[b] == 0, b
-        assert abs(scores[b, 0] - rs[b, 0]) < tol, (b, scores[b], rs[b], noise)
-        assert np.abs(pf[b, :, 0] - rpf[b, :, 0]).max() < 2 * tol, (b, pf[b], rpf[b], noise)
-        if c >= 2 and noise < ABS_SCORE / 10:
+        assert abs(scores[b, 0] - rs[b, 0]) < bar, (name, b, scores[b], rs[b], noise[b])
+        assert dev < 2 * bar, (name, b, pf[b], rpf[b], noise[b])
+        if c >= 1 and kind == "strict":
             for f in range(K):
-                assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (b, f)
+                assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (name, b, f)
         if c == 0:  # regression: the second score is the mean absolute error
-            assert abs(scores[b, 1] - rs[b, 1]) < tol and np.abs(pf[b, :, 1] - rpf[b, :, 1]).max() < 2 * tol, (b, scores[b], rs[b])
-        n_strict += noise < ABS_SCORE / 10
-        n_wide += noise >= ABS_SCORE / 10
-    return n_strict, n_wide
+            assert abs(scores[b, 1] - rs[b, 1]) < bar and np.abs(pf[b, :, 1] - rpf[b, :, 1]).max() < 2 * bar, (name, b)
+        counts[kind] += 1
+        worst[kind] = max(worst[kind], dev)
+    print("PARITY %s: %d suggestions x %d folds: strict %d (max fold deviation %.1e), widened %d (%.1e), "
+          "chaotic %d (%.1e, not asserted), non-finite on both sides %d" %
+          (name, len(hps), K, counts["strict"], worst["strict"], counts["widened"], worst["widened"],
+           counts["chaotic"], worst["chaotic"], counts["nonfinite"]))
+    return counts
+
+
+def check_scores_against_oracle(oracle, cfg, hps, scores, status, pf, name):
+    """compare_scores() with the oracle run here."""
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], K, hps, dtype=dt)
+    return compare_scores(name, cfg, hps, scores, status, pf, rs, rst, rpf, cv_noise(oracle, cfg, hps, dt, rpf))
+
+
+# The oracle's scores at the stated sizes and epoch counts, written by tests/golden/make_stated_epoch_scores.py
+# (which calls only the oracle): one model of the scale-up configuration takes the oracle two minutes per run.
+def stated_record(idx):
+    import json
+    import os
+    sys_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_stated_epoch_scores", os.path.join(sys_path, "make_stated_epoch_scores.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    rec = json.load(open(os.path.join(sys_path, "stated_epoch_scores.json")))["cfg%d" % idx]
+    cfg = inputs.make_config(idx)
+    assert rec["digest"] == mod.inputs_digest(cfg, rec["picks"]), "inputs changed since the oracle's scores were recorded: rerun tests/golden/make_stated_epoch_scores.py"
+    nan = lambda v: np.nan if v is None else v
+    rs = np.array([[nan(v) for v in row] for row in rec["scores"]], dtype=np.float32)
+    rpf = np.array([[[nan(v) for v in f] for f in b] for b in rec["per_fold"]], dtype=np.float64)
+    noise = np.array([np.inf if v is None else v for v in rec["noise"]])
+    assert rec["epochs"] == cfg["hparams"][0]["epochs"] and rec["rows"] == len(cfg["y"])
+    return cfg, rec["picks"], rs, np.array(rec["status"]), rpf, noise
+
+
+# how many of the recorded suggestions of each configuration must be held to a bar (what the oracle's
+# noise measurement gives for the seeded suggestions; a change here means the inputs or the oracle changed)
+STATED_FLOORS = {0: 8, 1: 6, 2: 7, 3: 5, 4: 1}
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2])
+def test_stated_epochs_parity_configs(bb, idx):
+    """The three 40-model configurations at full size for their stated epochs (20 / 200 / 200): every
+    suggestion against the oracle's recorded scores."""
+    cfg, picks, rs, rst, rpf, noise = stated_record(idx)
+    hps = cfg["hparams"]
+    assert picks == list(range(len(hps)))
+    X, y, ft = bb.to_device(cfg)
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, want_per_fold=True)
+    torch.cuda.synchronize()
+    counts = compare_scores("%s stated size, %d epochs" % (cfg["name"], hps[0]["epochs"]), cfg, hps, scores.cpu().numpy(),
+                            status.cpu().numpy(), pf.cpu().numpy(), rs, rst, rpf, noise)
+    assert counts["strict"] + counts["widened"] >= STATED_FLOORS[idx]
 
 
 def test_full_size_many_studies_launch_sampled(bb, oracle):
@@ -662,9 +774,10 @@ def test_full_size_many_studies_launch_sampled(bb, oracle):
     torch.cuda.synchronize()
     scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
     assert scores.shape == (len(hps), 2)
-    pick = [0, 1, 255, 256, 777, 1024, 1500, 2047]
-    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick])
-    assert n_strict >= 3
+    _, pick, rs, rst, rpf, noise = stated_record(3)
+    counts = compare_scores("cfg3_many_studies stated size, 100 epochs, sampled", cfg, [hps[i] for i in pick], scores[pick],
+                            status[pick], pf[pick], rs, rst, rpf, noise)
+    assert counts["strict"] + counts["widened"] >= STATED_FLOORS[3]
     # every suggestion either finished finite or flagged itself
     assert np.all((status == 0) == np.isfinite(scores[:, 0]))
 
@@ -687,34 +800,32 @@ def test_full_size_linear_launch_sampled(bb, oracle):
     scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
     assert np.all((status == 0) == np.isfinite(scores[:, 0]))
     pick = [0, 1, 255, 256, 777, 1024, 1500, 2047]
-    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick])
-    assert n_strict >= 6
+    counts = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick],
+                                         "cfg3 without hidden layers, stated size, sampled")
+    assert counts["strict"] >= 6
 
 
 def test_full_size_scale_up_launch(bb, oracle):
     """The scale-up workload at its full size (1,640 suggestions x 5 folds, 20,000 rows, 50 epochs) in the
-    benchmark's launch configuration.  A 50-epoch bf16 run of one model costs the oracle minutes, so the
-    full launch is tied to what the oracle can check: (i) a suggestion's score does not depend on the
-    launch it is part of (bit-exact against the same suggestions launched alone), and (ii) the same
-    suggestions at the full row count for one epoch match the oracle."""
+    benchmark's launch configuration.  Three of its suggestions (first, middle, last) are compared with the
+    oracle's recorded scores after the stated 50 epochs; a suggestion's score must also not depend on the
+    launch it is part of (bit-exact against the same suggestions launched alone)."""
     cfg = inputs.make_config(4)
     hps = cfg["hparams"]
     X, y, ft = bb.to_device(cfg)
     K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
     hp_arr = bb.make_hparams(hps)
     ws = bb.alloc_workspace(bb.bbo_mlp_workspace_bytes(len(cfg["y"]), X.shape[1], c, K, hps, dt, hp_arr), X.device)
-    scores, status = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, workspace=ws, hp_arr=hp_arr)
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, hps, dt, workspace=ws, hp_arr=hp_arr, want_per_fold=True)
     torch.cuda.synchronize()
     assert np.all((status.cpu().numpy() == 0) == np.isfinite(scores.cpu().numpy()[:, 0]))
-    pick = [0, 819, 1639]
+    _, pick, rs, rst, rpf, noise = stated_record(4)
     alone, st_alone = bb.bbo_mlp_cv_eval(X, y, c, ft, K, [hps[i] for i in pick], dt)
     torch.cuda.synchronize()
     assert torch.equal(alone, scores[pick]) and torch.equal(st_alone, status[pick])
-    one = [dict(hps[i], epochs=1) for i in pick[:2]]
-    s1, st1, pf1 = bb.bbo_mlp_cv_eval(X, y, c, ft, K, one, dt, want_per_fold=True)
-    torch.cuda.synchronize()
-    n_strict, n_wide = check_scores_against_oracle(oracle, cfg, one, s1.cpu().numpy(), st1.cpu().numpy(), pf1.cpu().numpy())
-    assert n_strict + n_wide >= 1
+    counts = compare_scores("cfg4_scaleup_bf16 stated size, 50 epochs, sampled", cfg, [hps[i] for i in pick],
+                            scores[pick].cpu().numpy(), status[pick].cpu().numpy(), pf[pick].cpu().numpy(), rs, rst, rpf, noise)
+    assert counts["strict"] + counts["widened"] >= STATED_FLOORS[4]
 
 
 # ------------------------------------------------------- hold-out score ----
@@ -766,25 +877,26 @@ def test_holdout_scores_match_oracle(bb, oracle, idx, kw):
     scores, status = scores.cpu().numpy(), status.cpu().numpy()
     run = lambda h, **k: oracle.holdout_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], h, dtype=dt, **k)
     rs, rst = run(hps)
-    probes = [run(hps, prec=1)[0]]
-    for toward in (np.float32(1e9), np.float32(0)):
-        probes.append(run([dict(h, lr=float(np.nextafter(np.float32(h.get("lr", 1e-3)), toward))) for h in hps])[0])
+    probes = [run(hps if up is None else [lr_ulp(h, up) for h in hps], prec=prec)[0] for _, up, prec in PROBES]
     n_va = int((cfg["fold_idx"] < 0).sum())
-    held = 0
+    held = chaotic = 0
     for b in range(len(hps)):
         if rst[b] != 0:
             assert status[b] == 1 and not np.isfinite(scores[b, 0])
             continue
         noise = max(abs(rs[b, 0] - q[b, 0]) if np.isfinite(q[b, 0]) else np.inf for q in probes)
-        if noise >= ABS_SCORE:
+        bar = score_bar(noise)
+        if bar is None:
+            assert (status[b] == 0) == bool(np.isfinite(scores[b, 0])), b
+            chaotic += 1
             continue
-        tol = ABS_SCORE if noise < ABS_SCORE / 10 else ABS_SCORE + 2 * noise
-        assert status[b] == 0 and abs(scores[b, 0] - rs[b, 0]) < tol, (b, scores[b], rs[b], noise)
+        assert status[b] == 0 and abs(scores[b, 0] - rs[b, 0]) < bar, (b, scores[b], rs[b], noise)
         if c >= 2 and noise < ABS_SCORE / 10:
             assert explained_flips(scores[b, 1], rs[b, 1], n_va), (b, scores[b], rs[b])
         if c == 0:
-            assert abs(scores[b, 1] - rs[b, 1]) < tol, (b, scores[b], rs[b])
+            assert abs(scores[b, 1] - rs[b, 1]) < bar, (b, scores[b], rs[b])
         held += 1
+    print("PARITY hold-out %s %s: held to a bar %d, chaotic %d of %d" % (cfg["name"], kw, held, chaotic, len(hps)))
     assert held >= 1
 
 
@@ -859,7 +971,13 @@ def test_mixed_shapes_in_one_call_keep_their_kernels(bb, oracle, dtype):
             assert relerr(th[t, sl], ref["theta_after"][t, sl]) < tol, (t, name, "theta")
     rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, hps, dtype=dtype)
     assert np.array_equal(status.cpu().numpy(), rst)
-    assert np.abs(pf.cpu().numpy()[:, :, 0] - rpf[:, :, 0]).max() < (10 if dtype else 2) * ABS_SCORE
+    noise = cv_noise(oracle, cfg, hps, dtype, rpf)
+    got = pf.cpu().numpy()
+    for i in range(len(hps)):
+        bar = score_bar(noise[i])
+        print("PARITY mixed shapes dtype %d %s: |gpu - oracle| = %.2e, bar %s" % (dtype, shapes[i], np.abs(got[i, :, 0] - rpf[i, :, 0]).max(), bar))
+        if bar is not None:
+            assert np.abs(got[i, :, 0] - rpf[i, :, 0]).max() < 2 * bar, (i, shapes[i])
 
 
 def test_divergent_neighbours_on_the_same_workgroup_bf16(bb):
@@ -936,7 +1054,8 @@ def test_maximum_sizes(bb, oracle, dtype):
         assert relerr(g[0, sl], ref["grad"][0, sl]) < tol, (name, "grad")
         assert relerr(th[0, sl], ref["theta_after"][0, sl]) < tol, (name, "theta")
     assert np.all(np.isfinite(g[1])) and np.all(np.isfinite(th[1]))
-    assert status.item() == 0 and abs(pf[0, f, 0].item() - ref["scores"][0]) < (20 if dtype else 1) * ABS_SCORE
+    assert status.item() == 0
+    check_fold_score(oracle, cfg, c, hp, f, dtype, pf[0, f, 0].item(), ref["scores"][0], "maximum sizes dtype %d" % dtype)
     # one more unit, feature, class or layer is refused with a code, not a fault
     for bad_hp, bad_d, bad_c in [(dict(hp, hidden=[1025]), d, c), (dict(hp, hidden=[8] * 5), d, c)]:
         with pytest.raises(bb.BboError):
