@@ -206,9 +206,9 @@ def main():
     if args.linear and idx == 4:
         sys.exit("bench.py: --linear goes with the fp32 workloads cfg0..cfg3")
     cfg, res, mfma, hbm = run_workload(idx, args.steps, args.warmup, args.suggestions, args.epochs, args.linear)
-    # cfg4 cannot keep its optimizer state on chip (0.9 MB of fp32 state per model, 256 models in flight):
-    # the training kernel is bound by streaming that state, so its roofline is HBM; the MFMA view is kept too.
-    # The small fp32 models live in LDS and are bound by MFMA issue and latency.
+    # The metric is throughput against the dense MFMA peak of the arithmetic type, so that is `roofline`.
+    # For cfg4 the optimizer state streams from HBM every step; `roofline_hbm` shows the same kernel
+    # against the HBM peak (algorithmic state + input bytes), with the counter-measured traffic beside it.
     out = {
         "metric": "MLP models x epochs/sec for batched CV eval",
         "value": res["value"], "unit": "model-epochs/s",
@@ -217,9 +217,10 @@ def main():
         "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
         "tflops": res["tflops"], "pct_mfma_peak": res["pct_mfma_peak"],
         "nonfinite_suggestions": res["nonfinite_suggestions"],
-        "roofline": hbm if idx == 4 else mfma,
-        "roofline_mfma": mfma,
+        "roofline": mfma,
     }
+    if idx == 4:
+        out["roofline_hbm"] = hbm
     if idx == 4 and not args.no_secondary and not (args.suggestions or args.epochs):
         _, r3, m3, _ = run_workload(3, 3, 1)
         out["secondary"] = {"config": r3["config"], "value": r3["value"], "unit": "model-epochs/s",
@@ -229,6 +230,14 @@ def main():
         out["secondary_linear"] = {"config": rl["config"], "value": rl["value"], "unit": "model-epochs/s",
                                    "ms_per_step": rl["ms_per_step"], "dtype": rl["dtype"], "tflops": rl["tflops"],
                                    "roofline": ml}
+    if idx == 4 and not args.no_secondary and not (args.suggestions or args.epochs):
+        # the three 40-model configurations (latency-bound parity workloads), full size, 1 warm-up + 5 calls each
+        out["parity_workloads"] = {}
+        for i in (0, 1, 2):
+            _, r, m, _ = run_workload(i, 5, 1)
+            out["parity_workloads"][r["config"]["workload"]] = {
+                "ms_per_step": r["ms_per_step"], "value": r["value"], "unit": "model-epochs/s", "dtype": r["dtype"],
+                "mlps": r["config"]["mlps"], "epochs": r["config"]["epochs"], "tflops": r["tflops"], "kernel": m["kernel"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
