@@ -116,6 +116,30 @@ int bbo_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t 
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * bbo_mlp_cv_eval for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the workspace is a static device array inside the library, so the call takes
+ * no workspace and makes no allocation of any kind on the device or in pinned
+ * host memory (the item list travels as kernel arguments).  Same arguments,
+ * same kernels and bit-identical results otherwise.
+ *   limit   the problem's bbo_mlp_workspace_bytes() must not exceed
+ *           BBO_STATIC_SCRATCH_BYTES, and its item records (a few hundred
+ *           bytes per suggestion and fold) BBO_STATIC_MAX_ITEM_BYTES; beyond
+ *           that the call returns BBO_WORKSPACE_TOO_SMALL and enqueues nothing.
+ *   sharing every call on a device uses that device's one array: calls that
+ *           overlap in time on one device (different streams or threads) race.
+ *           Calls one after the other on one stream are fine; nothing is
+ *           assumed about the array's contents.
+ * Each device the library runs on holds the array until the process ends.
+ */
+#define BBO_STATIC_SCRATCH_BYTES (32u << 20)
+#define BBO_STATIC_MAX_ITEM_BYTES (1u << 20)
+int bbo_mlp_cv_eval_static(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
+                           const int32_t* fold_idx, int32_t n_folds, const bbo_mlp_hparams* hp,
+                           int32_t B, int32_t dtype, float* scores, int32_t* status, float* per_fold,
+                           void* stream);
+
+/*
  * Same evaluation, additionally recording the training steps
  * [step_begin, step_end) (counted over all epochs) of the single model
  * (trace_b, trace_fold) for parity checks of the per-step arithmetic.

@@ -18,7 +18,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, DEVICE_ERROR = range(5)
 ADAM, SGD = 0, 1
 F32, BF16 = 0, 1
 
-EXPORTS = ["bbo_mlp_workspace_bytes", "bbo_mlp_cv_eval", "bbo_mlp_cv_eval_traced", "bbo_mlp_fold_lists",
+EXPORTS = ["bbo_mlp_workspace_bytes", "bbo_mlp_cv_eval", "bbo_mlp_cv_eval_static", "bbo_mlp_cv_eval_traced", "bbo_mlp_fold_lists",
            "bbo_mlp_holdout_eval", "bbo_mlp_holdout_lists", "bbo_mlp_minibatch_rows", "bbo_mlp_init_params", "bbo_mlp_param_count", "bbo_mlp_kernel_class",
            "bbo_mlp_last_error"]
 
@@ -206,6 +206,24 @@ def bbo_mlp_cv_eval(X, y, n_classes, fold_idx, n_folds, hps, dtype=F32, workspac
     if trace is not None:
         out.append({"loss": tr[:T, 0], "grad": tr[:T, 1:1 + P], "theta_after": tr[:T, 1 + P:]})
     return tuple(out)
+
+
+def bbo_mlp_cv_eval_static(X, y, n_classes, fold_idx, n_folds, hps, dtype=F32, scores=None, status=None, per_fold=None,
+                           stream=None, hp_arr=None):
+    """bbo_mlp_cv_eval on the library's static workspace: allocates nothing when the caller passes the
+    output tensors (scores float32 [B,2], status int32 [B], optionally per_fold float32 [B,K,2]).
+    Returns (scores, status)."""
+    _check_inputs(X, y, fold_idx, n_classes, dtype)
+    B = len(hps)
+    h = hp_arr if hp_arr is not None else make_hparams(hps)
+    if scores is None:
+        scores = _new(stream, (max(B, 1), 2), dtype=torch.float32, device=X.device)
+    if status is None:
+        status = _new(stream, max(B, 1), dtype=torch.int32, device=X.device)
+    _check(lib().bbo_mlp_cv_eval_static(_ptr(X), _ptr(y), C.c_int64(int(X.shape[0])), C.c_int32(int(X.shape[1])),
+                                        C.c_int32(n_classes), _ptr(fold_idx), C.c_int32(n_folds), h, C.c_int32(B),
+                                        C.c_int32(dtype), _ptr(scores), _ptr(status), _ptr(per_fold), _stream(stream)))
+    return scores[:B], status[:B]
 
 
 def bbo_mlp_holdout_eval(X, y, n_classes, fold_idx, hps, dtype=F32, workspace=None, stream=None, hp_arr=None):

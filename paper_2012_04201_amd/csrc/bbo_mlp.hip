@@ -39,6 +39,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -50,6 +51,12 @@
 #include "train_linear_f32.h"
 
 static_assert(sizeof(bbo_mlp_hparams) == 80, "the hyper-parameter record is part of the ABI");
+
+// Workspace of bbo_mlp_cv_eval_static: device memory that exists from the moment the library is loaded, for
+// callers that cannot allocate.  In host code the name is only a handle for hipGetSymbolAddress; the address
+// the kernels get is the one that call returns (scratch_address()).  One copy per device, shared by every
+// call on that device, contents left over from the last call.
+static __device__ __align__(256) unsigned char scratch[BBO_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -966,6 +973,48 @@ int stage_items(const void* src, size_t bytes, void* dst, hipStream_t s) {
   return BBO_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_address(void** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* ptr[MAX_DEV] = {};
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEV) return fail(BBO_UNSUPPORTED, "device index beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(BBO_DEVICE_ERROR, "hipGetSymbolAddress returned no address");
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return BBO_OK;
+}
+
+// Host bytes -> device memory without a staging buffer: the bytes travel as the argument of a small kernel
+// (3.5 KB per launch).  Used where nothing may be allocated, not even pinned host memory.
+struct PokeChunk {
+  uint32_t words[896];
+};
+__global__ void k_poke(const PokeChunk c, uint32_t* __restrict__ dst, int n_words) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_words) dst[i] = c.words[i];
+}
+int poke_items(const void* src, size_t bytes, void* dst, hipStream_t s) {
+  constexpr size_t CH = sizeof(PokeChunk);
+  for (size_t off = 0; off < bytes; off += CH) {
+    PokeChunk c;
+    const size_t nb = std::min(CH, bytes - off);
+    memset(&c, 0, sizeof(c));
+    memcpy(&c, (const char*)src + off, nb);
+    const int nw = (int)((nb + 3) / 4);  // the item region is padded to 256 bytes: whole words stay inside it
+    hipLaunchKernelGGL(k_poke, dim3((nw + 255) / 256), dim3(256), 0, s, c, (uint32_t*)((char*)dst + off), nw);
+    HIP_TRY(hipGetLastError());
+  }
+  return BBO_OK;
+}
+
 int64_t param_count(int d, int n_classes, const bbo_mlp_hparams& h) {
   int32_t dims[MAXL + 1];
   int L;
@@ -979,7 +1028,7 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
              int32_t n_folds, const bbo_mlp_hparams* hp, int32_t B, int32_t dtype, float* scores,
              int32_t* status, float* per_fold, void* workspace, size_t workspace_bytes, void* stream,
              int32_t trace_b, int32_t trace_fold, int64_t step_begin, int64_t step_end, float* trace_out,
-             size_t trace_floats, const float* state_in, bool traced, int fold_base = 0) {
+             size_t trace_floats, const float* state_in, bool traced, int fold_base = 0, bool static_ws = false) {
   g_err.clear();
   int rc = check_problem(n, d, n_classes, n_folds, dtype);
   if (rc) return rc;
@@ -988,6 +1037,10 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   if (B == 0) return BBO_OK;
   if (!scores || !status) return fail(BBO_INVALID_ARG, "scores/status is null");
   if (n > 0 && (!X || !y || !fold_idx)) return fail(BBO_INVALID_ARG, "X/y/fold_idx is null");
+  if (static_ws) {
+    if ((rc = scratch_address(&workspace))) return rc;
+    workspace_bytes = BBO_STATIC_SCRATCH_BYTES;
+  }
   if (!workspace) return fail(BBO_INVALID_ARG, "workspace is null");
   if (((uintptr_t)workspace & 255) != 0) return fail(BBO_INVALID_ARG, "workspace must be 256-byte aligned");
   if (traced) {
@@ -1001,6 +1054,12 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
   Plan pl;
   rc = make_plan(pl, n, d, n_classes, n_folds, fold_base, hp, B, dtype);
   if (rc) return rc;
+  if (static_ws && (pl.total > BBO_STATIC_SCRATCH_BYTES || pl.items_bytes > BBO_STATIC_MAX_ITEM_BYTES))
+    return fail(BBO_WORKSPACE_TOO_SMALL,
+                "this problem needs " + std::to_string(pl.total) + " bytes of workspace (" +
+                    std::to_string(pl.items_bytes) + " of item records); the allocation-free entry point holds " +
+                    std::to_string((size_t)BBO_STATIC_SCRATCH_BYTES) + " (" +
+                    std::to_string((size_t)BBO_STATIC_MAX_ITEM_BYTES) + "): use bbo_mlp_cv_eval with a workspace");
   if (workspace_bytes < pl.total) return fail(BBO_WORKSPACE_TOO_SMALL, "workspace too small");
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
@@ -1029,7 +1088,8 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
         }
       }
     }
-    rc = stage_items(blob.data(), blob.size(), ws + pl.o_items, s);
+    rc = static_ws ? poke_items(blob.data(), blob.size(), ws + pl.o_items, s)
+                   : stage_items(blob.data(), blob.size(), ws + pl.o_items, s);
     if (rc) return rc;
   }
 
@@ -1133,6 +1193,13 @@ int bbo_mlp_cv_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t 
                     size_t workspace_bytes, void* stream) {
   return run_eval(X, y, n, d, n_classes, fold_idx, n_folds, hp, B, dtype, scores, status, per_fold, workspace,
                   workspace_bytes, stream, -1, -1, 0, 0, nullptr, 0, nullptr, false);
+}
+
+int bbo_mlp_cv_eval_static(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
+                           const int32_t* fold_idx, int32_t n_folds, const bbo_mlp_hparams* hp, int32_t B,
+                           int32_t dtype, float* scores, int32_t* status, float* per_fold, void* stream) {
+  return run_eval(X, y, n, d, n_classes, fold_idx, n_folds, hp, B, dtype, scores, status, per_fold, nullptr, 0,
+                  stream, -1, -1, 0, 0, nullptr, 0, nullptr, false, 0, true);
 }
 
 int bbo_mlp_cv_eval_traced(const void* X, const void* y, int64_t n, int32_t d, int32_t n_classes,
