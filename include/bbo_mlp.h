@@ -67,6 +67,17 @@ typedef struct bbo_mlp_hparams {
                                      than this many epochs in a row; `epochs` stays
                                      the upper limit.  Switched off in a traced call
                                      that resumes from state_in. */
+  float validation_fraction;      /* early stopping on held-out rows (the option the
+                                     benchmark's MLP-adam / MLP-sgd of Table 1 are
+                                     tuned with), active when > 0 and
+                                     n_iter_no_change > 0: floor(fraction * n_train)
+                                     rows (at least 1, at most n_train - 1) of the
+                                     fold's training rows, chosen by a seeded
+                                     shuffle, are never trained on, and the rule
+                                     above watches THEIR loss (cross-entropy, or the
+                                     plain mean squared error) after every epoch
+                                     instead of the training loss. */
+  int32_t reserved;               /* 0 */
 } bbo_mlp_hparams;
 
 /*
@@ -206,6 +217,8 @@ int bbo_mlp_holdout_lists(const int32_t* fold_idx, int64_t n, int32_t* train_idx
  * The rows of minibatch `step` of `epoch` for suggestion hp[0] in fold `fold`,
  * from train_idx / counts as written by bbo_mlp_fold_lists; fold = -1 is the
  * hold-out model, with train_idx / counts from bbo_mlp_holdout_lists.
+ * step = -1 asks for the rows the model sets aside for early stopping instead
+ * (none unless validation_fraction and n_iter_no_change are both positive).
  *   rows_out  device, int32 [batch rows]; n_rows_out device int32 [1]
  */
 int bbo_mlp_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int64_t n,

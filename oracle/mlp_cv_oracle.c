@@ -25,7 +25,8 @@
  *   - ReLU derivative at 0 is 0;
  *   - Adam in the form with the bias corrections folded into the step size
  *     and eps added to sqrt(v); SGD with momentum, optionally Nesterov;
- *     constant learning rate, exactly `epochs` passes, no early stopping;
+ *     constant learning rate, exactly `epochs` passes unless a stopping rule
+ *     is switched on (see train_and_score);
  *   - scores on the held fold: nll = -mean log softmax(z)[y] (no clipping),
  *     acc = mean[argmax z == y] with ties to the lowest class, mse =
  *     mean (yhat - y)^2;  the CV score is the unweighted mean over folds.
@@ -69,6 +70,9 @@ typedef struct oracle_hparams {
   uint64_t seed;
   float tol;                /* with n_iter_no_change > 0: training stops once the epoch's mean data loss */
   int32_t n_iter_no_change; /* has failed to improve on the best so far by tol more than this many epochs in a row */
+  float validation_fraction; /* with n_iter_no_change > 0 and this > 0: that share of the fold's training rows is
+                                set aside, never trained on, and the rule watches ITS loss after every epoch */
+  int32_t reserved;
 } oracle_hparams;
 
 /* ------------------------------------------------------------------ */
@@ -496,16 +500,51 @@ static int64_t eff_batch(const oracle_hparams* hp, int64_t n_tr) {
   return bs;
 }
 
+/* Early stopping on a validation fraction (the scikit-learn-style option the benchmark's MLP-adam / MLP-sgd
+ * of Table 1 are tuned with).  Active when n_iter_no_change > 0 and validation_fraction > 0 and the fold has
+ * at least two training rows.  The fold's ascending training list is cut by a keyed bijection of its own
+ * (key = model key folded with 2): list[pi_split(p)] for p < n_fit are the rows the model is fitted on, in
+ * that order; p >= n_fit are the n_hold = floor(fraction * n_train) rows (at least 1, at most n_train - 1)
+ * it never trains on.  Returns n_hold (0: the rule is off). */
+static int64_t hold_count(const oracle_hparams* hp, int64_t n_tr) {
+  if (hp->n_iter_no_change <= 0 || !(hp->validation_fraction > 0.0f) || n_tr < 2) return 0;
+  int64_t h = (int64_t)floor((double)hp->validation_fraction * (double)n_tr);
+  if (h < 1) h = 1;
+  if (h > n_tr - 1) h = n_tr - 1;
+  return h;
+}
+
+static uint64_t split_key(uint64_t seed, int fold) { return oracle_combine(model_key(seed, fold), 2); }
+
+/* Index into the fold's training list of position p of epoch `key`'s order over the fitted rows. */
+static int64_t fit_index(const oracle_hparams* hp, int fold, uint64_t key, int64_t n_tr, int64_t n_hold, int64_t p) {
+  int64_t q = perm_index(key, n_tr - n_hold, p);
+  return n_hold ? perm_index(split_key(hp->seed, fold), n_tr, q) : q;
+}
+
+/* The rows set aside for early stopping of fold f's model (empty when the rule is off); returns the count. */
+int64_t oracle_early_stop_rows(const int32_t* fold_idx, int64_t n, const oracle_hparams* hp, int32_t f,
+                               int32_t* rows_out) {
+  int32_t* tr = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+  int64_t n_tr, n_va;
+  oracle_fold_lists(fold_idx, n, f, tr, NULL, &n_tr, &n_va);
+  int64_t n_hold = hold_count(hp, n_tr), n_fit = n_tr - n_hold;
+  for (int64_t i = 0; i < n_hold; i++) rows_out[i] = tr[perm_index(split_key(hp->seed, f), n_tr, n_fit + i)];
+  free(tr);
+  return n_hold;
+}
+
 /* Rows of minibatch `step` of `epoch` for fold f; returns the row count. */
 int64_t oracle_minibatch_rows(const int32_t* fold_idx, int64_t n, const oracle_hparams* hp,
                               int32_t f, int32_t epoch, int64_t step, int32_t* rows_out) {
   int32_t* tr = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
   int64_t n_tr, n_va;
   oracle_fold_lists(fold_idx, n, f, tr, NULL, &n_tr, &n_va);
-  int64_t bs = eff_batch(hp, n_tr);
-  int64_t lo = step * bs, hi = lo + bs > n_tr ? n_tr : lo + bs, cnt = 0;
+  int64_t n_hold = hold_count(hp, n_tr), n_fit = n_tr - n_hold;
+  int64_t bs = eff_batch(hp, n_fit);
+  int64_t lo = step * bs, hi = lo + bs > n_fit ? n_fit : lo + bs, cnt = 0;
   uint64_t key = epoch_key(hp->seed, f, epoch);
-  for (int64_t p = lo; p < hi; p++) rows_out[cnt++] = tr[perm_index(key, n_tr, p)];
+  for (int64_t p = lo; p < hi; p++) rows_out[cnt++] = tr[fit_index(hp, f, key, n_tr, n_hold, p)];
   free(tr);
   return cnt;
 }
@@ -524,18 +563,22 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
                            const int32_t* tr, int64_t n_tr, const int32_t* va, int64_t n_va,
                            int prec, double out[2], trace_t* trace, double* theta_out) {
   int64_t P = net->P;
-  int64_t bs = eff_batch(hp, n_tr);
+  int64_t n_hold = hold_count(hp, n_tr), n_fit = n_tr - n_hold;
+  int64_t bs = eff_batch(hp, n_fit);
   int64_t max_rows = bs > n_va ? bs : n_va;
+  if (n_hold > max_rows) max_rows = n_hold;
   scratch_t s;
   double* theta = (double*)malloc(sizeof(double) * (size_t)P * 4);
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)(bs > 0 ? bs : 1));
-  if (!theta || !rows || scratch_alloc(&s, net, max_rows)) return -2;
+  int32_t* held = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_hold > 0 ? n_hold : 1));
+  if (!theta || !rows || !held || scratch_alloc(&s, net, max_rows)) return -2;
+  for (int64_t i = 0; i < n_hold; i++) held[i] = tr[perm_index(split_key(hp->seed, fold), n_tr, n_fit + i)];
   double *grad = theta + P, *m = theta + 2 * P, *v = theta + 3 * P;
   memset(grad, 0, sizeof(double) * (size_t)P * 3);
   opt_t o = {m, v, 0};
   init_params(net, hp->seed, fold, theta);
 
-  int64_t steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0, gstep = 0;
+  int64_t steps = n_fit > 0 ? (n_fit + bs - 1) / bs : 0, gstep = 0;
   int done = 0, stalled = 0, stop = 0;
   float best = INFINITY;
   for (int e = 0; e < hp->epochs && !done && !stop; e++) {
@@ -543,11 +586,11 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
     /* inverse-scaling schedule of the sgd solver: the rate falls with the rows seen before the epoch */
     double lr_e = (double)hp->lr;
     if (hp->solver != 0 && hp->power_t != 0.0f)
-      lr_e = rnd(lr_e / pow(1.0 + (double)e * (double)n_tr, (double)hp->power_t), prec);
+      lr_e = rnd(lr_e / pow(1.0 + (double)e * (double)n_fit, (double)hp->power_t), prec);
     double esum = 0.0;
     for (int64_t st = 0; st < steps && !done; st++, gstep++) {
-      int64_t lo = st * bs, hi = lo + bs > n_tr ? n_tr : lo + bs, mb = hi - lo;
-      for (int64_t p = lo; p < hi; p++) rows[p - lo] = tr[perm_index(key, n_tr, p)];
+      int64_t lo = st * bs, hi = lo + bs > n_fit ? n_fit : lo + bs, mb = hi - lo;
+      for (int64_t p = lo; p < hi; p++) rows[p - lo] = tr[fit_index(hp, fold, key, n_tr, n_hold, p)];
       double data = 0.0;
       double loss = loss_grad(net, D, rows, mb, theta, (double)hp->alpha, grad, &s, prec, &data);
       esum += data * (double)mb;
@@ -565,9 +608,15 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
         if (trace->stop_after && gstep + 1 == trace->step_end) done = 1;
       }
     }
-    /* plateau stop on the epoch's mean data loss (single precision, as the kernels decide it) */
+    /* stopping rule, decided in single precision: without a validation fraction it watches the epoch's mean
+     * data loss over the steps just taken; with one, the loss of the rows set aside (the same loss the final
+     * score reports: cross-entropy, or the plain mean squared error), under the weights the epoch ends with */
     if (hp->n_iter_no_change > 0 && steps > 0 && !done) {
-      float le = (float)(esum / (double)n_tr);
+      float le = (float)(esum / (double)n_fit);
+      if (n_hold > 0) {
+        forward(net, D, held, n_hold, theta, &s, prec);
+        le = (float)data_loss(net, D, held, n_hold, &s, prec, 0, 0);
+      }
       stalled = le > best - hp->tol ? stalled + 1 : 0;
       if (le < best) best = le;
       if (stalled > hp->n_iter_no_change) stop = 1;
@@ -607,6 +656,7 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
   scratch_free(&s, net);
   free(theta);
   free(rows);
+  free(held);
   return 0;
 }
 

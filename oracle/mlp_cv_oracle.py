@@ -35,6 +35,8 @@ class HParams(C.Structure):
         ("seed", C.c_uint64),
         ("tol", C.c_float),
         ("n_iter_no_change", C.c_int32),
+        ("validation_fraction", C.c_float),
+        ("reserved", C.c_int32),
     ]
 
 
@@ -42,9 +44,11 @@ def build(force=False):
     """Compile the oracle with gcc (no fast-math, no contraction)."""
     if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
         return _LIB
+    tmp = _LIB + ".%d.tmp" % os.getpid()
     cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-           "-fno-fast-math", "-Wall", "-o", _LIB, _SRC, "-lm"]
+           "-fno-fast-math", "-Wall", "-o", tmp, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
+    os.replace(tmp, _LIB)  # a process that has the old library mapped keeps it
     return _LIB
 
 
@@ -65,6 +69,7 @@ def lib():
         L.oracle_bf16_bits.argtypes = [C.c_float]
         L.oracle_param_count.restype = C.c_int64
         L.oracle_minibatch_rows.restype = C.c_int64
+        L.oracle_early_stop_rows.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -91,6 +96,7 @@ def make_hparams(dicts):
         h.power_t = float(dct.get("power_t", 0.0))
         h.tol = float(dct.get("tol", 0.0))
         h.n_iter_no_change = int(dct.get("n_iter_no_change", 0))
+        h.validation_fraction = float(dct.get("validation_fraction", 0.0))
     return arr
 
 
@@ -155,6 +161,16 @@ def minibatch_rows(fold_idx, hp, f, epoch, step):
     out = np.zeros(max(n, 1), dtype=np.int32)
     cnt = lib().oracle_minibatch_rows(_p(fold_idx), C.c_int64(n), C.byref(h[0]), C.c_int32(f), C.c_int32(epoch),
                                       C.c_int64(step), _p(out))
+    return out[:cnt].copy()
+
+
+def early_stop_rows(fold_idx, hp, f):
+    """The rows fold f's model sets aside for early stopping (empty when the rule is off)."""
+    fold_idx = np.ascontiguousarray(fold_idx, dtype=np.int32)
+    n = fold_idx.shape[0]
+    h = make_hparams([hp])
+    out = np.zeros(max(n, 1), dtype=np.int32)
+    cnt = lib().oracle_early_stop_rows(_p(fold_idx), C.c_int64(n), C.byref(h[0]), C.c_int32(f), _p(out))
     return out[:cnt].copy()
 
 

@@ -41,6 +41,8 @@ class HParams(C.Structure):
         ("seed", C.c_uint64),
         ("tol", C.c_float),
         ("n_iter_no_change", C.c_int32),
+        ("validation_fraction", C.c_float),
+        ("reserved", C.c_int32),
     ]
 
 
@@ -93,6 +95,7 @@ def make_hparams(dicts):
         h.power_t = float(dct.get("power_t", 0.0))
         h.tol = float(dct.get("tol", 0.0))
         h.n_iter_no_change = int(dct.get("n_iter_no_change", 0))
+        h.validation_fraction = float(dct.get("validation_fraction", 0.0))
     return arr
 
 
@@ -269,6 +272,7 @@ def bbo_mlp_fold_lists(fold_idx, n_folds, stream=None):
 
 
 def bbo_mlp_minibatch_rows(train_idx, counts, n, hp, fold, epoch, step, stream=None):
+    """Rows of one minibatch; step = -1: the rows the model sets aside for early stopping."""
     dev = train_idx.device
     rows = torch.full((max(n, 1),), -1, dtype=torch.int32, device=dev)
     cnt = torch.zeros(1, dtype=torch.int32, device=dev)

@@ -50,7 +50,7 @@
 #include "train_small_f32.h"
 #include "train_linear_f32.h"
 
-static_assert(sizeof(bbo_mlp_hparams) == 80, "the hyper-parameter record is part of the ABI");
+static_assert(sizeof(bbo_mlp_hparams) == 88, "the hyper-parameter record is part of the ABI");
 
 // Workspace of bbo_mlp_cv_eval_static: device memory that exists from the moment the library is loaded, for
 // callers that cannot allocate.  In host code the name is only a handle for hipGetSymbolAddress; the address
@@ -305,10 +305,10 @@ struct Trainer {
 
   // Rows of this step -> row list; gather X into a_0 in both layouts; set the
   // ones unit of every unit-major activation.
-  __device__ void gather(const int32_t* list, uint64_t key, int n_list, int lo, int mb, int Mrows, bool permute) const {
+  __device__ void gather(const int32_t* list, const RowSplit& sp, int mode, uint64_t key, int lo, int mb, int Mrows) const {
     int32_t* rl = rowlist();
     for (int p = threadIdx.x; p < Mrows; p += blockDim.x)
-      rl[p] = p < mb ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
+      rl[p] = p < mb ? list[row_index(sp, mode, key, (uint32_t)(lo + p))] : -1;
     __syncthreads();
     const int d = y.dims[0], kp0 = y.kp[0], p16a = y.p16a[0], rows = y.rows;
     const int CW = max(kp0, p16a);
@@ -511,9 +511,11 @@ struct Trainer {
     const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
     const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
     const int32_t* va = P.val_idx + (int64_t)fl * P.n;
-    const int bs = eff_batch(it.batch_size, n_tr);
-    const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f);
+    const RowSplit sp = row_split(km, it.patience, it.val_frac, n_tr);
+    const int n_fit = sp.n_fit;
+    const int bs = eff_batch(it.batch_size, n_fit);
+    const int steps = n_fit > 0 ? (n_fit + bs - 1) / bs : 0;
     const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     // zero the slot, then initial parameters
@@ -545,11 +547,11 @@ struct Trainer {
     const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
     for (int e = e0; e < it.epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
-      const float lr_e = epoch_lr(it.lr, it.power_t, e, n_tr);  // SGD
+      const float lr_e = epoch_lr(it.lr, it.power_t, e, n_fit);  // SGD
       double esum = 0.0;  // the thread's share of the epoch's summed data loss
       for (int st = e == e0 ? st0 : 0; st < steps; st++, gstep++) {
-        const int lo = st * bs, mb = min(bs, n_tr - lo), Mrows = rup(mb, O::KSTEP);
-        gather(tr, ke, n_tr, lo, mb, Mrows, true);
+        const int lo = st * bs, mb = min(bs, n_fit - lo), Mrows = rup(mb, O::KSTEP);
+        gather(tr, sp, ROWS_EPOCH, ke, lo, mb, Mrows);
         forward(Mrows);
         const double lpart = loss_and_delta(mb, Mrows);
         esum += lpart;
@@ -569,15 +571,31 @@ struct Trainer {
         }
         wgrad_update(mb, Mrows, lr_t, rec);
       }
-      if (watch && plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) break;
+      if (watch) {
+        float watched = (float)(block_sum(esum, red) / (double)n_fit);
+        if (sp.n_hold) watched = (float)(score_rows(tr, sp, ROWS_HELD, sp.n_hold, nullptr) / (double)sp.n_hold);
+        if (plateau.stop_after(watched, it.tol, it.patience)) break;
+      }
     }
 
-    // validation score on the held rows, in chunks of the slot's row capacity
+    // validation score on the held rows
+    double hits = 0.0;
+    const double lsum = score_rows(va, sp, ROWS_PLAIN, n_va, &hits);
+    if (threadIdx.x == 0) {
+      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
+      out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
+      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
+    }
+  }
+
+  // Summed loss (cross-entropy, or plain squared error) of `count` rows of a list under the current weights,
+  // in chunks of the slot's row capacity; optionally the summed second score.  Block-wide result.
+  __device__ double score_rows(const int32_t* list, const RowSplit& sp, int mode, int count, double* hits_out) const {
     double lsum = 0.0, hits = 0.0;
     const int c = y.dims[y.L], zc = y.p16[y.L];
-    for (int off = 0; off < n_va; off += y.rows) {
-      const int mb = min(y.rows, n_va - off), Mrows = rup(mb, O::KSTEP);
-      gather(va, 0, n_va, off, mb, Mrows, false);
+    for (int off = 0; off < count; off += y.rows) {
+      const int mb = min(y.rows, count - off), Mrows = rup(mb, O::KSTEP);
+      gather(list, sp, mode, 0, off, mb, Mrows);
       forward(Mrows);
       const float* Z = fp(y.Z);
       const int32_t* rl = rowlist();
@@ -590,11 +608,8 @@ struct Trainer {
     }
     lsum = block_sum(lsum, red);
     hits = block_sum(hits, red);
-    if (threadIdx.x == 0) {
-      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
-      out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
-      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
-    }
+    if (hits_out) *hits_out = hits;
+    return lsum;
   }
 };
 
@@ -644,16 +659,18 @@ __global__ void k_reduce(const float* __restrict__ item_out, int B, int K, float
 
 // Inspection kernels ---------------------------------------------------------
 __global__ void k_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int64_t n, uint64_t seed,
-                                 int fold, int epoch, int64_t step, int batch_size, int32_t* rows_out,
-                                 int32_t* n_rows_out) {
+                                 int fold, int epoch, int64_t step, int batch_size, int patience, float val_frac,
+                                 int32_t* rows_out, int32_t* n_rows_out) {
   const int fl = fold < 0 ? 0 : fold;  // the hold-out lists are a set of their own, with one entry
   const int n_tr = counts[2 * fl];
-  const int bs = eff_batch(batch_size, n_tr);
-  const int64_t lo = step * bs;
-  const int mb = (int)max((int64_t)0, min((int64_t)bs, (int64_t)n_tr - lo));
-  const uint64_t ke = key_epoch(key_model(seed, fold), epoch);
+  const uint64_t km = key_model(seed, fold);
+  const RowSplit sp = row_split(km, patience, val_frac, n_tr);
+  const int bs = eff_batch(batch_size, sp.n_fit);
+  const int64_t lo = step < 0 ? 0 : step * bs;
+  const int mb = step < 0 ? sp.n_hold : (int)max((int64_t)0, min((int64_t)bs, (int64_t)sp.n_fit - lo));
+  const uint64_t ke = key_epoch(km, epoch);
   for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < mb; p += gridDim.x * blockDim.x)
-    rows_out[p] = train_idx[(int64_t)fl * n + perm_index(ke, (uint32_t)n_tr, (uint32_t)(lo + p))];
+    rows_out[p] = train_idx[(int64_t)fl * n + row_index(sp, step < 0 ? ROWS_HELD : ROWS_EPOCH, ke, (uint32_t)(lo + p))];
   if (blockIdx.x == 0 && threadIdx.x == 0) *n_rows_out = mb;
 }
 
@@ -708,9 +725,12 @@ int check_hparams(const bbo_mlp_hparams* hp, int B) {
     if (h.solver != BBO_ADAM && h.solver != BBO_SGD) return fail(BBO_INVALID_ARG, "unknown solver");
     if (h.epochs < 0) return fail(BBO_INVALID_ARG, "epochs < 0");
     if (std::isnan(h.lr) || std::isnan(h.alpha) || std::isnan(h.momentum) || std::isnan(h.beta1) ||
-        std::isnan(h.beta2) || std::isnan(h.eps) || std::isnan(h.power_t) || std::isnan(h.tol))
+        std::isnan(h.beta2) || std::isnan(h.eps) || std::isnan(h.power_t) || std::isnan(h.tol) ||
+        std::isnan(h.validation_fraction))
       return fail(BBO_INVALID_ARG, "NaN hyper-parameter");
     if (h.n_iter_no_change < 0) return fail(BBO_INVALID_ARG, "n_iter_no_change < 0");
+    if (h.validation_fraction < 0.f || h.validation_fraction >= 1.f)
+      return fail(BBO_INVALID_ARG, "validation_fraction outside [0, 1)");
   }
   return BBO_OK;
 }
@@ -805,7 +825,8 @@ int ensure_dynamic_lds(const void* fn, uint32_t bytes) {
 }
 
 // The fastest kernel that takes a model of these layer sizes on a data set of n rows.
-int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
+// `cut`: the model sets rows aside for early stopping, which the LDS-tiled and the generic kernel know how to do.
+int kernel_class(const int32_t* dims, int L, int64_t n, int dtype, bool cut) {
   const int d = dims[0];
   // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
   if (dtype == BBO_BF16) {
@@ -814,9 +835,9 @@ int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
       make_tlay(ty, dims, L);
       if (ty.lds_total <= TB_LDS_LIMIT) return KC_TILED;
     }
-    return n * (int64_t)d < 0x7fffffff && linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
+    return !cut && n * (int64_t)d < 0x7fffffff && linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
   }
-  if (n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
+  if (cut || n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
   if (small_eligible(dims, L)) {
     SLay sy;
     make_slay(sy, dims, n);
@@ -860,7 +881,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
     it.power_t = h.power_t;
     it.tol = h.tol;
     it.patience = h.n_iter_no_change;
-    it.pad_ = 0;
+    it.val_frac = h.validation_fraction;
     const int64_t bs = (h.batch_size <= 0 || h.batch_size > n) ? n : h.batch_size;
     it.rows_cap = rup((int)std::max<int64_t>(bs, 1), kstep);
     double fps = 0, params = 0;
@@ -869,7 +890,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
       fps += 2.0 * it.dims[l] * it.dims[l + 1] * (l == 0 ? 2 : 3);
       params += (double)it.dims[l] * it.dims[l + 1];
     }
-    const int k = kernel_class(it.dims, it.L, n, dtype);
+    const int k = kernel_class(it.dims, it.L, n, dtype, h.n_iter_no_change > 0 && h.validation_fraction > 0.f);
     if (k == KC_TILED) {
       TLay ty;
       make_tlay(ty, it.dims, it.L);
@@ -1246,10 +1267,11 @@ int bbo_mlp_minibatch_rows(const int32_t* train_idx, const int32_t* counts, int6
                            int32_t fold, int32_t epoch, int64_t step, int32_t* rows_out, int32_t* n_rows_out,
                            void* stream) {
   g_err.clear();
-  if (!train_idx || !counts || !hp || !rows_out || !n_rows_out || n < 0 || fold < -1 || epoch < 0 || step < 0)
+  if (!train_idx || !counts || !hp || !rows_out || !n_rows_out || n < 0 || fold < -1 || epoch < 0 || step < -1)
     return fail(BBO_INVALID_ARG, "bad argument");
   hipLaunchKernelGGL(k_minibatch_rows, dim3(64), dim3(256), 0, (hipStream_t)stream, train_idx, counts, n, hp->seed,
-                     fold, epoch, step, hp->batch_size, rows_out, n_rows_out);
+                     fold, epoch, step, hp->batch_size, hp->n_iter_no_change, hp->validation_fraction, rows_out,
+                     n_rows_out);
   HIP_TRY(hipGetLastError());
   return BBO_OK;
 }
@@ -1285,7 +1307,7 @@ int bbo_mlp_kernel_class(int64_t n, int32_t d, int32_t n_classes, const bbo_mlp_
   int32_t dims[MAXL + 1];
   int L;
   fill_dims(*hp, d, n_classes, dims, &L);
-  return kernel_class(dims, L, n, dtype);
+  return kernel_class(dims, L, n, dtype, hp->n_iter_no_change > 0 && hp->validation_fraction > 0.f);
 }
 
 const char* bbo_mlp_last_error(void) { return g_err.c_str(); }

@@ -57,6 +57,40 @@ __device__ inline uint32_t perm_index(uint64_t key, uint32_t n, uint32_t p) {
   return x;
 }
 
+// Early stopping on a validation fraction: the fold's ascending training list is cut by a keyed bijection of
+// its own (key = model key folded with 2): list[pi_split(p)], p < n_fit, are the rows the model is fitted on,
+// in that order; p >= n_fit are the n_hold = floor(fraction * n_train) rows (at least 1, at most n_train - 1)
+// it never trains on and whose loss the stopping rule watches.  n_hold = 0: no cut.
+struct RowSplit {
+  uint64_t ksplit;
+  int n_tr, n_fit, n_hold;
+};
+__device__ inline RowSplit row_split(uint64_t kmodel, int patience, float frac, int n_tr) {
+  RowSplit s{key_fold(kmodel, 2), n_tr, n_tr, 0};
+  if (patience > 0 && frac > 0.f && n_tr >= 2) {
+    int h = (int)floor((double)frac * (double)n_tr);
+    h = h < 1 ? 1 : h;
+    h = h > n_tr - 1 ? n_tr - 1 : h;
+    s.n_hold = h;
+    s.n_fit = n_tr - h;
+  }
+  return s;
+}
+// index into the training list of position p of the epoch whose key is ke
+__device__ inline uint32_t fit_index(const RowSplit& s, uint64_t ke, uint32_t p) {
+  const uint32_t q = perm_index(ke, (uint32_t)s.n_fit, p);
+  return s.n_hold ? perm_index(s.ksplit, (uint32_t)s.n_tr, q) : q;
+}
+// index into the training list of the i-th row set aside
+__device__ inline uint32_t held_index(const RowSplit& s, uint32_t i) {
+  return perm_index(s.ksplit, (uint32_t)s.n_tr, (uint32_t)s.n_fit + i);
+}
+// Which rows a pass works on: the positions of a training epoch, the rows set aside, or a list as it stands.
+enum RowMode { ROWS_EPOCH = 0, ROWS_HELD = 1, ROWS_PLAIN = 2 };
+__device__ inline uint32_t row_index(const RowSplit& s, int mode, uint64_t ke, uint32_t p) {
+  return mode == ROWS_EPOCH ? fit_index(s, ke, p) : (mode == ROWS_HELD ? held_index(s, p) : p);
+}
+
 // The permutation's domain for callers that walk many positions at once with a table of the
 // round function (which sees the round and one half of the position only): n >= 2.
 struct PermDomain {
@@ -78,7 +112,8 @@ struct ItemDesc {
   int32_t b, fold, L, solver, nesterov, batch_size, epochs, rows_cap;
   float lr, alpha, momentum, beta1, beta2, eps;
   float power_t, tol;
-  int32_t patience, pad_;
+  int32_t patience;
+  float val_frac;  // early stopping on held-out rows when > 0 (and patience > 0)
   int32_t dims[MAXL + 1];
   float bound[MAXL];
 };

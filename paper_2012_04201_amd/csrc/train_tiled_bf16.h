@@ -297,13 +297,13 @@ struct Tiled {
 
   // ---- staging --------------------------------------------------------------
   // Row list of the chunk and the gathered input rows (with their pad columns) into the buffer.
-  __device__ __forceinline__ void stage_rows(const int32_t* list, uint64_t key, int n_list, int lo, int rows,
-                                             bool permute) const {
+  __device__ __forceinline__ void stage_rows(const int32_t* list, const RowSplit& sp, int mode, uint64_t key, int lo,
+                                             int rows) const {
     int32_t* rl = rowlist();
     int32_t* tg = targets();
     const int32_t* Y = (const int32_t*)P.y;  // class indices or float values: 32 bits either way
     for (int p = threadIdx.x; p < TB_ROWS; p += blockDim.x) {
-      const int row = p < rows ? list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p] : -1;
+      const int row = p < rows ? list[row_index(sp, mode, key, (uint32_t)(lo + p))] : -1;
       rl[p] = row;
       tg[p] = row >= 0 ? Y[row] : 0;  // in flight while the rows are gathered
     }
@@ -1307,9 +1307,11 @@ struct Tiled {
     const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
     const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
     const int32_t* va = P.val_idx + (int64_t)fl * P.n;
-    const int bs = eff_batch(it.batch_size, n_tr);
-    const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f);
+    const RowSplit sp = row_split(km, it.patience, it.val_frac, n_tr);
+    const int n_fit = sp.n_fit;
+    const int bs = eff_batch(it.batch_size, n_fit);
+    const int steps = n_fit > 0 ? (n_fit + bs - 1) / bs : 0;
     const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     {
@@ -1354,12 +1356,17 @@ struct Tiled {
     uint32_t bits[2][4];
     Plateau plateau;
     const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
-    for (int e = e0; e < it.epochs; e++) {
-      const uint64_t ke = key_epoch(km, e);
-      if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, e, n_tr);
+    // One loop over the epochs and, after the last one, the scoring of the held fold: the scoring pass (rows
+    // set aside for early stopping after an epoch, the fold's held rows at the end) exists once in the code.
+    bool stop = false;
+    for (int e = e0;; e++) {
+      const bool final = stop || e >= it.epochs;
       double esum = 0.0;  // the lane's share of the epoch's summed data loss
+      if (!final) {
+      const uint64_t ke = key_epoch(km, e);
+      if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, e, n_fit);
       for (int st = e == e0 ? st0 : 0; st < steps; st++, gstep++) {
-        const int lo = st * bs, mb = min(bs, n_tr - lo);
+        const int lo = st * bs, mb = min(bs, n_fit - lo);
         const int nch = (mb + TB_ROWS - 1) / TB_ROWS, par = (int)(gstep & 1);
         const float inv_mb = 1.f / (float)mb;
         oc.am = it.alpha / (float)mb;
@@ -1378,7 +1385,7 @@ struct Tiled {
           const int rows = min(TB_ROWS, mb - ch * TB_ROWS);
           const int KB = (rows + 31) / 32;
           const bool first = ch == 0, last = ch == nch - 1;
-          stage_rows(tr, ke, n_tr, lo + ch * TB_ROWS, rows, true);
+          stage_rows(tr, sp, ROWS_EPOCH, ke, lo + ch * TB_ROWS, rows);
           // a minibatch of one chunk takes the streaming weight gradient, which reads the inputs themselves
           forward_all<true>(par, rows, inv_mb, bits, lsum, hits, !(first && last));
           __syncthreads();
@@ -1398,23 +1405,33 @@ struct Tiled {
           if (threadIdx.x == 0) rec[0] = (float)(data + 0.5 * (double)it.alpha * pen / (double)mb);
         }
       }
-      if (watch && plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) break;
-    }
-
-    // validation score on the held rows
-    double lsum = 0.0, hits = 0.0;
-    for (int off = 0; off < n_va; off += TB_ROWS) {
-      const int rows = min(TB_ROWS, n_va - off);
-      stage_rows(va, 0, n_va, off, rows, false);
-      forward_all<false>((int)(gstep & 1), rows, 0.f, bits, lsum, hits);
-      __syncthreads();
-    }
-    lsum = block_sum(lsum, red);
-    hits = block_sum(hits, red);
-    if (threadIdx.x == 0) {
-      float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
-      out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
-      out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
+      }
+      float watched = 0.f;
+      if (watch && !final && !sp.n_hold) watched = (float)(block_sum(esum, red) / (double)n_fit);
+      if (final || (watch && sp.n_hold)) {
+        // loss (and second score) of a list of rows under the current weights
+        const int32_t* list = final ? va : tr;
+        const int mode = final ? ROWS_PLAIN : ROWS_HELD, count = final ? n_va : sp.n_hold;
+        double lsum = 0.0, hits = 0.0;
+        for (int off = 0; off < count; off += TB_ROWS) {
+          const int rows = min(TB_ROWS, count - off);
+          stage_rows(list, sp, mode, 0, off, rows);
+          forward_all<false>((int)(gstep & 1), rows, 0.f, bits, lsum, hits);
+          __syncthreads();
+        }
+        lsum = block_sum(lsum, red);
+        hits = block_sum(hits, red);
+        if (final) {
+          if (threadIdx.x == 0) {
+            float* out = P.item_out + 2 * ((int64_t)it.b * P.n_folds + fl);
+            out[0] = n_va > 0 ? (float)(lsum / (double)n_va) : __builtin_nanf("");
+            out[1] = n_va > 0 ? (float)(hits / (double)n_va) : __builtin_nanf("");  // accuracy | mean absolute error
+          }
+          break;
+        }
+        watched = (float)(lsum / (double)count);  // the loss of the rows set aside, under the weights the epoch ends with
+      }
+      if (watch) stop = plateau.stop_after(watched, it.tol, it.patience);
     }
   }
 };

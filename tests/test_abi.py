@@ -33,7 +33,7 @@ def test_header_symbols_are_exported(bb):
 
 
 def test_hparams_struct_layout(bb):
-    assert C.sizeof(bb.HParams) == 80
+    assert C.sizeof(bb.HParams) == 88 and bb.HParams.validation_fraction.offset == 80
     assert bb.HParams.seed.offset == 64 and bb.HParams.lr.offset == 36 and bb.HParams.power_t.offset == 60 and bb.HParams.tol.offset == 72
 
 

@@ -648,6 +648,67 @@ def test_plateau_stop_epoch_and_score(bb, oracle, n, d, c, hidden, bs, dtype):
     assert stops[0] < E and stops[2] == E  # the first rule does stop early; the switched-off rule never does
 
 
+EARLY_STOP_SHAPES = [
+    # n, d, classes, hidden, batch, dtype: one case per training kernel a suggestion of that shape would otherwise use
+    (300, 20, 3, [40], 50, 0),          # (LDS-resident fp32 shape)
+    (260, 70, 5, [33, 21], 64, 0),      # generic
+    (240, 12, 0, [], 32, 0),            # (wavefront-per-model shape)
+    (400, 64, 10, [96, 80], 128, 1),    # LDS-tiled bf16
+    (700, 128, 10, [200], 300, 1),      # LDS-tiled bf16, minibatches of two chunks of rows
+]
+
+
+@pytest.mark.parametrize("n,d,c,hidden,bs,dtype", EARLY_STOP_SHAPES)
+def test_early_stopping_on_a_validation_fraction(bb, oracle, n, d, c, hidden, bs, dtype):
+    """validation_fraction > 0: the rows set aside and every minibatch are bit-identical to the oracle's, the
+    per-step arithmetic on the remaining rows matches, training ends at the epoch the held rows' loss says,
+    and the fold score agrees."""
+    cfg = small_problem(1700 + d, n, d, c, bf16=bool(dtype))
+    X, y, ft = bb.to_device(cfg)
+    f, frac, E = 1, 0.15, 40
+    base = {"hidden": hidden, "solver": "adam", "batch_size": bs, "alpha": 0.001, "lr": 0.01, "epochs": E, "seed": 61,
+            "validation_fraction": frac}
+    hp0 = dict(base, tol=1e-2, n_iter_no_change=2)
+    # integers first: held rows and minibatches
+    tr, va, cnt = bb.bbo_mlp_fold_lists(ft, 5)
+    held = bb.bbo_mlp_minibatch_rows(tr, cnt, n, hp0, f, 0, -1).cpu().numpy()
+    want_held = oracle.early_stop_rows(cfg["fold_idx"], hp0, f)
+    assert np.array_equal(held, want_held) and len(held) == int(np.floor(np.float32(frac) * int((cfg["fold_idx"] != f).sum())))
+    n_fit = int((cfg["fold_idx"] != f).sum()) - len(held)
+    spe = -(-n_fit // bs)
+    for epoch, step in [(0, 0), (3, spe - 1)]:
+        got = bb.bbo_mlp_minibatch_rows(tr, cnt, n, hp0, f, epoch, step).cpu().numpy()
+        assert np.array_equal(got, oracle.minibatch_rows(cfg["fold_idx"], hp0, f, epoch, step)), (epoch, step)
+    assert bb.bbo_mlp_kernel_class(n, d, c, hp0, dtype) in (bb.KERNEL_TILED, bb.KERNEL_GENERIC)
+    tol = REL_BF16 if dtype else REL_F32
+    c_out = c if c >= 2 else 1
+    stops = []
+    for tol_, k in [(3e-2, 1), (1e-2, 3), (0.0, 0)]:
+        hp = dict(base, tol=tol_, n_iter_no_change=k)
+        spe_k = spe if k else -(-int((cfg["fold_idx"] != f).sum()) // bs)  # the rule switched off: nothing set aside
+        scores, status, pf, tr_ = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], dtype, want_per_fold=True,
+                                                     trace=(0, f, 0, E * spe_k))
+        torch.cuda.synchronize()
+        ls = tr_["loss"].cpu().numpy()
+        done = int(np.isfinite(ls).sum())
+        ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=E * spe_k)
+        ref_done = int(np.isfinite(ref["loss"]).sum())
+        assert done % spe_k == 0 and ref_done % spe_k == 0
+        # the first two steps (before rounding differences can grow): same rows, same arithmetic
+        g, th = tr_["grad"].cpu().numpy(), tr_["theta_after"].cpu().numpy()
+        for t in range(2):
+            for name, sl in layer_slices(d, hidden, c_out):
+                assert relerr(g[t, sl], ref["grad"][t, sl]) < tol, (t, name, "grad")
+                assert relerr(th[t, sl], ref["theta_after"][t, sl]) < tol, (t, name, "theta")
+        # as for the plateau rule: a held loss within rounding of the threshold may be judged differently
+        assert abs(done - ref_done) <= (k + 1) * spe_k, (tol_, k, done // spe_k, ref_done // spe_k)
+        if done == ref_done:
+            check_fold_score(oracle, cfg, c, hp, f, dtype, pf[0, f, 0].item(), ref["scores"][0],
+                             "early stop %s" % ((n, d, hidden, dtype, tol_, k),))
+        stops.append(done // spe_k)
+    assert stops[0] < E and stops[2] == E
+
+
 # ----------------------------------------------------------- final scores ----
 
 def explained_flips(acc_gpu, acc_ref, n_va):

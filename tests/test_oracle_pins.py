@@ -598,3 +598,126 @@ def test_plateau_stop_ends_training_at_the_epoch_the_rule_gives(oracle):
     # n_iter_no_change = 0 switches the rule off whatever tol is
     off = oracle.train_one(X, y, 3, fold, dict(base, tol=10.0), f)
     np.testing.assert_array_equal(off["theta"], free["theta"])
+
+
+# ------------------------------------------ validation-fraction early stopping ----
+
+def py_mix64(z):
+    z &= M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+    return z ^ (z >> 31)
+
+
+def py_fold(h, v):
+    return py_mix64((h + (v + 1) * G) & M64)
+
+
+def py_perm(key, n, p):
+    """The keyed bijection of [0, n) written out in plain integers: 4-round balanced Feistel network on an
+    even number of bits, cycle-walked into range."""
+    if n <= 1:
+        return 0
+    bits = max(2, (n - 1).bit_length())
+    bits += bits & 1
+    hb = bits // 2
+    mask = (1 << hb) - 1
+    x = p
+    while True:
+        L, R = x >> hb, x & mask
+        for r in range(4):
+            L, R = R, L ^ (py_fold(key, (r << 32) | R) & mask)
+        x = (L << hb) | R
+        if x < n:
+            return x
+
+
+def test_early_stop_split_is_a_keyed_cut_of_the_training_list(oracle):
+    """The rows set aside are the tail of a keyed shuffle of the fold's training list, n_hold = floor(fraction x
+    n_train) clamped to [1, n_train - 1]; every epoch's minibatches cover exactly the remaining rows once.
+    The shuffle is recomputed here in plain Python integers from the SplitMix64 mixer."""
+    fold = inputs.make_folds(103, 5, 4)
+    for frac, bs, seed, f in [(0.1, 16, 5, 0), (0.25, 0, 77, 3), (0.001, 7, 9, 1), (0.9999, 5, 3, 2), (0.5, 200, 1, 4)]:
+        hp = {"hidden": [3], "batch_size": bs, "seed": seed, "n_iter_no_change": 2, "validation_fraction": frac}
+        tr, _ = oracle.fold_lists(fold, f)
+        n_tr = len(tr)
+        n_hold = min(max(int(np.floor(float(np.float32(frac)) * n_tr)), 1), n_tr - 1)
+        n_fit = n_tr - n_hold
+        kmodel = py_fold(py_fold(seed, 0x4D4C50), f)
+        ksplit = py_fold(kmodel, 2)
+        held = [tr[py_perm(ksplit, n_tr, n_fit + i)] for i in range(n_hold)]
+        assert oracle.early_stop_rows(fold, hp, f).tolist() == held
+        fit = sorted(set(tr.tolist()) - set(held))
+        assert len(fit) == n_fit
+        eb = bs if 0 < bs <= n_fit else n_fit
+        for epoch in (0, 3):
+            kep = py_fold(py_fold(kmodel, 1), epoch)
+            seen = []
+            for s in range(-(-n_fit // eb)):
+                rows = oracle.minibatch_rows(fold, hp, f, epoch, s).tolist()
+                want = [tr[py_perm(ksplit, n_tr, py_perm(kep, n_fit, p))] for p in range(s * eb, min((s + 1) * eb, n_fit))]
+                assert rows == want
+                seen += rows
+            assert sorted(seen) == fit
+    # switched off (no patience, or no fraction): nothing is set aside, the order is the plain one
+    for off in ({"n_iter_no_change": 0, "validation_fraction": 0.3}, {"n_iter_no_change": 3, "validation_fraction": 0.0}):
+        hp = dict({"hidden": [3], "batch_size": 16, "seed": 5}, **off)
+        assert len(oracle.early_stop_rows(fold, hp, 0)) == 0
+        assert oracle.minibatch_rows(fold, hp, 0, 1, 2).tolist() == oracle.minibatch_rows(fold, {"hidden": [3], "batch_size": 16, "seed": 5}, 0, 1, 2).tolist()
+
+
+@pytest.mark.parametrize("n_classes", [3, 0])
+def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
+    """Validation-fraction early stopping against the same training written with library autograd: plain SGD
+    on the rows that are not set aside, the held rows' loss (cross-entropy / plain mean squared error)
+    after every epoch, the stall rule in single precision; stop epoch, final parameters and score."""
+    X, y = tiny_problem(21 + n_classes, n=90, d=5, n_classes=n_classes)
+    fold = inputs.make_folds(90, 5, 6)
+    f, E, frac = 2, 40, 0.2
+    dims = [5, 7, n_classes if n_classes else 1]
+    base = {"hidden": [7], "solver": "sgd", "nesterov": False, "momentum": 0.0, "lr": 0.08, "alpha": 0.01,
+            "batch_size": 16, "epochs": E, "seed": 14, "validation_fraction": frac}
+    tr, va = oracle.fold_lists(fold, f)
+    n_tr = len(tr)
+    n_hold = int(np.floor(float(np.float32(frac)) * n_tr))
+    n_fit = n_tr - n_hold
+    kmodel = py_fold(py_fold(14, 0x4D4C50), f)
+    ksplit = py_fold(kmodel, 2)
+    held = np.array([tr[py_perm(ksplit, n_tr, n_fit + i)] for i in range(n_hold)])
+    Xt = torch.tensor(X, dtype=torch.float64)
+    yt = torch.tensor(y.astype(np.int64) if n_classes else y.astype(np.float64))
+    lr, alpha = float(np.float32(0.08)), float(np.float32(0.01))
+
+    def held_loss(tt):
+        return float(torch_loss(tt, dims, Xt[held], yt[held], n_classes, 0.0)) * (1.0 if n_classes else 2.0)
+
+    stops = []
+    for tol, k in [(1e-3, 2), (2e-2, 1), (0.0, 4)]:
+        tt = torch.tensor(oracle.init_params(5, n_classes, base, f), dtype=torch.float64, requires_grad=True)
+        best, stalled, stop_at = np.float32(np.inf), 0, E
+        for e in range(E):
+            kep = py_fold(py_fold(kmodel, 1), e)
+            for s in range(-(-n_fit // 16)):
+                rows = [tr[py_perm(ksplit, n_tr, py_perm(kep, n_fit, p))] for p in range(s * 16, min((s + 1) * 16, n_fit))]
+                loss = torch_loss(tt, dims, Xt[rows], yt[rows], n_classes, alpha)
+                (g,) = torch.autograd.grad(loss, tt)
+                tt = (tt - lr * g).detach().requires_grad_(True)
+            le = np.float32(held_loss(tt.detach()))
+            stalled = stalled + 1 if le > np.float32(best - np.float32(tol)) else 0
+            best = min(best, le)
+            if stalled > k:
+                stop_at = e + 1
+                break
+        hp = dict(base, tol=tol, n_iter_no_change=k)
+        spe = -(-n_fit // 16)
+        got = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1, step_begin=0, step_end=E * spe)
+        assert int(np.isfinite(got["loss"]).sum()) == stop_at * spe, (tol, k, stop_at)
+        np.testing.assert_allclose(got["theta"], tt.detach().numpy(), rtol=1e-9, atol=1e-12)
+        want = float(torch_loss(tt.detach(), dims, Xt[va], yt[va], n_classes, 0.0)) * (1.0 if n_classes else 2.0)
+        assert abs(got["scores"][0] - want) < 1e-10
+        stops.append(stop_at)
+    assert min(stops) < E, stops  # the rule does end some run early
+    # the same rule on the training loss (no fraction) stops elsewhere: the held rows really are what is watched
+    other = oracle.train_one(X, y, n_classes, fold, dict(base, tol=2e-2, n_iter_no_change=1, validation_fraction=0.0), f,
+                             prec=1, step_begin=0, step_end=E * 5)
+    assert int(np.isfinite(other["loss"]).sum()) != stops[1] * spe or not np.array_equal(other["theta"], got["theta"])

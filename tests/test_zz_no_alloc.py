@@ -28,10 +28,12 @@ def both_ways(bb, cfg):
     status = torch.full((B,), -7, dtype=torch.int32, device=X.device)
     pf = torch.full((B, K, 2), -7.0, dtype=torch.float32, device=X.device)
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # torch's count of device allocations made so far: the call must not add to it (the library itself has no
+    # way to allocate through torch; this guards the binding)
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     bb.bbo_mlp_cv_eval_static(X, y, c, ft, K, hps, dt, scores=scores, status=status, per_fold=pf)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     assert torch.equal(scores, want_s) and torch.equal(status, want_st) and torch.equal(pf, want_pf)
     assert np.all(np.isfinite(scores.cpu().numpy()[status.cpu().numpy() == 0]))
     return scores
