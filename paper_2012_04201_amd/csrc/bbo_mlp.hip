@@ -825,8 +825,7 @@ int ensure_dynamic_lds(const void* fn, uint32_t bytes) {
 }
 
 // The fastest kernel that takes a model of these layer sizes on a data set of n rows.
-// `cut`: the model sets rows aside for early stopping, which the LDS-tiled and the generic kernel know how to do.
-int kernel_class(const int32_t* dims, int L, int64_t n, int dtype, bool cut) {
+int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
   const int d = dims[0];
   // the tiled kernel addresses the input matrix with 32-bit byte offsets, the fp32 kernels with 32-bit indices
   if (dtype == BBO_BF16) {
@@ -835,9 +834,9 @@ int kernel_class(const int32_t* dims, int L, int64_t n, int dtype, bool cut) {
       make_tlay(ty, dims, L);
       if (ty.lds_total <= TB_LDS_LIMIT) return KC_TILED;
     }
-    return !cut && n * (int64_t)d < 0x7fffffff && linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
+    return n * (int64_t)d < 0x7fffffff && linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
   }
-  if (cut || n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
+  if (n * (int64_t)d >= 0x7fffffff) return KC_GENERIC;
   if (small_eligible(dims, L)) {
     SLay sy;
     make_slay(sy, dims, n);
@@ -890,7 +889,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
       fps += 2.0 * it.dims[l] * it.dims[l + 1] * (l == 0 ? 2 : 3);
       params += (double)it.dims[l] * it.dims[l + 1];
     }
-    const int k = kernel_class(it.dims, it.L, n, dtype, h.n_iter_no_change > 0 && h.validation_fraction > 0.f);
+    const int k = kernel_class(it.dims, it.L, n, dtype);
     if (k == KC_TILED) {
       TLay ty;
       make_tlay(ty, it.dims, it.L);
@@ -1307,7 +1306,7 @@ int bbo_mlp_kernel_class(int64_t n, int32_t d, int32_t n_classes, const bbo_mlp_
   int32_t dims[MAXL + 1];
   int L;
   fill_dims(*hp, d, n_classes, dims, &L);
-  return kernel_class(dims, L, n, dtype, hp->n_iter_no_change > 0 && hp->validation_fraction > 0.f);
+  return kernel_class(dims, L, n, dtype);
 }
 
 const char* bbo_mlp_last_error(void) { return g_err.c_str(); }

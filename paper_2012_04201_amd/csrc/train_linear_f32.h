@@ -157,7 +157,10 @@ struct Linear {
   }
 
   // ep[p] = row visited at position p of the epoch with key ke
-  __device__ __forceinline__ void epoch_order(uint64_t ke, const int32_t* tr, int n_tr) const {
+  // (n_tr = rows the model is fitted on; with an early-stopping cut their positions in the training list go
+  // through the cut's own bijection)
+  __device__ __forceinline__ void epoch_order(uint64_t ke, const int32_t* tr, const RowSplit& sp) const {
+    const int n_tr = sp.n_fit;
     if (n_tr <= 1) {
       if (lane < n_tr) ep[lane] = 0;
     } else {
@@ -193,7 +196,8 @@ struct Linear {
 #pragma unroll
       for (int u = 0; u < 8; u++) {
         const int q = p0 + 64 * u + lane;
-        v[u] = tr[q < n_tr ? ep[q] : 0];
+        const int at = q < n_tr ? ep[q] : 0;
+        v[u] = tr[sp.n_hold ? (int)perm_index(sp.ksplit, (uint32_t)sp.n_tr, (uint32_t)at) : at];
       }
 #pragma unroll
       for (int u = 0; u < 8; u++) {
@@ -204,9 +208,9 @@ struct Linear {
     ln_lds_fence();
   }
   // the lane's row of the chunk of `left` rows that starts at position `pos` of the epoch
-  __device__ __forceinline__ int chunk_row(uint64_t ke, const int32_t* tr, int n_tr, int pos, int left) const {
+  __device__ __forceinline__ int chunk_row(uint64_t ke, const int32_t* tr, const RowSplit& sp, int pos, int left) const {
     if (lane >= min(64, left)) return -1;
-    return ep ? ep[pos + lane] : tr[perm_index(ke, (uint32_t)n_tr, (uint32_t)(pos + lane))];
+    return ep ? ep[pos + lane] : tr[fit_index(sp, ke, (uint32_t)(pos + lane))];
   }
 
   // the label (class id or target, as stored) of a row, 0 for no row
@@ -280,16 +284,39 @@ struct Linear {
     }
   }
 
+  // Loss and second score, summed per lane, of `count` rows of a list (taken as it stands, or the rows of the
+  // training list that the early-stopping cut sets aside) under the current weights.
+  __device__ __forceinline__ void score_rows(const int32_t* list, const RowSplit& sp, int mode, int count, double& lsum,
+                                             double& hits) const {
+    auto row_at = [&](int p) { return p < count ? list[row_index(sp, mode, 0, (uint32_t)p)] : -1; };
+    int vrow = row_at(lane);
+    uint32_t vlab = label(vrow);
+    for (int off = 0; off < count; off += 64) {
+      const int mbc = min(64, count - off);
+      const int row = vrow;
+      const uint32_t lab = vlab;
+      vrow = row_at(off + 64 + lane);
+      stage(row, mbc);
+      float z[CO];
+      forward(z);
+      outputs<false>(z, row, lab, 0.f, lsum, hits);
+      ln_lds_fence();
+      vlab = label(vrow);
+    }
+  }
+
   __device__ void run(const ItemDesc& it) const {
     const int f = it.fold, fl = f - P.fold_base;
     const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
     const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
     const int32_t* va = P.val_idx + (int64_t)fl * P.n;
-    const int bs = eff_batch(it.batch_size, n_tr);
-    const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
+    const uint64_t km = key_model(it.seed, f);
+    const RowSplit sp = row_split(km, it.patience, it.val_frac, n_tr);
+    const int n_fit = sp.n_fit;
+    const int bs = eff_batch(it.batch_size, n_fit);
+    const int steps = n_fit > 0 ? (n_fit + bs - 1) / bs : 0;
     const int epochs = it.epochs, patience = it.patience;
     const float lr0 = it.lr, alpha = it.alpha, power_t = it.power_t, tol = it.tol, beta1 = it.beta1, beta2 = it.beta2;
-    const uint64_t km = key_model(it.seed, f);
     const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     OptC oc;
@@ -362,19 +389,19 @@ struct Linear {
     const bool watch = patience > 0 && steps > 0 && !resume;
     for (int e = e0; e < epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
-      if (!oc.adam) oc.lr = epoch_lr(lr0, power_t, e, n_tr);
+      if (!oc.adam) oc.lr = epoch_lr(lr0, power_t, e, n_fit);
       double esum = 0.0;  // the lane's share of the epoch's summed data loss
       // The lane's row of a chunk and its label are fetched one chunk ahead within the epoch.
       const int st_first = e == e0 ? st0 : 0;
       int nrow = -1;
       if (st_first < steps) {
-        if (ep) epoch_order(ke, tr, n_tr);
+        if (ep) epoch_order(ke, tr, sp);
         const int lo = st_first * bs;
-        nrow = chunk_row(ke, tr, n_tr, lo, min(bs, n_tr - lo));
+        nrow = chunk_row(ke, tr, sp, lo, min(bs, n_fit - lo));
       }
       uint32_t nlab = label(nrow);
       for (int st = st_first; st < steps; st++, gstep++) {
-        const int lo = st * bs, mb = min(bs, n_tr - lo);
+        const int lo = st * bs, mb = min(bs, n_fit - lo);
         const float inv_mb = 1.f / (float)mb;
         float g[KI][CO];
 #pragma unroll
@@ -390,8 +417,8 @@ struct Linear {
           {  // the next chunk of the epoch: the rest of this step, else the start of the next one
             const bool same = c0 + 64 < mb;
             const int nlo = same ? lo + c0 + 64 : lo + mb;
-            const int nleft = same ? mb - c0 - 64 : (st + 1 < steps ? min(bs, n_tr - nlo) : 0);
-            nrow = chunk_row(ke, tr, n_tr, nlo, nleft);
+            const int nleft = same ? mb - c0 - 64 : (st + 1 < steps ? min(bs, n_fit - nlo) : 0);
+            nrow = chunk_row(ke, tr, sp, nlo, nleft);
           }
           stage(row, mbc);
           float z[CO];
@@ -460,25 +487,20 @@ struct Linear {
         }
         ln_lds_fence();
       }
-      if (watch && plateau.stop_after((float)(wave_sum(esum) / (double)n_tr), tol, patience)) break;
+      if (watch) {
+        float watched = (float)(wave_sum(esum) / (double)n_fit);
+        if (sp.n_hold) {  // the loss of the rows set aside for early stopping, under the weights the epoch ends with
+          double hl = 0.0, hh = 0.0;
+          score_rows(tr, sp, ROWS_HELD, sp.n_hold, hl, hh);
+          watched = (float)(wave_sum(hl) / (double)sp.n_hold);
+        }
+        if (plateau.stop_after(watched, tol, patience)) break;
+      }
     }
 
     // validation score on the held rows
     double lsum = 0.0, hits = 0.0;
-    int vrow = lane < n_va ? va[lane] : -1;
-    uint32_t vlab = label(vrow);
-    for (int off = 0; off < n_va; off += 64) {
-      const int mbc = min(64, n_va - off);
-      const int row = vrow;
-      const uint32_t lab = vlab;
-      vrow = off + 64 + lane < n_va ? va[off + 64 + lane] : -1;
-      stage(row, mbc);
-      float z[CO];
-      forward(z);
-      outputs<false>(z, row, lab, 0.f, lsum, hits);
-      ln_lds_fence();
-      vlab = label(vrow);
-    }
+    score_rows(va, sp, ROWS_PLAIN, n_va, lsum, hits);
     lsum = wave_sum(lsum);
     hits = wave_sum(hits);
     if (lane == 0) {

@@ -176,16 +176,17 @@ struct Small {
 
   // ---- input staging, one chunk ahead ---------------------------------------
   // (1) row ids of a chunk: the load is issued here, the value parked in LDS later
-  __device__ __forceinline__ int fetch_row_id(const int32_t* list, uint64_t key, int n_list, int lo, int rows, bool permute) const {
+  __device__ __forceinline__ int fetch_row_id(const int32_t* list, const RowSplit& sp, int mode, uint64_t key, int lo,
+                                              int rows) const {
     const int p = threadIdx.x;
     if (p >= SM_RC || p >= rows) return -1;
-    if (permute && y.epoch_cap) return ((const int32_t*)(lds + y.o_epoch))[lo + p];
-    return list[permute ? perm_index(key, (uint32_t)n_list, (uint32_t)(lo + p)) : lo + p];
+    if (mode == ROWS_EPOCH && y.epoch_cap) return ((const int32_t*)(lds + y.o_epoch))[lo + p];
+    return list[row_index(sp, mode, key, (uint32_t)(lo + p))];
   }
   // Row ids of a whole epoch, in minibatch order, into the LDS table.
-  __device__ __forceinline__ void build_epoch_table(const int32_t* list, uint64_t key, int n_list) const {
+  __device__ __forceinline__ void build_epoch_table(const int32_t* list, const RowSplit& sp, uint64_t key) const {
     int32_t* tab = (int32_t*)(lds + y.o_epoch);
-    for (int p = threadIdx.x; p < n_list; p += blockDim.x) tab[p] = list[perm_index(key, (uint32_t)n_list, (uint32_t)p)];
+    for (int p = threadIdx.x; p < sp.n_fit; p += blockDim.x) tab[p] = list[fit_index(sp, key, (uint32_t)p)];
   }
   __device__ __forceinline__ void park_row_id(int par, int row) const {
     if ((int)threadIdx.x < SM_RC) rowlist(par)[threadIdx.x] = row;
@@ -645,9 +646,11 @@ struct Small {
     const int n_tr = P.counts[2 * fl], n_va = P.counts[2 * fl + 1];
     const int32_t* tr = P.train_idx + (int64_t)fl * P.n;
     const int32_t* va = P.val_idx + (int64_t)fl * P.n;
-    const int bs = eff_batch(it.batch_size, n_tr);
-    const int steps = n_tr > 0 ? (n_tr + bs - 1) / bs : 0;
     const uint64_t km = key_model(it.seed, f_);
+    const RowSplit sp = row_split(km, it.patience, it.val_frac, n_tr);
+    const int n_fit = sp.n_fit;
+    const int bs = eff_batch(it.batch_size, n_fit);
+    const int steps = n_fit > 0 ? (n_fit + bs - 1) / bs : 0;
     const bool traced = P.trace_item == it.b * P.n_folds + fl;
 
     // zero the weights and output-layer moments (pads must be zero), then the initial or given parameters
@@ -694,9 +697,9 @@ struct Small {
     // ---- training: the chunks of all steps of all epochs, inputs fetched one chunk ahead ----
     int epochs_lim = it.epochs;  // lowered when the plateau rule ends training
     auto chunk_valid = [&](const ChunkPos& p) { return steps > 0 && p.e < epochs_lim; };
-    auto chunk_rows = [&](const ChunkPos& p) { return min(SM_RC, min(bs, n_tr - p.st * bs) - p.c0); };
+    auto chunk_rows = [&](const ChunkPos& p) { return min(SM_RC, min(bs, n_fit - p.st * bs) - p.c0); };
     auto chunk_next = [&](ChunkPos p) {
-      const int mb = min(bs, n_tr - p.st * bs);
+      const int mb = min(bs, n_fit - p.st * bs);
       p.c0 += SM_RC;
       if (p.c0 >= mb) {
         p.c0 = 0;
@@ -708,13 +711,13 @@ struct Small {
       return p;
     };
     auto chunk_row_id = [&](const ChunkPos& p) {
-      return fetch_row_id(tr, key_epoch(km, p.e), n_tr, p.st * bs + p.c0, chunk_rows(p), true);
+      return fetch_row_id(tr, sp, ROWS_EPOCH, key_epoch(km, p.e), p.st * bs + p.c0, chunk_rows(p));
     };
     float xr[NX], yv = 0.f;
     int par = 0;
     if (chunk_valid(pos)) {
       if (y.epoch_cap) {
-        build_epoch_table(tr, key_epoch(km, pos.e), n_tr);
+        build_epoch_table(tr, sp, key_epoch(km, pos.e));
         __syncthreads();
       }
       park_row_id(0, chunk_row_id(pos));
@@ -727,12 +730,28 @@ struct Small {
     float* rec = nullptr;
     Plateau plateau;
     const bool watch = it.patience > 0 && !resume;
+    // Loss and second score (the thread's share) of `count` rows of a list under the current weights; uses
+    // the input tiles of parity 0 and the forward accumulators.
+    auto score_rows = [&](const int32_t* list, int mode, int count, double& ls, double& hs) {
+      for (int off = 0; off < count; off += SM_RC) {
+        const int rows = min(SM_RC, count - off);
+        park_row_id(0, fetch_row_id(list, sp, mode, 0, off, rows));
+        __syncthreads();
+        fetch_inputs(0, xr, yv);
+        commit_inputs(0, xr, yv);
+        __syncthreads();
+        forward((rows + 15) / 16, acc);
+        __syncthreads();
+        outputs<false>(0, rows, 0.f, ls, hs, gb2);
+        __syncthreads();
+      }
+    };
     while (chunk_valid(pos)) {
-      const int mb = min(bs, n_tr - pos.st * bs);
+      const int mb = min(bs, n_fit - pos.st * bs);
       const int rows = chunk_rows(pos), nrt = (rows + 15) / 16;
       if (pos.c0 == 0) {  // first chunk of a step
         oc.am = it.alpha / (float)mb;
-        if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, pos.e, n_tr);
+        if (!oc.adam) oc.lr = epoch_lr(it.lr, it.power_t, pos.e, n_fit);
         if (oc.adam) {
           b1t *= (double)it.beta1;
           b2t *= (double)it.beta2;
@@ -759,7 +778,7 @@ struct Small {
       const bool more = chunk_valid(nxt);
       if (more && nxt.e != pos.e && y.epoch_cap) {
         // the next chunk opens an epoch: its row order replaces the table (this epoch's last rows are already read)
-        build_epoch_table(tr, key_epoch(km, nxt.e), n_tr);
+        build_epoch_table(tr, sp, key_epoch(km, nxt.e));
         __syncthreads();
       }
       int nrow = -1;
@@ -781,7 +800,23 @@ struct Small {
         gstep++;
         esum += lsum;
         if (watch && nxt.e != pos.e) {  // that was the last step of the epoch
-          if (plateau.stop_after((float)(block_sum(esum, red) / (double)n_tr), it.tol, it.patience)) epochs_lim = pos.e + 1;
+          float watched;
+          if (sp.n_hold) {
+            // the loss of the rows set aside for early stopping, under the weights the epoch ends with; the
+            // pass takes over the input tiles, so the next chunk's rows and inputs are fetched again after it
+            __syncthreads();  // the update, by every wave
+            double hl = 0.0, hh = 0.0;
+            score_rows(tr, ROWS_HELD, sp.n_hold, hl, hh);
+            watched = (float)(block_sum(hl, red) / (double)sp.n_hold);
+            if (more) {
+              park_row_id(par ^ 1, chunk_row_id(nxt));
+              __syncthreads();
+              fetch_inputs(par ^ 1, xr, yv);
+            }
+          } else {
+            watched = (float)(block_sum(esum, red) / (double)n_fit);
+          }
+          if (plateau.stop_after(watched, it.tol, it.patience)) epochs_lim = pos.e + 1;
           esum = 0.0;
         }
       }
@@ -793,18 +828,7 @@ struct Small {
     // ---- validation score on the held rows ----
     lsum = 0.0;
     hits = 0.0;
-    for (int off = 0; off < n_va; off += SM_RC) {
-      const int rows = min(SM_RC, n_va - off);
-      park_row_id(0, fetch_row_id(va, 0, n_va, off, rows, false));
-      __syncthreads();
-      fetch_inputs(0, xr, yv);
-      commit_inputs(0, xr, yv);
-      __syncthreads();
-      forward((rows + 15) / 16, acc);
-      __syncthreads();
-      outputs<false>(0, rows, 0.f, lsum, hits, gb2);
-      __syncthreads();
-    }
+    score_rows(va, ROWS_PLAIN, n_va, lsum, hits);
     lsum = block_sum(lsum, red);
     hits = block_sum(hits, red);
     if (threadIdx.x == 0) {
