@@ -25,7 +25,8 @@ PEAK_VALU_TFLOPS = 157.3  # fp32 vector: 256 CUs x 128 lanes x 2 flop (multiply-
 PEAK_HBM_GBS = 8000.0
 # the sources each workload's training kernel is built from (the host code in bbo_mlp.hip does not count)
 KERNEL_SOURCES = {"k_train_tiled": ["common.h", "train_tiled_bf16.h"], "k_train_small": ["common.h", "train_small_f32.h"],
-                  "k_train_linear": ["common.h", "train_linear_f32.h"], "k_train": ["common.h", "bbo_mlp.hip"]}
+                  "k_train_linear": ["common.h", "train_linear_f32.h"], "k_train": ["common.h", "bbo_mlp.hip"],
+                  "k_train_mid": ["common.h", "train_mid_f32.h"]}
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
@@ -146,7 +147,7 @@ def run_workload(idx, steps, warmup, suggestions=0, epochs=0, linear=False):
     kern_s = sum(a.elapsed_time(b) for a, b in ev) / len(ev) / 1e3
     per_step = wall / steps
     dname = "bf16" if dt else "f32"
-    kernel = "k_train_tiled" if dt else ("k_train_linear" if linear else ("k_train_small" if idx in (0, 2, 3) else "k_train"))
+    kernel = "k_train_tiled" if dt else ("k_train_linear" if linear else ("k_train_small" if idx in (0, 2, 3) else "k_train_mid"))
     tflops = flops / per_step / 1e12
     abytes = algorithmic_bytes(cfg)
     traffic = measured_traffic(cfg["name"], kernel)

@@ -241,7 +241,8 @@ int64_t bbo_mlp_param_count(int32_t d, int32_t n_classes, const bbo_mlp_hparams*
  * Which training kernel suggestion hp[0] runs on for a data set of n rows (host
  * logic only, no device call): 0 the LDS-tiled bf16 kernel, 1 the LDS-resident
  * fp32 kernel, 2 the wavefront-per-model kernel (no hidden layer), 3 the
- * generic kernel; negative on invalid input.  Every suggestion of a call gets
+ * generic kernel, 4 the wider LDS-resident fp32 kernel (one hidden layer, up to
+ * 127 inputs and 16 outputs); negative on invalid input.  Every suggestion of a call gets
  * the kernel this returns for it, whatever else the call holds (Algorithm 1's
  * evaluate(params_list) treats the suggestions independently).
  */

@@ -150,7 +150,7 @@ def bbo_mlp_param_count(d, n_classes, hp):
     return int(lib().bbo_mlp_param_count(C.c_int32(d), C.c_int32(n_classes), h))
 
 
-KERNEL_TILED, KERNEL_SMALL, KERNEL_LINEAR, KERNEL_GENERIC = range(4)
+KERNEL_TILED, KERNEL_SMALL, KERNEL_LINEAR, KERNEL_GENERIC, KERNEL_MID = range(5)
 
 
 def bbo_mlp_kernel_class(n, d, n_classes, hp, dtype=F32):

@@ -48,6 +48,7 @@
 #include "common.h"
 #include "train_tiled_bf16.h"
 #include "train_small_f32.h"
+#include "train_mid_f32.h"
 #include "train_linear_f32.h"
 
 static_assert(sizeof(bbo_mlp_hparams) == 88, "the hyper-parameter record is part of the ABI");
@@ -187,7 +188,7 @@ __device__ inline float row_loss(const float* z, int c, int n_classes, const voi
 
 // The training kernels.  Every suggestion of a call goes to the fastest kernel that takes its shape, so
 // a suggestion's scores do not depend on which other suggestions share its call.
-enum { KC_TILED = 0, KC_SMALL = 1, KC_LINEAR = 2, KC_GENERIC = 3, KC_N = 4 };
+enum { KC_TILED = 0, KC_SMALL = 1, KC_LINEAR = 2, KC_GENERIC = 3, KC_MID = 4, KC_N = 5 };
 
 // ---------------------------------------------------------------------------
 // Fold lists (ascending), one workgroup per list; also resets the work queues.
@@ -840,7 +841,12 @@ int kernel_class(const int32_t* dims, int L, int64_t n, int dtype) {
   if (small_eligible(dims, L)) {
     SLay sy;
     make_slay(sy, dims, n);
-    return sy.lds_total <= SM_LDS_LIMIT ? KC_SMALL : KC_GENERIC;
+    if (sy.lds_total <= SM_LDS_LIMIT) return KC_SMALL;
+  }
+  if (mid_eligible(dims, L)) {
+    MLay my;
+    make_mlay(my, dims, n);
+    if (my.lds_total <= MD_LDS_LIMIT) return KC_MID;
   }
   return linear_eligible(dims, L) ? KC_LINEAR : KC_GENERIC;
 }
@@ -859,6 +865,7 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
   pl.sub[KC_SMALL].item_bytes = sizeof(SItem);
   pl.sub[KC_LINEAR].item_bytes = sizeof(ItemDesc);
   pl.sub[KC_GENERIC].item_bytes = sizeof(ItemDesc);
+  pl.sub[KC_MID].item_bytes = sizeof(MItem);
   pl.sub[KC_SMALL].slot_bytes = 256;
   for (int b = 0; b < B; b++) {
     const bbo_mlp_hparams& h = hp[b];
@@ -900,6 +907,11 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
       make_slay(sy, it.dims, n);  // only the hidden layer's moments live in global memory
       pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, 2ull * sy.HP * sy.ldw * 4);
       pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, sy.lds_total);
+    } else if (k == KC_MID) {
+      MLay my;
+      make_mlay(my, it.dims, n);  // the moments of both layers live in global memory
+      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, my.g_total);
+      pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, my.lds_total);
     } else if (k == KC_GENERIC) {
       Layout y;
       make_layout(y, it.dims, it.L, it.rows_cap, kstep, opsz);
@@ -1103,6 +1115,12 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
           si.d = sp.items[i];
           make_slay(si.y, sp.items[i].dims, n);
           memcpy(at + i * sizeof(SItem), &si, sizeof(SItem));
+        } else if (k == KC_MID) {
+          MItem mi;
+          memset(&mi, 0, sizeof(mi));
+          mi.d = sp.items[i];
+          make_mlay(mi.y, sp.items[i].dims, n);
+          memcpy(at + i * sizeof(MItem), &mi, sizeof(MItem));
         } else {
           memcpy(at + i * sizeof(ItemDesc), &sp.items[i], sizeof(ItemDesc));
         }
@@ -1160,6 +1178,12 @@ int run_eval(const void* X, const void* y, int64_t n, int32_t d, int32_t n_class
       const small_fn fn = fns[kt == 1 ? 0 : (kt == 2 ? 1 : 2)][co == 1 ? 0 : (co == 2 ? 1 : 2)];
       if ((rc = ensure_dynamic_lds((const void*)fn, sp.lds_bytes))) return rc;
       hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(SM_THREADS), sp.lds_bytes, s, P);
+    } else if (k == KC_MID) {
+      typedef void (*mid_fn)(const TrainParams);
+      const int kt = md_kt(d);
+      const mid_fn fn = kt == 2 ? k_train_mid<2> : (kt == 4 ? k_train_mid<4> : (kt == 5 ? k_train_mid<5> : (kt == 6 ? k_train_mid<6> : k_train_mid<8>)));
+      if ((rc = ensure_dynamic_lds((const void*)fn, sp.lds_bytes))) return rc;
+      hipLaunchKernelGGL(fn, dim3(sp.n_slots), dim3(MD_THREADS), sp.lds_bytes, s, P);
     } else if (k == KC_LINEAR) {
       const int c_out = n_classes >= 2 ? n_classes : 1, co = ln_co(c_out), ki = ln_ki(d);
       typedef void (*linear_fn)(const TrainParams);

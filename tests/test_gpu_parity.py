@@ -365,6 +365,57 @@ def test_random_shapes_fp32_steps(bb, oracle, seed):
             assert relerr(th1[sl], rth[sl]) < REL_F32, (case, t, name, "theta")
 
 
+def random_mid_case(seed, fits):
+    """A seeded random shape for the wider LDS-resident fp32 kernel: one hidden layer, up to 127 inputs and
+    16 outputs, shapes the narrower kernel does not take (64 inputs or more, or more than 4 outputs)."""
+    r = np.random.default_rng(8500 + seed)
+    if seed % 2 == 0:
+        d, c = int(r.integers(64, 128)), int(r.choice([0, 1, 2, 3, 10, 16]))
+    else:
+        d, c = int(r.integers(1, 128)), int(r.integers(5, 17))
+    n = int(r.integers(60, 600))
+    h = int(r.integers(1, 257))
+    while not fits(n, d, c, h):  # the hidden weights must fit in LDS beside the input tile
+        h = int(r.integers(1, h))
+    bs = int(r.choice([0, 1, 5, 16, 63, 64, 65, 100, 130, 200]))
+    return n, d, c, [h], bs, str(r.choice(["adam", "sgd"])), bool(r.integers(0, 2)), float(r.choice([0.0, 0.05, 2.0]))
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_shapes_mid_kernel_steps_and_scores(bb, oracle, seed):
+    n, d, c, hidden, bs, solver, nesterov, alpha = random_mid_case(
+        seed, lambda n, d, c, h: bb.bbo_mlp_kernel_class(n, d, c, {"hidden": [h]}, 0) == bb.KERNEL_MID)
+    cfg = small_problem(950 + seed, n, d, c)
+    hp = {"hidden": hidden, "solver": solver, "nesterov": nesterov, "momentum": 0.8, "batch_size": bs, "alpha": alpha,
+          "lr": 0.005, "epochs": 3, "seed": 177 + seed}
+    case = (n, d, c, hidden, bs, solver)
+    assert bb.bbo_mlp_kernel_class(n, d, c, hp, 0) == bb.KERNEL_MID, case
+    f = seed % 5
+    n_tr = int((cfg["fold_idx"] != f).sum())
+    total = 3 * -(-n_tr // (bs if 0 < bs <= n_tr else n_tr))
+    T = min(8, total)
+    c_out = c if c >= 2 else 1
+    X, y, ft = bb.to_device(cfg)
+    scores, status, pf, tr = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], 0, want_per_fold=True, trace=(0, f, 0, min(3, total)))
+    torch.cuda.synchronize()
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, step_begin=0, step_end=min(3, total))
+    g, th, ls = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy(), tr["loss"].cpu().numpy()
+    for t in range(min(3, total)):
+        assert abs(ls[t] - ref["loss"][t]) <= 1e-5 * max(1.0, abs(ref["loss"][t])), (case, t)
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g[t, sl], ref["grad"][t, sl]) < REL_F32, (case, t, name, "grad")
+            assert relerr(th[t, sl], ref["theta_after"][t, sl]) < REL_F32, (case, t, name, "theta")
+    for t, g1, th1, rg, rth in forced_steps(bb, oracle, cfg, hp, f, 0, [t for t in (4, 7) if t < T], T):
+        for name, sl in layer_slices(d, hidden, c_out):
+            assert relerr(g1[sl], rg[sl]) < REL_F32, (case, t, name, "grad")
+            assert relerr(th1[sl], rth[sl]) < REL_F32, (case, t, name, "theta")
+    # all five folds' scores after the free run
+    rs, rst, rpf = oracle.cv_eval(cfg["X"], cfg["y"], c, cfg["fold_idx"], 5, [hp])
+    counts = compare_scores("mid kernel %s" % (case,), dict(cfg, n_folds=5), [hp], scores.cpu().numpy(), status.cpu().numpy(),
+                            pf.cpu().numpy(), rs, rst, rpf, cv_noise(oracle, cfg, [hp], 0, rpf, n_folds=5))
+    assert sum(counts.values()) == 1
+
+
 # ------------------------------------------------ single-logit binary head ----
 
 LOGIT_SHAPES = [
