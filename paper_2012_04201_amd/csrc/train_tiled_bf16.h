@@ -882,7 +882,8 @@ struct Tiled {
   // operand changes at most every Ne tiles and the next one is fetched a whole in tile early); the bias
   // tiles (ones operand) are dealt round-robin and their state is fetched before anything else.  Pad
   // elements of edge tiles keep their zeros through selects, not branches.
-  template <bool ADAM, bool FROM_X>
+  // LD: cache policy of the state LOADS (see state_load_hint()); the stores are always non-temporal.
+  template <bool ADAM, bool FROM_X, int LD>
   __device__ __forceinline__ void wgrad_stream(int l, const OptC& oc, int par_next, float* rec) const {
     const int t_ = tid(), lane = t_ & 63, li = lane & 15, q = lane >> 4;
     const int w = uniform(t_ >> 6);
@@ -995,9 +996,9 @@ struct Tiled {
         // also out of range: the lanes whose elements are all pad (their in units or their out unit)
         const uint32_t vo = lane16 + (pt >= t1 || pm * 16 + 4 * q >= fi || pn * 16 + li >= fo ? OUT_OF_RANGE : 0u);
         const int so = (pm * Nt + pn) * 1024;
-        s.w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, so, NT_HINT));
-        s.m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, so, NT_HINT));
-        if (ADAM) s.v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, so, NT_HINT));
+        s.w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, so, LD));
+        s.m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, so, LD));
+        if (ADAM) s.v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, so, LD));
         pt++;
         pn++;
         const int wrap = pn == Ne ? 1 : 0;
@@ -1113,7 +1114,7 @@ struct Tiled {
   // chunk, rows past it carry zero deltas): wave w takes in tiles w and w + 8, their state is requested before anything else, and the
   // two tile bodies are straight-line code.  The activation operand comes from the buffer, the delta from its
   // own buffer, both through the transposing read.  The bias tile goes to the wave with the fewest tiles.
-  template <bool ADAM>
+  template <bool ADAM, int LD>
   __device__ __forceinline__ void wgrad_last(const OptC& oc, int par_next, float* rec) const {
     const int l = y.L - 1;
     const int t_ = tid(), lane = t_ & 63, li = lane & 15, q = lane >> 4;
@@ -1152,9 +1153,9 @@ struct Tiled {
       const int mt = w + 8 * k;
       // out of range: tiles past the layer, and the lanes whose elements are all pad (out unit or in units)
       const uint32_t vo = lane16 + (mt < Mr && li < fo && mt * 16 + 4 * q < fi ? 0u : OUT_OF_RANGE);
-      st[k].w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, mt * 1024, NT_HINT));
-      st[k].m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, mt * 1024, NT_HINT));
-      st[k].v = ADAM ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, mt * 1024, NT_HINT)) : zero4;
+      st[k].w = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rW, vo, mt * 1024, LD));
+      st[k].m = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rM, vo, mt * 1024, LD));
+      st[k].v = ADAM ? __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rV, vo, mt * 1024, LD)) : zero4;
     }
     // bias state: out unit li (lanes of group 0 use it)
     float bw_ = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rB, (uint32_t)li * 4, 0, 0));
@@ -1227,25 +1228,45 @@ struct Tiled {
     }
   }
 
+  // Cache policy of the optimizer-state loads.  The state of all models in flight (about 200 MB) is far more
+  // than the caches hold, so it streams with the non-temporal hint, which keeps it from evicting the operand
+  // copies, spills and input rows that are re-read within a step.  But a share of the workgroups does better
+  // with ordinary loads (measured on the scale-up workload: every fourth workgroup of an XCD, 64 of 256, is the
+  // optimum, 5 % off the pass; all of them is 13 % slower than none).  The stores are non-temporal for everyone.
+  __device__ __forceinline__ static bool state_loads_cached() { return ((blockIdx.x >> 3) & 3) == 0; }
+
   __device__ __forceinline__ void wgrad(int l, int KB, bool first, bool last, const OptC& oc, int par_next,
                                         float* rec) const {
+    const bool cached = state_loads_cached();
     if (first && last && l + 1 < y.L) {
       if (l == 0) {
-        if (oc.adam)
-          wgrad_stream<true, true>(l, oc, par_next, rec);
-        else
-          wgrad_stream<false, true>(l, oc, par_next, rec);
+        if (oc.adam) {
+          if (cached)
+            wgrad_stream<true, true, 0>(l, oc, par_next, rec);
+          else
+            wgrad_stream<true, true, 2>(l, oc, par_next, rec);
+        } else {
+          wgrad_stream<false, true, 2>(l, oc, par_next, rec);
+        }
       } else {
-        if (oc.adam)
-          wgrad_stream<true, false>(l, oc, par_next, rec);
-        else
-          wgrad_stream<false, false>(l, oc, par_next, rec);
+        if (oc.adam) {
+          if (cached)
+            wgrad_stream<true, false, 0>(l, oc, par_next, rec);
+          else
+            wgrad_stream<true, false, 2>(l, oc, par_next, rec);
+        } else {
+          wgrad_stream<false, false, 2>(l, oc, par_next, rec);
+        }
       }
     } else if (first && last) {
-      if (oc.adam)
-        wgrad_last<true>(oc, par_next, rec);
-      else
-        wgrad_last<false>(oc, par_next, rec);
+      if (oc.adam) {
+        if (cached)
+          wgrad_last<true, 0>(oc, par_next, rec);
+        else
+          wgrad_last<true, 2>(oc, par_next, rec);
+      } else {
+        wgrad_last<false, 2>(oc, par_next, rec);
+      }
     } else {
       wgrad_t(l, KB, first, last, oc, par_next, rec);
     }
