@@ -11,10 +11,10 @@
 // gradient is never stored.  (Models without a hidden layer are the exception:
 // a wavefront each, on the vector ALU; see train_linear_f32.h.)
 //
-// Four training kernels share this scheme: the LDS-tiled bf16 kernel
-// (train_tiled_bf16.h), the LDS-resident fp32 kernel (train_small_f32.h), the
-// wavefront-per-model fp32 kernel (train_linear_f32.h) and the generic kernel
-// below, which takes every shape the header admits.  The planner gives each
+// Five training kernels share this scheme: the LDS-tiled bf16 kernel
+// (train_tiled_bf16.h), the two LDS-resident fp32 kernels (train_small_f32.h,
+// train_mid_f32.h), the wavefront-per-model fp32 kernel (train_linear_f32.h)
+// and the generic kernel below, which takes every shape the header admits.  The planner gives each
 // suggestion to the fastest kernel that takes its shape and launches every
 // kernel that got items, one after the other, each with its own item array
 // and queue counter.

@@ -424,6 +424,7 @@ LOGIT_SHAPES = [
     (210, 9, [130], "sgd", 0, 0),           # LDS-resident fp32, full batch, ragged row tiles
     (150, 6, [], "adam", 32, 0),            # no hidden layer
     (260, 70, [33, 21], "adam", 64, 0),     # generic fp32
+    (280, 80, [50], "adam", 70, 0),         # wider LDS-resident fp32 (64 inputs or more), two chunks per step
     (400, 64, [96, 80], "adam", 128, 1),    # LDS-tiled bf16, one chunk
     (640, 128, [200], "sgd", 300, 1),       # LDS-tiled bf16, two chunks
     (330, 36, [50, 40, 30], "adam", 77, 1), # generic bf16 (three hidden layers)
@@ -640,6 +641,7 @@ def test_linear_models_many_on_one_launch(bb, oracle):
 CONTROL_SHAPES = [
     # n, d, classes, hidden, batch, dtype: one shape per training kernel
     (300, 20, 3, [40], 50, 0),        # LDS-resident fp32
+    (330, 64, 10, [72], 48, 0),       # wider LDS-resident fp32
     (260, 70, 5, [33, 21], 64, 0),    # generic fp32
     (400, 64, 10, [96, 80], 128, 1),  # LDS-tiled bf16
 ]
@@ -703,6 +705,8 @@ EARLY_STOP_SHAPES = [
     # n, d, classes, hidden, batch, dtype, kernel: every training kernel
     (300, 20, 3, [40], 50, 0, "SMALL"),          # LDS-resident fp32, row order tabled per epoch
     (5000, 20, 2, [24], 700, 0, "SMALL"),        # LDS-resident fp32, rows permuted on the fly
+    (330, 64, 10, [72], 48, 0, "MID"),           # wider LDS-resident fp32, row order tabled per epoch
+    (5000, 70, 5, [60], 700, 0, "MID"),          # wider LDS-resident fp32, rows permuted on the fly
     (260, 70, 5, [33, 21], 64, 0, "GENERIC"),
     (240, 12, 0, [], 32, 0, "LINEAR"),           # wavefront per model, row order tabled
     (5000, 9, 3, [], 600, 0, "LINEAR"),          # wavefront per model, rows permuted on the fly
