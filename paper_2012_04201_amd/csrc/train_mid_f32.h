@@ -104,20 +104,31 @@ __host__ __device__ inline void make_mlay(MLay& y, const int32_t* dims, int64_t 
   y.g_total = g;
 }
 
-// reductions over the 16 lanes that share lane / 16
-__device__ __forceinline__ float r16_sum(float v) {
-#pragma unroll
-  for (int s = 1; s < 16; s <<= 1) v += __shfl_xor(v, s);
+// Reductions over the 16 lanes of a DPP row (the lanes that share lane / 16); every lane gets the result.
+// Rotations by 8 and 4 within the row, then the two quad permutations: four cross-lane moves, no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+template <class Op>
+__device__ __forceinline__ float r16_reduce(float v, Op op) {
+  v = op(v, __builtin_bit_cast(float, dpp_mov<0x128>(__builtin_bit_cast(int, v))));
+  v = op(v, __builtin_bit_cast(float, dpp_mov<0x124>(__builtin_bit_cast(int, v))));
+  v = op(v, __builtin_bit_cast(float, dpp_mov<0x4E>(__builtin_bit_cast(int, v))));
+  v = op(v, __builtin_bit_cast(float, dpp_mov<0xB1>(__builtin_bit_cast(int, v))));
   return v;
+}
+__device__ __forceinline__ float r16_sum(float v) {
+  return r16_reduce(v, [](float a, float b) { return a + b; });
 }
 __device__ __forceinline__ float r16_max(float v) {
-#pragma unroll
-  for (int s = 1; s < 16; s <<= 1) v = fmaxf(v, __shfl_xor(v, s));
-  return v;
+  return r16_reduce(v, [](float a, float b) { return fmaxf(a, b); });
 }
 __device__ __forceinline__ int r16_min(int v) {
-#pragma unroll
-  for (int s = 1; s < 16; s <<= 1) v = min(v, __shfl_xor(v, s));
+  v = min(v, dpp_mov<0x128>(v));
+  v = min(v, dpp_mov<0x124>(v));
+  v = min(v, dpp_mov<0x4E>(v));
+  v = min(v, dpp_mov<0xB1>(v));
   return v;
 }
 
@@ -413,6 +424,26 @@ struct Mid {
     float* v1 = g(y.g_v1);
     OptC cc = oc;
     cc.adam = ADAM;
+    // every load of a moment is issued before the first is used: one exposed L2 latency per step, not three
+    float* w2 = f(y.o_w2);
+    float* m2 = g(y.g_m2);
+    float* v2 = g(y.g_v2);
+    float m2r[2][4], v2r[2][4], mb = 0.f, vb = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int u = (w + 8 * i) * 16 + 4 * q + e;
+        m2r[i][e] = v2r[i][e] = 0.f;
+        if (w + 8 * i < nut && li < c && u < h) {
+          m2r[i][e] = m2[u * MD_CP + li];
+          if (ADAM) v2r[i][e] = v2[u * MD_CP + li];
+        }
+      }
+    if (w == 0 && q == 0 && li < c) {
+      mb = m2[y.HP * MD_CP + li];
+      if (ADAM) vb = v2[y.HP * MD_CP + li];
+    }
     // hidden layer: the lane holds gradient elements (unit j = tile*16 + li, columns k0..k0+3)
     f32x4 m1r[2][KT], v1r[2][KT];
 #pragma unroll
@@ -464,9 +495,6 @@ struct Mid {
         }
       }
     // output layer: the lane holds gradient elements (units tile*16 + 4q + e, out li)
-    float* w2 = f(y.o_w2);
-    float* m2 = g(y.g_m2);
-    float* v2 = g(y.g_v2);
 #pragma unroll
     for (int i = 0; i < 2; i++)
       if (w + 8 * i < nut && li < c) {
@@ -475,7 +503,7 @@ struct Mid {
           const int u = (w + 8 * i) * 16 + 4 * q + e;
           if (u < h) {
             const int o = u * MD_CP + li;
-            float wr = w2[o], mr = m2[o], vr = ADAM ? v2[o] : 0.f;
+            float wr = w2[o], mr = m2r[i][e], vr = v2r[i][e];
             const float gg = g2[i][e] + cc.am * wr;
             opt_update(cc, gg, wr, mr, vr);
             w2[o] = wr;
@@ -495,7 +523,7 @@ struct Mid {
       gb += __shfl_xor(gb, 32);
       if (q == 0 && li < c) {
         const int o = y.HP * MD_CP + li;
-        float wr = w2[o], mr = m2[o], vr = ADAM ? v2[o] : 0.f;
+        float wr = w2[o], mr = mb, vr = vb;
         opt_update(cc, gb, wr, mr, vr);
         w2[o] = wr;
         m2[o] = mr;
