@@ -76,7 +76,10 @@ typedef struct bbo_mlp_hparams {
                                      shuffle, are never trained on, and the rule
                                      above watches THEIR loss (cross-entropy, or the
                                      plain mean squared error) after every epoch
-                                     instead of the training loss. */
+                                     instead of the training loss.  The parameters
+                                     of the epoch with the lowest such loss are kept
+                                     aside, and when training ends (by the rule or
+                                     at `epochs`) they are the model that is scored. */
   int32_t reserved;               /* 0 */
 } bbo_mlp_hparams;
 

@@ -71,7 +71,8 @@ typedef struct oracle_hparams {
   float tol;                /* with n_iter_no_change > 0: training stops once the epoch's mean data loss */
   int32_t n_iter_no_change; /* has failed to improve on the best so far by tol more than this many epochs in a row */
   float validation_fraction; /* with n_iter_no_change > 0 and this > 0: that share of the fold's training rows is
-                                set aside, never trained on, and the rule watches ITS loss after every epoch */
+                                set aside, never trained on, and the rule watches ITS loss after every epoch;
+                                the model that is scored is the one of the epoch with the lowest such loss */
   int32_t reserved;
 } oracle_hparams;
 
@@ -505,7 +506,10 @@ static int64_t eff_batch(const oracle_hparams* hp, int64_t n_tr) {
  * at least two training rows.  The fold's ascending training list is cut by a keyed bijection of its own
  * (key = model key folded with 2): list[pi_split(p)] for p < n_fit are the rows the model is fitted on, in
  * that order; p >= n_fit are the n_hold = floor(fraction * n_train) rows (at least 1, at most n_train - 1)
- * it never trains on.  Returns n_hold (0: the rule is off). */
+ * it never trains on.  After every epoch the held rows' loss is taken; the parameters of the epoch with the
+ * lowest loss so far are kept aside, and when training ends (by the rule or by reaching `epochs`) they are
+ * the model that is scored, as scikit-learn-style early stopping hands back its best iterate.
+ * Returns n_hold (0: the rule is off). */
 static int64_t hold_count(const oracle_hparams* hp, int64_t n_tr) {
   if (hp->n_iter_no_change <= 0 || !(hp->validation_fraction > 0.0f) || n_tr < 2) return 0;
   int64_t h = (int64_t)floor((double)hp->validation_fraction * (double)n_tr);
@@ -568,12 +572,13 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
   int64_t max_rows = bs > n_va ? bs : n_va;
   if (n_hold > max_rows) max_rows = n_hold;
   scratch_t s;
-  double* theta = (double*)malloc(sizeof(double) * (size_t)P * 4);
+  double* theta = (double*)malloc(sizeof(double) * (size_t)P * 5);
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)(bs > 0 ? bs : 1));
   int32_t* held = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_hold > 0 ? n_hold : 1));
   if (!theta || !rows || !held || scratch_alloc(&s, net, max_rows)) return -2;
   for (int64_t i = 0; i < n_hold; i++) held[i] = tr[perm_index(split_key(hp->seed, fold), n_tr, n_fit + i)];
-  double *grad = theta + P, *m = theta + 2 * P, *v = theta + 3 * P;
+  double *grad = theta + P, *m = theta + 2 * P, *v = theta + 3 * P, *theta_best = theta + 4 * P;
+  int have_best = 0;
   memset(grad, 0, sizeof(double) * (size_t)P * 3);
   opt_t o = {m, v, 0};
   init_params(net, hp->seed, fold, theta);
@@ -618,10 +623,17 @@ static int train_and_score(const net_t* net, const data_t* D, const oracle_hpara
         le = (float)data_loss(net, D, held, n_hold, &s, prec, 0, 0);
       }
       stalled = le > best - hp->tol ? stalled + 1 : 0;
-      if (le < best) best = le;
+      if (le < best) {
+        best = le;
+        if (n_hold > 0) { /* the best iterate so far on the held rows */
+          memcpy(theta_best, theta, sizeof(double) * (size_t)P);
+          have_best = 1;
+        }
+      }
       if (stalled > hp->n_iter_no_change) stop = 1;
     }
   }
+  if (have_best && !done) memcpy(theta, theta_best, sizeof(double) * (size_t)P);
 
   out[0] = NAN;
   out[1] = NAN;

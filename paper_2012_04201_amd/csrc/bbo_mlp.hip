@@ -304,6 +304,37 @@ struct Trainer {
     }
   }
 
+  // Early stopping on held-out rows hands back the parameters of the best epoch: keep them aside ...
+  __device__ void keep_best() const {
+    for (int l = 0; l < y.L; l++) {
+      const float4* W = (const float4*)fp(y.w[l]);
+      float4* B = (float4*)fp(y.best[l]);
+      const int n4 = y.p16[l + 1] * y.ld[l] / 4;
+      for (int i = threadIdx.x; i < n4; i += blockDim.x) B[i] = W[i];
+    }
+    __syncthreads();
+  }
+  // ... and put them back, with their operand copies, before the held fold is scored.
+  __device__ void restore_best() const {
+    for (int l = 0; l < y.L; l++) {
+      const int fi = y.dims[l], fo = y.dims[l + 1], ld = y.ld[l];
+      float* W = fp(y.w[l]);
+      const float* B = fp(y.best[l]);
+      OpT* oi = op(y.oi[l]);
+      OpT* io = op(y.io[l]);
+      for (int i = threadIdx.x; i < fi * fo + fo; i += blockDim.x) {
+        const bool isb = i >= fi * fo;
+        const int e = isb ? i - fi * fo : i;
+        const int k = isb ? fi : e / fo, j = isb ? e : e % fo;
+        const float val = B[j * ld + k];
+        W[j * ld + k] = val;
+        if (sizeof(OpT) != 4) oi[j * ld + k] = O::cvt(val);
+        if (l >= 1 && !isb) io[k * y.kp[l + 1] + j] = O::cvt(val);
+      }
+    }
+    __syncthreads();
+  }
+
   // Rows of this step -> row list; gather X into a_0 in both layouts; set the
   // ones unit of every unit-major activation.
   __device__ void gather(const int32_t* list, const RowSplit& sp, int mode, uint64_t key, int lo, int mb, int Mrows) const {
@@ -545,6 +576,7 @@ struct Trainer {
     __syncthreads();
 
     Plateau plateau;
+    bool have_best = false;
     const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
     for (int e = e0; e < it.epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
@@ -575,9 +607,15 @@ struct Trainer {
       if (watch) {
         float watched = (float)(block_sum(esum, red) / (double)n_fit);
         if (sp.n_hold) watched = (float)(score_rows(tr, sp, ROWS_HELD, sp.n_hold, nullptr) / (double)sp.n_hold);
-        if (plateau.stop_after(watched, it.tol, it.patience)) break;
+        const bool stop = plateau.stop_after(watched, it.tol, it.patience);
+        if (sp.n_hold && plateau.improved) {
+          keep_best();
+          have_best = true;
+        }
+        if (stop) break;
       }
     }
+    if (have_best) restore_best();
 
     // validation score on the held rows
     double hits = 0.0;
@@ -905,7 +943,8 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
     } else if (k == KC_SMALL) {
       SLay sy;
       make_slay(sy, it.dims, n);  // only the hidden layer's moments live in global memory
-      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, 2ull * sy.HP * sy.ldw * 4);
+      // the hidden layer's moments, and room for the best epoch's weights (early stopping on held-out rows)
+      pl.sub[k].slot_bytes = std::max<uint64_t>(pl.sub[k].slot_bytes, (3ull * sy.HP * sy.ldw + (sy.HP + 1) * 4ull) * 4);
       pl.sub[k].lds_bytes = std::max<uint32_t>(pl.sub[k].lds_bytes, sy.lds_total);
     } else if (k == KC_MID) {
       MLay my;

@@ -129,7 +129,7 @@ struct Layout {
   int32_t p16a[MAXL + 1];  // dims+1 rounded up to 16
   int32_t cw[MAXL], cb[MAXL];  // offsets in the packed W[in][out], b[out] order
   int32_t P;
-  uint64_t w[MAXL], m[MAXL], v[MAXL], oi[MAXL], io[MAXL];
+  uint64_t w[MAXL], m[MAXL], v[MAXL], oi[MAXL], io[MAXL], best[MAXL];
   uint64_t A[MAXL], AT[MAXL], D[MAXL + 1], DT[MAXL + 1], Z, rowlist, total;
 };
 
@@ -165,6 +165,7 @@ __host__ __device__ inline void make_layout(Layout& y, const int32_t* dims, int 
     y.w[l] = take(wn * 4);
     y.m[l] = take(wn * 4);
     y.v[l] = take(wn * 4);
+    y.best[l] = take(wn * 4);  // the parameters of the best epoch so far under early stopping on held-out rows
     y.oi[l] = opsz == 4 ? y.w[l] : take(wn * opsz);
     y.io[l] = l >= 1 ? take((uint64_t)y.p16[l] * y.kp[l + 1] * opsz) : 0;
     y.A[l] = take((uint64_t)rows * y.kp[l] * opsz);
@@ -227,9 +228,11 @@ __device__ inline float epoch_lr(float lr, float power_t, int e, int n_tr) {
 struct Plateau {
   float best = INFINITY;
   int stalled = 0;
+  bool improved = false;  // the last loss given was the lowest so far
   __device__ bool stop_after(float epoch_loss, float tol, int patience) {
     stalled = epoch_loss > best - tol ? stalled + 1 : 0;
-    if (epoch_loss < best) best = epoch_loss;
+    improved = epoch_loss < best;
+    if (improved) best = epoch_loss;
     return stalled > patience;
   }
 };

@@ -26,7 +26,8 @@
 // No workgroup barrier anywhere: a wavefront's LDS accesses execute in order.
 //
 // LDS per wavefront (floats): xs[64][S] (S = d + 1 made odd), ws[d + 1][CO]
-// (CO = outputs padded to 1, 2, 4, 8 or 16), ds[64][CO], and, for data sets of
+// (CO = outputs padded to 1, 2, 4, 8 or 16), ds[64][CO], wbest[d + 1][CO] (the best
+// epoch's parameters when early stopping watches held-out rows), and, for data sets of
 // up to LN_EPOCH_CAP rows, the epoch's row order ep[n]: the seeded permutation
 // is walked for all positions of the epoch at once (a lane that finishes a
 // position's walk starts its next one, so the lanes stay busy), instead of per
@@ -53,7 +54,8 @@ __host__ __device__ inline int ln_epoch_rows(int64_t n) { return n <= LN_EPOCH_C
 __host__ __device__ inline uint32_t ln_wave_bytes(int d, int c, int64_t n) {
   const int co = ln_co(c);
   const int epoch_words = ln_epoch_rows(n) ? ln_epoch_rows(n) + 256 : 0;  // the row order and the round-function table
-  return (uint32_t)(((64 * ln_stride(d) + (d + 1) * co + 64 * co + epoch_words) * 4 + 15) & ~15);
+  // (ws twice: the operand copy, and the parameters of the best epoch under early stopping on held-out rows)
+  return (uint32_t)(((64 * ln_stride(d) + 2 * (d + 1) * co + 64 * co + epoch_words) * 4 + 15) & ~15);
 }
 __host__ __device__ inline bool linear_eligible(const int32_t* dims, int L) {
   return L == 1 && dims[0] <= LN_MAX_D && dims[1] <= LN_MAX_OUT && ln_ki(dims[0]) * ln_co(dims[1]) <= LN_MAX_PER_LANE;
@@ -107,6 +109,7 @@ struct Linear {
   float* xs;
   float* ws;
   float* ds;
+  float* wbest; // parameters of the best epoch so far (early stopping on held-out rows), unrounded
   int32_t* ep;  // the epoch's rows in visiting order, or null: permuted on the fly
   int lane, d, c, S, Pn;
   int r0, k0, q64, r64;  // element `lane` of a chunk's row-major block, and the step of 64 elements
@@ -386,6 +389,7 @@ struct Linear {
     }
 
     Plateau plateau;
+    bool have_best = false;
     const bool watch = patience > 0 && steps > 0 && !resume;
     for (int e = e0; e < epochs; e++) {
       const uint64_t ke = key_epoch(km, e);
@@ -494,8 +498,30 @@ struct Linear {
           score_rows(tr, sp, ROWS_HELD, sp.n_hold, hl, hh);
           watched = (float)(wave_sum(hl) / (double)sp.n_hold);
         }
-        if (plateau.stop_after(watched, tol, patience)) break;
+        const bool stop = plateau.stop_after(watched, tol, patience);
+        if (sp.n_hold && plateau.improved) {  // keep the best epoch's parameters: every lane parks its own
+#pragma unroll
+          for (int i = 0; i < KI; i++)
+            if (lane + 64 * i < d) lds_put<CO>(wbest + (lane + 64 * i) * CO, w[i]);
+          if (lane < CO) wbest[d * CO + lane] = bw;
+          have_best = true;
+        }
+        if (stop) break;
       }
+    }
+    if (have_best) {  // early stopping on held-out rows scores the best epoch's model
+      ln_lds_fence();
+#pragma unroll
+      for (int i = 0; i < KI; i++)
+        if (lane + 64 * i < d) {
+          lds_get<CO>(wbest + (lane + 64 * i) * CO, w[i]);
+          put_weights(lane + 64 * i, w[i]);
+        }
+      if (lane < CO) {
+        bw = wbest[d * CO + lane];
+        ws[d * CO + lane] = bw;
+      }
+      ln_lds_fence();
     }
 
     // validation score on the held rows
@@ -521,8 +547,9 @@ __global__ __launch_bounds__(256) void k_train_linear(const TrainParams P) {
   float* xs = (float*)(ln_lds + (size_t)wave * ln_wave_bytes(d, c, P.n));
   float* ws = xs + 64 * S;
   float* ds = ws + (d + 1) * CO;
-  int32_t* ep = ln_epoch_rows(P.n) ? (int32_t*)(ds + 64 * CO) : nullptr;
-  Linear<CO, KI> T{P, xs, ws, ds, ep, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
+  float* wbest = ds + 64 * CO;
+  int32_t* ep = ln_epoch_rows(P.n) ? (int32_t*)(wbest + (d + 1) * CO) : nullptr;
+  Linear<CO, KI> T{P, xs, ws, ds, wbest, ep, lane, d, c, S, Pn, lane / d, lane % d, 64 / d, 64 % d};
   for (;;) {
     // Every lane takes part in the pop (lane 0 adds one, the others nothing) and lane 0's result is the
     // wavefront's item.  A pop under `if (lane == 0)` must not be used here: the loop body ends with

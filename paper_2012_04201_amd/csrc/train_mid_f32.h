@@ -40,7 +40,7 @@ struct MLay {
   int32_t cw[2], cb[2], P;
   uint32_t o_w1, o_w2, o_xs, o_zp, o_d3, o_patch, o_rows, o_ys, o_epoch, lds_total;
   int32_t epoch_cap;  // entries of the per-epoch row table in LDS (0: rows are permuted on the fly)
-  uint32_t g_m1, g_v1, g_m2, g_v2, g_total;  // byte offsets in the global slot
+  uint32_t g_m1, g_v1, g_m2, g_v2, g_zero, g_best, g_total;  // byte offsets in the global slot
 };
 
 struct MItem {
@@ -101,6 +101,8 @@ __host__ __device__ inline void make_mlay(MLay& y, const int32_t* dims, int64_t 
   y.g_v1 = gtake(y.HP * y.ldw);
   y.g_m2 = gtake((y.HP + 1) * MD_CP);
   y.g_v2 = gtake((y.HP + 1) * MD_CP);
+  y.g_zero = g;  // what a new model must find zeroed: the moments
+  y.g_best = gtake(y.HP * y.ldw + (y.HP + 1) * MD_CP);  // weights of the best epoch so far (early stopping)
   y.g_total = g;
 }
 
@@ -163,6 +165,22 @@ struct Mid {
     const uint64_t kt = key_fold(key_model(it.seed, it.fold), 16 + 2 * l + (isb ? 1 : 0));
     const uint32_t k24 = (uint32_t)(key_fold(kt, (uint64_t)e) >> 40);
     return it.bound[l] * ((float)((int32_t)k24 - 8388608) * 0x1p-23f);
+  }
+
+  // Keep the current weights (both layers, as they lie in LDS) aside / put the kept ones back.  Block-wide; the
+  // caller orders it against updates.
+  __device__ __forceinline__ void copy_best(bool keep) const {
+    float* w1 = f(y.o_w1);
+    float* w2 = f(y.o_w2);
+    float* b = g(y.g_best);
+    const int n1 = y.HP * y.ldw, n2 = (y.HP + 1) * MD_CP;
+    for (int i = threadIdx.x; i < n1 + n2; i += blockDim.x) {
+      float* l = i < n1 ? w1 + i : w2 + (i - n1);
+      if (keep)
+        b[i] = *l;
+      else
+        *l = b[i];
+    }
   }
 
   // Weights into LDS (and, from a packed state, the moments into the slot).
@@ -569,7 +587,7 @@ struct Mid {
       const uint32_t n16 = y.o_rows / 16;
       for (uint32_t i = threadIdx.x; i < n16; i += blockDim.x) z[i] = uint4{0, 0, 0, 0};
       uint4* zg = (uint4*)slot;
-      const uint32_t g16 = y.g_total / 16;
+      const uint32_t g16 = y.g_zero / 16;
       for (uint32_t i = threadIdx.x; i < g16; i += blockDim.x) zg[i] = uint4{0, 0, 0, 0};
     }
     double b1t = 1.0, b2t = 1.0;
@@ -636,6 +654,7 @@ struct Mid {
     double lsum = 0.0, hits = 0.0, pen = 0.0, esum = 0.0;  // esum: the lane's share of the epoch's summed data loss
     float* rec = nullptr;
     Plateau plateau;
+    bool have_best = false;
     const bool watch = it.patience > 0 && !resume;
     // Loss and second score (the thread's share) of `count` rows of a list under the current weights.
     auto score_rows = [&](const int32_t* list, int mode, int count, double& ls, double& hs) {
@@ -727,6 +746,10 @@ struct Mid {
             watched = (float)(block_sum(esum, red) / (double)n_fit);
           }
           if (plateau.stop_after(watched, it.tol, it.patience)) epochs_lim = pos.e + 1;
+          if (sp.n_hold && plateau.improved) {  // (the scoring pass ended with a barrier: the weights are at rest)
+            copy_best(true);
+            have_best = true;
+          }
           esum = 0.0;
         }
       }
@@ -734,6 +757,10 @@ struct Mid {
       par ^= 1;
     }
     __syncthreads();
+    if (have_best) {  // early stopping on held-out rows scores the best epoch's model
+      copy_best(false);
+      __syncthreads();
+    }
 
     // ---- validation score on the held rows ----
     lsum = 0.0;

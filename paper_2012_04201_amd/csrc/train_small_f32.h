@@ -125,6 +125,22 @@ struct Small {
   __device__ float* f(uint32_t off) const { return (float*)(lds + off); }
   __device__ float* m1g() const { return (float*)slot; }
   __device__ float* v1g() const { return (float*)slot + y.HP * y.ldw; }
+  // weights of the best epoch so far (early stopping on held-out rows): both layers, as they lie in LDS
+  __device__ float* bestg() const { return (float*)slot + 2 * y.HP * y.ldw; }
+  // Keep the current weights aside / put the kept ones back.  Block-wide; the caller orders it against updates.
+  __device__ __forceinline__ void copy_best(bool keep) const {
+    float* w1 = f(y.o_w1);
+    float* w2 = f(y.o_w2);
+    float* b = bestg();
+    const int n1 = y.HP * y.ldw, n2 = (y.HP + 1) * 4;
+    for (int i = threadIdx.x; i < n1 + n2; i += blockDim.x) {
+      float* l = i < n1 ? w1 + i : w2 + (i - n1);
+      if (keep)
+        b[i] = *l;
+      else
+        *l = b[i];
+    }
+  }
   __device__ int32_t* rowlist(int par) const { return (int32_t*)(lds + y.o_rows) + par * SM_RC; }
   __device__ float* xt(int par) const { return f(y.o_xt) + par * K0 * y.lda; }
   __device__ float* ys(int par) const { return f(y.o_ys) + par * SM_RC; }
@@ -729,6 +745,7 @@ struct Small {
     double lsum = 0.0, hits = 0.0, pen = 0.0, esum = 0.0;  // esum: the lane's share of the epoch's summed data loss
     float* rec = nullptr;
     Plateau plateau;
+    bool have_best = false;
     const bool watch = it.patience > 0 && !resume;
     // Loss and second score (the thread's share) of `count` rows of a list under the current weights; uses
     // the input tiles of parity 0 and the forward accumulators.
@@ -817,6 +834,10 @@ struct Small {
             watched = (float)(block_sum(esum, red) / (double)n_fit);
           }
           if (plateau.stop_after(watched, it.tol, it.patience)) epochs_lim = pos.e + 1;
+          if (sp.n_hold && plateau.improved) {  // (the scoring pass ended with a barrier: the weights are at rest)
+            copy_best(true);
+            have_best = true;
+          }
           esum = 0.0;
         }
       }
@@ -824,6 +845,10 @@ struct Small {
       par ^= 1;
     }
     __syncthreads();
+    if (have_best) {  // early stopping on held-out rows scores the best epoch's model
+      copy_best(false);
+      __syncthreads();
+    }
 
     // ---- validation score on the held rows ----
     lsum = 0.0;

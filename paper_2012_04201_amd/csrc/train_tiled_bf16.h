@@ -91,6 +91,7 @@ struct TLay {
   uint32_t lds_total;
   uint64_t w[TB_MAXL], m[TB_MAXL], v[TB_MAXL], gp[TB_MAXL], oi[TB_MAXL][2], io[2], T[TB_MAXL];
   uint64_t bias[TB_MAXL], bm[TB_MAXL], bv[TB_MAXL], bg[TB_MAXL], total;  // bias: value, moments, partial gradient
+  uint64_t wb[TB_MAXL], bb[TB_MAXL];  // weights and bias of the best epoch so far (early stopping on held-out rows)
 };
 
 __host__ __device__ inline bool tiled_eligible(const int32_t* dims, int L) {
@@ -138,6 +139,8 @@ __host__ __device__ inline void make_tlay(TLay& y, const int32_t* dims, int L) {
     y.bm[l] = take((uint64_t)y.UP[l + 1] * 4);
     y.bv[l] = take((uint64_t)y.UP[l + 1] * 4);
     y.bg[l] = take((uint64_t)y.UP[l + 1] * 4);
+    y.wb[l] = take(wn * 4);
+    y.bb[l] = take((uint64_t)y.UP[l + 1] * 4);
     // transposed spill of level l: needed by the weight gradient of every layer but the last
     y.T[l] = l <= L - 2 ? take((uint64_t)y.UP[l] * TB_ROWS * 2) : 0;
   }
@@ -293,6 +296,31 @@ struct Tiled {
         }
       }
     }
+  }
+
+  // Early stopping on held-out rows hands back the parameters of the best epoch: keep them aside ...
+  __device__ __forceinline__ void keep_best() const {
+    for (int l = 0; l < y.L; l++) {
+      const uint4* W = (const uint4*)fp(y.w[l]);
+      uint4* B = (uint4*)fp(y.wb[l]);
+      const int n16 = y.UP[l + 1] * y.UP[l] / 4;
+      for (int i = threadIdx.x; i < n16; i += blockDim.x) B[i] = W[i];
+      for (int j = threadIdx.x; j < y.UP[l + 1]; j += blockDim.x) fp(y.bb[l])[j] = fp(y.bias[l])[j];
+    }
+    __syncthreads();
+  }
+  // ... and put them back, with the operand copies of parity `par`, before the held fold is scored.
+  __device__ __forceinline__ void restore_best(int par) const {
+    for (int l = 0; l < y.L; l++) {
+      const int fi = y.U[l], fo = y.U[l + 1];
+      for (int i = threadIdx.x; i < fi * fo + fo; i += blockDim.x) {
+        const bool isb = i >= fi * fo;
+        const int e = isb ? i - fi * fo : i;
+        const int k = isb ? 0 : e / fo, j = isb ? e : e % fo;
+        store_param(l, k, j, isb, isb ? fp(y.bb[l])[j] : fp(y.wb[l])[sidx(l, k, j)], par);
+      }
+    }
+    __syncthreads();
   }
 
   // ---- staging --------------------------------------------------------------
@@ -1379,7 +1407,7 @@ struct Tiled {
     const bool watch = it.patience > 0 && steps > 0 && !(traced && P.state_in);
     // One loop over the epochs and, after the last one, the scoring of the held fold: the scoring pass (rows
     // set aside for early stopping after an epoch, the fold's held rows at the end) exists once in the code.
-    bool stop = false;
+    bool stop = false, have_best = false;
     for (int e = e0;; e++) {
       const bool final = stop || e >= it.epochs;
       double esum = 0.0;  // the lane's share of the epoch's summed data loss
@@ -1429,6 +1457,7 @@ struct Tiled {
       }
       float watched = 0.f;
       if (watch && !final && !sp.n_hold) watched = (float)(block_sum(esum, red) / (double)n_fit);
+      if (final && have_best) restore_best((int)(gstep & 1));
       if (final || (watch && sp.n_hold)) {
         // loss (and second score) of a list of rows under the current weights
         const int32_t* list = final ? va : tr;
@@ -1452,7 +1481,13 @@ struct Tiled {
         }
         watched = (float)(lsum / (double)count);  // the loss of the rows set aside, under the weights the epoch ends with
       }
-      if (watch) stop = plateau.stop_after(watched, it.tol, it.patience);
+      if (watch) {
+        stop = plateau.stop_after(watched, it.tol, it.patience);
+        if (sp.n_hold && plateau.improved) {
+          keep_best();
+          have_best = true;
+        }
+      }
     }
   }
 };

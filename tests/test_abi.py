@@ -62,9 +62,13 @@ def test_kernel_class_is_a_property_of_the_suggestion(bb):
     """Host logic: which training kernel a shape goes to (the limits each kernel documents)."""
     k = lambda n, d, c, hidden, dt=0: bb.bbo_mlp_kernel_class(n, d, c, {"hidden": hidden}, dt)
     assert k(569, 30, 2, [100]) == bb.KERNEL_SMALL
-    assert k(569, 63, 4, [224]) in (bb.KERNEL_SMALL, bb.KERNEL_GENERIC)  # decided by the LDS the shape needs
-    assert k(569, 64, 2, [100]) == bb.KERNEL_GENERIC      # 64 inputs and the bias column do not fit 64 columns
-    assert k(569, 30, 5, [100]) == bb.KERNEL_GENERIC      # more than 4 outputs
+    assert k(569, 63, 4, [224]) in (bb.KERNEL_SMALL, bb.KERNEL_MID)  # decided by the LDS the shape needs
+    assert k(569, 64, 2, [100]) == bb.KERNEL_MID          # 64 inputs and the bias column do not fit 64 columns
+    assert k(569, 30, 5, [100]) == bb.KERNEL_MID          # more than 4 outputs
+    assert k(1797, 64, 10, [100]) == bb.KERNEL_MID        # the digits shape
+    assert k(500, 127, 17, [64]) == bb.KERNEL_GENERIC     # more than 16 outputs
+    assert k(500, 128, 16, [64]) == bb.KERNEL_GENERIC     # more than 127 inputs
+    assert k(500, 100, 10, [256]) == bb.KERNEL_GENERIC    # both weight matrices no longer fit one CU's LDS
     assert k(569, 30, 2, [100, 50]) == bb.KERNEL_GENERIC  # two hidden layers in fp32
     assert k(569, 30, 2, []) == bb.KERNEL_LINEAR
     assert k(1797, 64, 10, []) == bb.KERNEL_LINEAR

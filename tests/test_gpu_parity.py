@@ -766,6 +766,39 @@ def test_early_stopping_on_a_validation_fraction(bb, oracle, n, d, c, hidden, bs
     assert stops[2] == E and (stops[0] < E or n >= 1000)  # the small cases do stop early; the switched-off rule never does
 
 
+@pytest.mark.parametrize("n,d,c,hidden,bs,dtype,kernel", EARLY_STOP_SHAPES)
+def test_early_stopping_scores_the_best_epoch_on_the_held_rows(bb, oracle, n, d, c, hidden, bs, dtype, kernel):
+    """A step size large enough that the held rows' loss goes up and down, tol = 0 and a patience of 3 epochs:
+    training stops some epochs after the best one, and the model that is scored is the best epoch's.  A run of
+    e epochs ends with the best of its first e, so the run of exactly the best epoch's length scores bit for
+    bit what the stopped run scored, and that length is shorter than the stopped run."""
+    cfg = small_problem(1700 + d, n, d, c, bf16=bool(dtype))
+    X, y, ft = bb.to_device(cfg)
+    f, E = 1, 60 if n < 1000 else 16
+    hp = {"hidden": hidden, "solver": "adam", "batch_size": bs, "alpha": 0.001, "lr": 0.2 if n >= 1000 and not hidden else 0.05,
+          "epochs": E, "seed": 61, "validation_fraction": 0.15, "tol": 0.0, "n_iter_no_change": 3}
+    assert bb.bbo_mlp_kernel_class(n, d, c, hp, dtype) == getattr(bb, "KERNEL_" + kernel)
+    n_fit = int((cfg["fold_idx"] != f).sum())
+    n_fit -= int(np.floor(np.float32(0.15) * n_fit))
+    spe = -(-n_fit // bs)
+    scores, status, pf, tr_ = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, [hp], dtype, want_per_fold=True, trace=(0, f, 0, E * spe))
+    torch.cuda.synchronize()
+    done = int(np.isfinite(tr_["loss"].cpu().numpy()).sum())
+    assert done % spe == 0 and 3 < done // spe < E, done
+    stop = done // spe
+    shorter = [dict(hp, epochs=e) for e in range(1, stop + 1)]
+    _, _, pfe = bb.bbo_mlp_cv_eval(X, y, c, ft, 5, shorter, dtype, want_per_fold=True)
+    torch.cuda.synchronize()
+    same = [e for e in range(1, stop + 1) if pfe[e - 1, f, 0].item() == pf[0, f, 0].item()]
+    assert same and min(same) <= stop - 3, (stop, same)
+    ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, f, dtype=dtype, step_begin=0, step_end=E * spe)
+    ref_done = int(np.isfinite(ref["loss"]).sum())
+    assert abs(done - ref_done) <= 4 * spe, (stop, ref_done // spe)
+    if done == ref_done:
+        check_fold_score(oracle, cfg, c, hp, f, dtype, pf[0, f, 0].item(), ref["scores"][0],
+                         "best epoch %s" % ((n, d, hidden, dtype, stop, min(same)),))
+
+
 # ----------------------------------------------------------- final scores ----
 
 def explained_flips(acc_gpu, acc_ref, n_va):

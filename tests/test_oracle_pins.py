@@ -691,10 +691,10 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
     def held_loss(tt):
         return float(torch_loss(tt, dims, Xt[held], yt[held], n_classes, 0.0)) * (1.0 if n_classes else 2.0)
 
-    stops = []
+    stops, late = [], []
     for tol, k in [(1e-3, 2), (2e-2, 1), (0.0, 4)]:
         tt = torch.tensor(oracle.init_params(5, n_classes, base, f), dtype=torch.float64, requires_grad=True)
-        best, stalled, stop_at = np.float32(np.inf), 0, E
+        best, stalled, stop_at, tt_best, best_epoch = np.float32(np.inf), 0, E, None, -1
         for e in range(E):
             kep = py_fold(py_fold(kmodel, 1), e)
             for s in range(-(-n_fit // 16)):
@@ -704,7 +704,8 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
                 tt = (tt - lr * g).detach().requires_grad_(True)
             le = np.float32(held_loss(tt.detach()))
             stalled = stalled + 1 if le > np.float32(best - np.float32(tol)) else 0
-            best = min(best, le)
+            if le < best:  # the best iterate on the held rows is the model that is handed back
+                best, tt_best, best_epoch = le, tt.detach().clone(), e
             if stalled > k:
                 stop_at = e + 1
                 break
@@ -712,11 +713,16 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
         spe = -(-n_fit // 16)
         got = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1, step_begin=0, step_end=E * spe)
         assert int(np.isfinite(got["loss"]).sum()) == stop_at * spe, (tol, k, stop_at)
-        np.testing.assert_allclose(got["theta"], tt.detach().numpy(), rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(got["theta"], tt_best.numpy(), rtol=1e-9, atol=1e-12)
+        # ... which is the recorded state after that epoch's last step, not the last one when the rule let training run on
+        np.testing.assert_allclose(got["theta"], got["theta_after"][(best_epoch + 1) * spe - 1], rtol=0, atol=0)
+        late.append(best_epoch + 1 < stop_at)
+        tt = tt_best
         want = float(torch_loss(tt.detach(), dims, Xt[va], yt[va], n_classes, 0.0)) * (1.0 if n_classes else 2.0)
         assert abs(got["scores"][0] - want) < 1e-10
         stops.append(stop_at)
     assert min(stops) < E, stops  # the rule does end some run early
+    assert any(late), late        # and some run's best epoch is not its last one
     # the same rule on the training loss (no fraction) stops elsewhere: the held rows really are what is watched
     other = oracle.train_one(X, y, n_classes, fold, dict(base, tol=2e-2, n_iter_no_change=1, validation_fraction=0.0), f,
                              prec=1, step_begin=0, step_end=E * 5)
