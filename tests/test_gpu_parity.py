@@ -174,6 +174,7 @@ TRACE_CASES = [
     (260, 20, 5, [40, 24], "adam", False, 64, 0.02),
     (180, 9, 0, [17, 18, 19], "sgd", True, 48, 0.01),
     (90, 3, 3, [1], "adam", False, 5, 0.0),
+    (180, 9, 3, [9, 1, 5, 7], "adam", False, 48, 0.01),   # the maximum depth, one hidden layer a single unit wide
     # the LDS-resident kernel without its per-epoch row table (rows permuted on the fly): more than 4,096 rows,
     # and a hidden layer so wide that the table no longer fits beside the weights
     (5000, 20, 3, [40], "adam", False, 700, 0.01),

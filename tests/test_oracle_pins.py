@@ -82,6 +82,15 @@ def test_permutation_is_bijection(oracle, n):
     assert np.array_equal(np.sort(p), np.arange(n))
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 15, 16, 17, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 4096, 4097])
+def test_permutation_network_width_at_powers_of_two(oracle, n):
+    """The network works on the smallest even number of bits (at least 2) that holds n - 1: at a power of two
+    no position is walked twice, one past it the width grows.  Checked against the network in plain integers."""
+    kep = py_fold(py_fold(py_fold(py_fold(77, 0x4D4C50), 3), 1), 6)
+    ps = range(n) if n <= 300 else list(range(0, n, 37)) + [n - 1]
+    assert [oracle.perm_index(77, 3, 6, n, p) for p in ps] == [py_perm(kep, n, p) for p in ps]
+
+
 def test_permutation_depends_on_key_and_mixes(oracle):
     n = 1000
     a = oracle.permutation(1, 0, 0, n)
@@ -124,6 +133,39 @@ def test_minibatches_cover_train_rows_once_per_epoch(oracle):
         hp2 = dict(hp, batch_size=bs)
         tr, _ = oracle.fold_lists(fold, 1)
         assert len(oracle.minibatch_rows(fold, hp2, 1, 0, 0)) == len(tr)
+
+
+def test_init_tensors_draw_from_streams_of_their_own(oracle):
+    """Divided by its layer's bound every tensor is a sequence of centred 24-bit draws; no tensor repeats the
+    draws of another one (a shared or shifted key would), and none is correlated with another."""
+    hp = {"hidden": [40, 40, 40], "seed": 9}
+    d, c = 40, 40
+    dims = [d, 40, 40, 40, c]
+    th = oracle.init_params(d, c, hp, 0)
+    assert th.shape[0] == oracle.param_count(d, c, hp) == sum(fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
+    draws = []
+    for (W, b), fi, fo in zip(unpack(th, dims), dims[:-1], dims[1:]):
+        bound = float(np.float32(np.sqrt(6.0 / (fi + fo))))
+        draws += [W.ravel() / bound, b / bound]
+    for i, a in enumerate(draws):
+        k = np.round(a * 2**23)
+        assert np.abs(a * 2**23 - k).max() < 1.0  # a 24-bit draw times a bound, rounded once to fp32
+        for b in draws[i + 1:]:
+            m = min(a.size, b.size)
+            assert np.abs(a[:m] - b[:m]).max() > 0.5          # not the same draws
+            assert abs(np.corrcoef(a[:m], b[:m])[0, 1]) < 5 / np.sqrt(m)
+
+
+def test_shapes_at_the_limits_are_taken(oracle):
+    """Four hidden layers and a hidden layer of one unit are legal; five layers or a width of zero are not."""
+    assert oracle.param_count(4, 3, {"hidden": [3, 1, 2, 4]}) == 4 * 3 + 3 + 3 * 1 + 1 + 1 * 2 + 2 + 2 * 4 + 4 + 4 * 3 + 3
+    assert oracle.param_count(4, 0, {"hidden": [1]}) == 4 + 1 + 1 + 1
+    import ctypes as C
+    hp = oracle.make_hparams([{"hidden": [3]}])
+    hp[0].n_hidden = 5
+    assert oracle.lib().oracle_param_count(C.c_int32(4), C.c_int32(3), hp) < 0
+    hp[0].n_hidden, hp[0].hidden[0] = 1, 0
+    assert oracle.lib().oracle_param_count(C.c_int32(4), C.c_int32(3), hp) < 0
 
 
 def test_init_glorot_bounds_and_moments(oracle):
@@ -189,6 +231,7 @@ CASES = [
     (1, [5], 0.3),      # single-logit binary head
     (1, [], 0.0),
     (1, [4, 3], 0.6),
+    (3, [3, 1, 2, 4], 0.2),   # the maximum depth, with a hidden layer one unit wide
 ]
 
 
@@ -659,6 +702,13 @@ def test_early_stop_split_is_a_keyed_cut_of_the_training_list(oracle):
                 assert rows == want
                 seen += rows
             assert sorted(seen) == fit
+    # the cut keeps at least one row on either side
+    two = np.array([0, 1, 1, 0, 1], dtype=np.int32)  # fold 0 leaves three rows, fold 1 two
+    for frac, f, want in [(0.01, 0, 1), (0.99, 0, 2), (7.5, 0, 2), (0.5, 1, 1), (0.01, 1, 1), (3.0, 1, 1)]:
+        hp = {"hidden": [3], "seed": 5, "n_iter_no_change": 1, "validation_fraction": frac}
+        assert len(oracle.early_stop_rows(two, hp, f)) == want, (frac, f)
+    one = np.array([0, 1, 1, 1], dtype=np.int32)      # fold 1 leaves one training row: nothing to set aside
+    assert len(oracle.early_stop_rows(one, dict(hp, validation_fraction=0.5), 1)) == 0
     # switched off (no patience, or no fraction): nothing is set aside, the order is the plain one
     for off in ({"n_iter_no_change": 0, "validation_fraction": 0.3}, {"n_iter_no_change": 3, "validation_fraction": 0.0}):
         hp = dict({"hidden": [3], "batch_size": 16, "seed": 5}, **off)
