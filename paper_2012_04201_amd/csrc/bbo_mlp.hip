@@ -812,31 +812,47 @@ struct Plan {
            total = 0;
 };
 
+// Resident workgroups of the generic kernel / compute units, of the current device (looked up once per
+// device and thread).
+struct DeviceFacts {
+  int dev, cus, slots[2];
+};
+int device_facts(DeviceFacts** out) {
+  static thread_local std::vector<DeviceFacts> seen;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  for (DeviceFacts& e : seen)
+    if (e.dev == dev) {
+      *out = &e;
+      return BBO_OK;
+    }
+  DeviceFacts e{dev, 0, {0, 0}};
+  HIP_TRY(hipDeviceGetAttribute(&e.cus, hipDeviceAttributeMultiprocessorCount, dev));
+  seen.push_back(e);
+  *out = &seen.back();
+  return BBO_OK;
+}
+
 int device_slots(int dtype, int* out) {
-  static thread_local int cached[2] = {0, 0};
-  if (!cached[dtype]) {
-    int dev = 0, cus = 0, occ = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  DeviceFacts* e = nullptr;
+  if (int rc = device_facts(&e)) return rc;
+  if (!e->slots[dtype]) {
+    int occ = 0;
     if (dtype == BBO_F32)
       HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_train<float>, NTHREADS, 0));
     else
       HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_train<__bf16>, NTHREADS, 0));
     if (occ < 1) occ = 1;
-    cached[dtype] = cus * occ;
+    e->slots[dtype] = e->cus * occ;
   }
-  *out = cached[dtype];
+  *out = e->slots[dtype];
   return BBO_OK;
 }
 
 int device_cus(int* out) {
-  static thread_local int cus = 0;
-  if (!cus) {
-    int dev = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  }
-  *out = cus;
+  DeviceFacts* e = nullptr;
+  if (int rc = device_facts(&e)) return rc;
+  *out = e->cus;
   return BBO_OK;
 }
 
@@ -1014,33 +1030,44 @@ int make_plan(Plan& pl, int64_t n, int d, int n_classes, int n_folds, int fold_b
 }
 
 
-// Pinned staging for the item list: one buffer per host thread, reused once
+// Pinned staging for the item list: one buffer per host thread and device, reused once
 // the previous call's copy has completed.
 struct Staging {
+  int dev = -1;
   void* ptr = nullptr;
   size_t cap = 0;
   hipEvent_t ev = nullptr;
   bool pending = false;
 };
-thread_local Staging g_stage;
+thread_local std::vector<Staging> g_stage;
 
 int stage_items(const void* src, size_t bytes, void* dst, hipStream_t s) {
-  if (!g_stage.ev) HIP_TRY(hipEventCreateWithFlags(&g_stage.ev, hipEventDisableTiming));
-  if (g_stage.pending) {
-    HIP_TRY(hipEventSynchronize(g_stage.ev));
-    g_stage.pending = false;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  Staging* st = nullptr;
+  for (Staging& e : g_stage)
+    if (e.dev == dev) st = &e;
+  if (!st) {
+    g_stage.push_back(Staging());
+    st = &g_stage.back();
+    st->dev = dev;
   }
-  if (g_stage.cap < bytes) {
-    if (g_stage.ptr) HIP_TRY(hipHostFree(g_stage.ptr));
-    g_stage.ptr = nullptr;
-    g_stage.cap = 0;
-    HIP_TRY(hipHostMalloc(&g_stage.ptr, bytes, hipHostMallocDefault));
-    g_stage.cap = bytes;
+  if (!st->ev) HIP_TRY(hipEventCreateWithFlags(&st->ev, hipEventDisableTiming));
+  if (st->pending) {
+    HIP_TRY(hipEventSynchronize(st->ev));
+    st->pending = false;
   }
-  memcpy(g_stage.ptr, src, bytes);
-  HIP_TRY(hipMemcpyAsync(dst, g_stage.ptr, bytes, hipMemcpyHostToDevice, s));
-  HIP_TRY(hipEventRecord(g_stage.ev, s));
-  g_stage.pending = true;
+  if (st->cap < bytes) {
+    if (st->ptr) HIP_TRY(hipHostFree(st->ptr));
+    st->ptr = nullptr;
+    st->cap = 0;
+    HIP_TRY(hipHostMalloc(&st->ptr, bytes, hipHostMallocDefault));
+    st->cap = bytes;
+  }
+  memcpy(st->ptr, src, bytes);
+  HIP_TRY(hipMemcpyAsync(dst, st->ptr, bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipEventRecord(st->ev, s));
+  st->pending = true;
   return BBO_OK;
 }
 

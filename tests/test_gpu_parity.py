@@ -1185,6 +1185,22 @@ def test_edge_cases(bb, oracle):
     rs, rst, _ = oracle.cv_eval(reg["X"], reg["y"], 0, reg["fold_idx"], 5, [bad, good])
     assert st.cpu().tolist() == [1, 0] and rst.tolist() == [1, 0]
     assert abs(s[1, 0].item() - rs[1, 0]) < ABS_SCORE
+    # one feature (with and without a hidden layer); a single fold: every row is held out, nothing is trained
+    # on, and the initial weights are scored
+    one = dict(reg, X=np.ascontiguousarray(reg["X"][:, :1]))
+    X1, y1, f1 = bb.to_device(one)
+    hps = [dict(good, hidden=[8]), dict(good, hidden=[]), dict(good, hidden=[5, 4])]
+    s, st = bb.bbo_mlp_cv_eval(X1, y1, 0, f1, 5, hps, 0)
+    torch.cuda.synchronize()
+    rs, rst, _ = oracle.cv_eval(one["X"], one["y"], 0, one["fold_idx"], 5, hps)
+    assert st.cpu().tolist() == [0, 0, 0] and np.allclose(s.cpu().numpy(), rs, atol=ABS_SCORE)
+    all0 = torch.zeros_like(f1)
+    s, st = bb.bbo_mlp_cv_eval(X1, y1, 0, all0, 1, hps, 0)
+    s0, _ = bb.bbo_mlp_cv_eval(X1, y1, 0, all0, 1, [dict(h, epochs=0) for h in hps], 0)
+    torch.cuda.synchronize()
+    rs, rst, _ = oracle.cv_eval(one["X"], one["y"], 0, np.zeros(80, dtype=np.int32), 1, hps)
+    assert st.cpu().tolist() == rst.tolist() == [0, 0, 0] and torch.equal(s, s0)
+    assert np.allclose(s.cpu().numpy(), rs, atol=1e-5)
 
 
 @pytest.mark.parametrize("dtype", [0, 1])

@@ -431,8 +431,23 @@ def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov,
             np.testing.assert_allclose(res["grad"][k], tt.grad.numpy(), rtol=1e-8, atol=1e-12)
             opt.step()
             np.testing.assert_allclose(res["theta_after"][k], tt.detach().numpy(), rtol=1e-8, atol=1e-12)
+            # the recorded optimizer state is the library's: both Adam moments, or the velocity
+            # (the library keeps buf = mu buf + g and steps by -lr buf: the velocity is -lr buf at a constant rate)
+            st = opt.state[tt]
+            if solver == "adam":
+                np.testing.assert_allclose(res["m_after"][k], st["exp_avg"].numpy(), rtol=1e-8, atol=1e-14)
+                np.testing.assert_allclose(res["v_after"][k], st["exp_avg_sq"].numpy(), rtol=1e-8, atol=1e-16)
+            else:
+                np.testing.assert_allclose(res["m_after"][k], -lr * st["momentum_buffer"].numpy(), rtol=1e-8, atol=1e-14)
             k += 1
     np.testing.assert_allclose(res["theta"], tt.detach().numpy(), rtol=1e-8, atol=1e-12)
+    # a later window of steps records the same steps, and a run told to stop after its window hands back the
+    # parameters of the window's last step
+    win = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1, step_begin=4, step_end=7, stop_after=True)
+    for key in ("loss", "grad", "theta_after", "m_after", "v_after"):
+        assert np.array_equal(win[key], res[key][4:7]), key
+    assert np.array_equal(win["theta"], res["theta_after"][6])
+    assert not np.array_equal(win["theta"], res["theta"])
 
 
 def test_linear_mse_converges_to_least_squares_and_ridge(oracle):
@@ -506,6 +521,58 @@ def test_cv_score_is_unweighted_mean_of_folds_and_batch_invariant(oracle):
     # per-fold value equals the single-model entry point
     one = oracle.train_one(cfg["X"], cfg["y"], 3, cfg["fold_idx"], hps[3], 4)
     assert np.array_equal(one["scores"], pf[3, 4])
+
+
+@pytest.mark.parametrize("n_classes", [0, 1, 2, 3])
+def test_scores_are_the_library_metrics_of_the_returned_model(oracle, n_classes):
+    """Both reported scores, recomputed with library routines from the parameters the run hands back, on the
+    held fold: mean negative log-likelihood and accuracy (argmax, or the sign of the one logit), or mean
+    squared and mean absolute error."""
+    X, y = tiny_problem(21, n=90, d=5, n_classes=n_classes)
+    fold = inputs.make_folds(90, 5, 2)
+    hp = {"hidden": [6], "solver": "adam", "lr": 0.02, "alpha": 0.01, "batch_size": 16, "epochs": 6, "seed": 3}
+    f = 3
+    res = oracle.train_one(X, y, n_classes, fold, hp, f, prec=1)
+    c_out = n_classes if n_classes >= 2 else 1
+    (W1, b1), (W2, b2) = unpack(res["theta"], [5, 6, c_out])
+    va = np.flatnonzero(fold == f)
+    z = torch.tensor(np.maximum(X[va].astype(np.float64) @ W1 + b1, 0.0) @ W2 + b2)
+    if n_classes >= 2:
+        yt = torch.tensor(y[va].astype(np.int64))
+        want = [torch.nn.functional.cross_entropy(z, yt).item(), (z.argmax(1) == yt).double().mean().item()]
+        assert 0.0 < want[1] < 1.0  # neither score is trivial here
+    elif n_classes == 1:
+        yt = torch.tensor(y[va].astype(np.float64))
+        want = [torch.nn.functional.binary_cross_entropy_with_logits(z[:, 0], yt).item(),
+                ((z[:, 0] > 0).double() == yt).double().mean().item()]
+        assert 0.0 < want[1] < 1.0
+    else:
+        yt = torch.tensor(y[va].astype(np.float64))
+        want = [torch.nn.functional.mse_loss(z[:, 0], yt).item(), torch.nn.functional.l1_loss(z[:, 0], yt).item()]
+    np.testing.assert_allclose(res["scores"], want, rtol=1e-12, atol=1e-14)
+
+
+def test_smallest_problems_are_taken(oracle):
+    """One feature, one fold, no suggestions: legal.  With a single fold every row is held out, nothing is
+    trained on, and the score is that of the initial weights."""
+    X, y = tiny_problem(2, n=30, d=2, n_classes=0)
+    X = np.ascontiguousarray(X[:, :1])
+    fold = inputs.make_folds(30, 3, 0)
+    hp = {"hidden": [4], "solver": "sgd", "lr": 0.01, "batch_size": 8, "epochs": 4, "seed": 1}
+    s, st, pf = oracle.cv_eval(X, y, 0, fold, 3, [hp])
+    assert np.all(np.isfinite(s)) and st[0] == 0
+    s0, st0, pf0 = oracle.cv_eval(X, y, 0, fold, 3, [])
+    assert s0.shape[0] == 0
+    one = np.zeros(30, dtype=np.int32)
+    s1, st1, _ = oracle.cv_eval(X, y, 0, one, 1, [hp])
+    s2, _, _ = oracle.cv_eval(X, y, 0, one, 1, [dict(hp, epochs=0)])
+    assert st1[0] == 0 and np.isfinite(s1[0, 0]) and np.array_equal(s1, s2)
+    h1, hst = oracle.holdout_eval(X, y, 0, np.where(np.arange(30) < 20, 0, -1).astype(np.int32), [hp])
+    assert np.all(np.isfinite(h1)) and hst[0] == 0
+    assert oracle.holdout_eval(X, y, 0, fold, [])[0].shape[0] == 0
+    # no rows at all: every fold is empty, which is a score that does not exist, not an error
+    sn, stn, _ = oracle.cv_eval(X[:0], y[:0], 0, fold[:0], 3, [hp])
+    assert stn[0] == 1 and np.all(np.isnan(sn[0]))
 
 
 def test_stratified_folds_are_balanced():
@@ -704,7 +771,8 @@ def test_early_stop_split_is_a_keyed_cut_of_the_training_list(oracle):
             assert sorted(seen) == fit
     # the cut keeps at least one row on either side
     two = np.array([0, 1, 1, 0, 1], dtype=np.int32)  # fold 0 leaves three rows, fold 1 two
-    for frac, f, want in [(0.01, 0, 1), (0.99, 0, 2), (7.5, 0, 2), (0.5, 1, 1), (0.01, 1, 1), (3.0, 1, 1)]:
+    for frac, f, want in [(0.01, 0, 1), (0.99, 0, 2), (1.0, 0, 2), (1.34, 0, 2), (7.5, 0, 2), (0.5, 1, 1), (0.01, 1, 1),
+                          (3.0, 1, 1)]:
         hp = {"hidden": [3], "seed": 5, "n_iter_no_change": 1, "validation_fraction": frac}
         assert len(oracle.early_stop_rows(two, hp, f)) == want, (frac, f)
     one = np.array([0, 1, 1, 1], dtype=np.int32)      # fold 1 leaves one training row: nothing to set aside
