@@ -48,7 +48,10 @@
  * number of bits with cycle walking.
  *
  * Parity unpinned: the final CV scores of the benchmark configurations have
- * no published value; they are compared GPU <-> oracle only.
+ * no published value; they are compared GPU <-> oracle only.  The two tie
+ * rules of the accuracy (equal logits go to the lowest class; a single logit
+ * of exactly zero counts as class 0) need exactly equal logits, which no
+ * input of this interface produces on purpose: they are unpinned as well.
  */
 #include <math.h>
 #include <stdint.h>

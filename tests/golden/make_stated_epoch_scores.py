@@ -37,8 +37,9 @@ PICKS = {
     0: list(range(8)),
     1: list(range(8)),
     2: list(range(8)),
-    3: [0, 1, 255, 256, 777, 1024, 1500, 2047],
-    4: [0, 819, 1639],
+    3: [0, 1, 255, 256, 777, 1024, 1500, 2047, 100, 333, 512, 640, 900, 1111, 1300, 1400, 1601, 1700, 1800, 1900,
+        1999, 2000, 2020, 2040],
+    4: [0, 205, 410, 819, 1024, 1230, 1435, 1639],
 }
 
 

@@ -891,13 +891,40 @@ def stated_record(idx):
     return cfg, rec["picks"], rs, np.array(rec["status"]), rpf, noise
 
 
+def check_chaotic_early(bb, oracle, cfg, X, y, ft, hps, noise, rst, name):
+    """The suggestions whose final score the oracle cannot pin to 1e-3 (see score_bar) are still compared where
+    rounding has not grown yet: the first step's gradient and weights per layer, and the scores after one
+    epoch under the same rule as everywhere else."""
+    idx = [b for b in range(len(hps)) if rst[b] == 0 and score_bar(noise[b]) is None]
+    if not idx:
+        return None
+    K, c, dt = cfg["n_folds"], cfg["n_classes"], cfg["dtype"]
+    d = cfg["X"].shape[1]
+    one = [dict(hps[b], epochs=1) for b in idx]
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, c, ft, K, one, dt, want_per_fold=True)
+    torch.cuda.synchronize()
+    counts = check_scores_against_oracle(oracle, cfg, one, scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy(),
+                                         name + ": the chaotic ones after one epoch")
+    tol = REL_BF16 if dt else REL_F32
+    for hp in one:
+        out = bb.bbo_mlp_cv_eval(X, y, c, ft, K, [hp], dt, trace=(0, 0, 0, 1))
+        torch.cuda.synchronize()
+        tr = out[-1]
+        ref = oracle.train_one(cfg["X"], cfg["y"], c, cfg["fold_idx"], hp, 0, dtype=dt, step_begin=0, step_end=1)
+        g, th = tr["grad"].cpu().numpy(), tr["theta_after"].cpu().numpy()
+        for lname, sl in layer_slices(d, hp["hidden"], c if c >= 2 else 1):
+            assert relerr(g[0, sl], ref["grad"][0, sl]) < tol, (name, hp, lname, "grad")
+            assert relerr(th[0, sl], ref["theta_after"][0, sl]) < tol, (name, hp, lname, "theta")
+    return counts
+
+
 # how many of the recorded suggestions of each configuration must be held to a bar (what the oracle's
 # noise measurement gives for the seeded suggestions; a change here means the inputs or the oracle changed)
-STATED_FLOORS = {0: 8, 1: 6, 2: 7, 3: 5, 4: 2}
+STATED_FLOORS = {0: 8, 1: 6, 2: 7, 3: 17, 4: 4}
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2])
-def test_stated_epochs_parity_configs(bb, idx):
+def test_stated_epochs_parity_configs(bb, oracle, idx):
     """The three 40-model configurations at full size for their stated epochs (20 / 200 / 200): every
     suggestion against the oracle's recorded scores."""
     cfg, picks, rs, rst, rpf, noise = stated_record(idx)
@@ -910,6 +937,7 @@ def test_stated_epochs_parity_configs(bb, idx):
     counts = compare_scores("%s stated size, %d epochs" % (cfg["name"], hps[0]["epochs"]), cfg, hps, scores.cpu().numpy(),
                             status.cpu().numpy(), pf.cpu().numpy(), rs, rst, rpf, noise)
     assert counts["strict"] + counts["widened"] >= STATED_FLOORS[idx]
+    check_chaotic_early(bb, oracle, cfg, X, y, ft, hps, noise, rst, cfg["name"])
 
 
 def test_full_size_many_studies_launch_sampled(bb, oracle):
@@ -930,6 +958,7 @@ def test_full_size_many_studies_launch_sampled(bb, oracle):
     counts = compare_scores("cfg3_many_studies stated size, 100 epochs, sampled", cfg, [hps[i] for i in pick], scores[pick],
                             status[pick], pf[pick], rs, rst, rpf, noise)
     assert counts["strict"] + counts["widened"] >= STATED_FLOORS[3]
+    check_chaotic_early(bb, oracle, cfg, X, y, ft, [hps[i] for i in pick], noise, rst, cfg["name"])
     # every suggestion either finished finite or flagged itself
     assert np.all((status == 0) == np.isfinite(scores[:, 0]))
 
@@ -951,15 +980,15 @@ def test_full_size_linear_launch_sampled(bb, oracle):
     assert torch.equal(again, scores) and torch.equal(st2, status)  # which wavefront trains a model does not matter
     scores, status, pf = scores.cpu().numpy(), status.cpu().numpy(), pf.cpu().numpy()
     assert np.all((status == 0) == np.isfinite(scores[:, 0]))
-    pick = [0, 1, 255, 256, 777, 1024, 1500, 2047]
+    pick = stated_record(3)[1]  # the same 24 suggestions as with their hidden layers
     counts = check_scores_against_oracle(oracle, cfg, [hps[i] for i in pick], scores[pick], status[pick], pf[pick],
                                          "cfg3 without hidden layers, stated size, sampled")
-    assert counts["strict"] >= 6
+    assert counts["strict"] == len(pick)
 
 
 def test_full_size_scale_up_launch(bb, oracle):
     """The scale-up workload at its full size (1,640 suggestions x 5 folds, 20,000 rows, 50 epochs) in the
-    benchmark's launch configuration.  Three of its suggestions (first, middle, last) are compared with the
+    benchmark's launch configuration.  Eight of its suggestions (spread over the list) are compared with the
     oracle's recorded scores after the stated 50 epochs; a suggestion's score must also not depend on the
     launch it is part of (bit-exact against the same suggestions launched alone)."""
     cfg = inputs.make_config(4)
@@ -978,6 +1007,7 @@ def test_full_size_scale_up_launch(bb, oracle):
     counts = compare_scores("cfg4_scaleup_bf16 stated size, 50 epochs, sampled", cfg, [hps[i] for i in pick],
                             scores[pick].cpu().numpy(), status[pick].cpu().numpy(), pf[pick].cpu().numpy(), rs, rst, rpf, noise)
     assert counts["strict"] + counts["widened"] >= STATED_FLOORS[4]
+    check_chaotic_early(bb, oracle, cfg, X, y, ft, [hps[i] for i in pick], noise, rst, cfg["name"])
 
 
 # ------------------------------------------------------- hold-out score ----
