@@ -829,7 +829,7 @@ def compare_scores(name, cfg, hps, scores, status, pf, rs, rst, rpf, noise):
     """GPU scores of the suggestions `hps` against the oracle's (rs, rst, rpf) under the rule of score_bar().
     Every suggestion that is not chaotic must pass; returns and prints the counts per category."""
     K, c = cfg["n_folds"], cfg["n_classes"]
-    n_va = len(cfg["y"]) // K
+    held = [max(int((np.asarray(cfg["fold_idx"]) == f).sum()), 1) for f in range(K)]  # rows scored per fold
     counts = {"strict": 0, "widened": 0, "chaotic": 0, "nonfinite": 0}
     worst = {"strict": 0.0, "widened": 0.0, "chaotic": 0.0}
     for b in range(len(hps)):
@@ -851,7 +851,7 @@ def compare_scores(name, cfg, hps, scores, status, pf, rs, rst, rpf, noise):
         assert dev < 2 * bar, (name, b, pf[b], rpf[b], noise[b])
         if c >= 1 and kind == "strict":
             for f in range(K):
-                assert explained_flips(pf[b, f, 1], rpf[b, f, 1], n_va), (name, b, f)
+                assert explained_flips(pf[b, f, 1], rpf[b, f, 1], held[f]), (name, b, f)
         if c == 0:  # regression: the second score is the mean absolute error
             assert abs(scores[b, 1] - rs[b, 1]) < bar and np.abs(pf[b, :, 1] - rpf[b, :, 1]).max() < 2 * bar, (name, b)
         counts[kind] += 1
