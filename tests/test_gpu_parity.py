@@ -800,6 +800,23 @@ def test_early_stopping_scores_the_best_epoch_on_the_held_rows(bb, oracle, n, d,
                          "best epoch %s" % ((n, d, hidden, dtype, stop, min(same)),))
 
 
+def test_early_stopping_hands_back_the_best_epoch_of_a_run_that_diverges_later(bb, oracle):
+    """SGD with a momentum of 0.99: the plain run ends non-finite (status 1) on both sides; with rows set aside
+    and a patience that never runs out, the same run keeps its best epoch's model, which is what is scored."""
+    reg = small_problem(6, 80, 5, 0)
+    X, y, ft = bb.to_device(reg)
+    hp = {"hidden": [8], "solver": "sgd", "momentum": 0.99, "nesterov": True, "lr": 0.05, "batch_size": 8, "epochs": 60, "seed": 1}
+    kept = dict(hp, validation_fraction=0.25, n_iter_no_change=100, tol=0.0)
+    scores, status, pf = bb.bbo_mlp_cv_eval(X, y, 0, ft, 5, [hp, kept], 0, want_per_fold=True)
+    torch.cuda.synchronize()
+    rs, rst, rpf = oracle.cv_eval(reg["X"], reg["y"], 0, reg["fold_idx"], 5, [hp, kept])
+    assert status.cpu().tolist() == rst.tolist() == [1, 0]
+    assert not np.isfinite(scores[0, 0].item()) and np.isfinite(scores[1, 0].item())
+    counts = compare_scores("best epoch of a run that diverges later", reg, [kept], scores.cpu().numpy()[1:], status.cpu().numpy()[1:],
+                            pf.cpu().numpy()[1:], rs[1:], rst[1:], rpf[1:], cv_noise(oracle, reg, [kept], 0, rpf[1:]))
+    assert counts["strict"] + counts["widened"] == 1
+
+
 # ----------------------------------------------------------- final scores ----
 
 def explained_flips(acc_gpu, acc_ref, n_va):
