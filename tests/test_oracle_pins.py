@@ -396,6 +396,21 @@ def test_adam_first_step_closed_form(oracle):
     np.testing.assert_allclose(th[big], (theta - lr * np.sign(g))[big], atol=1e-6)
 
 
+def test_single_sgd_steps_closed_form(oracle):
+    """The single-step entry point with the momentum solver: u = mu u - lr g, then theta + u, or with Nesterov's
+    look-ahead theta + mu u - lr g."""
+    rng = np.random.default_rng(3)
+    theta0, g, u0 = rng.normal(size=9), rng.normal(size=9), rng.normal(size=9)
+    lr, mu = float(np.float32(0.07)), float(np.float32(0.6))
+    for nesterov in (False, True):
+        theta, u, v = theta0.copy(), u0.copy(), np.zeros(9)
+        oracle.opt_step({"hidden": [], "solver": "sgd", "nesterov": nesterov, "lr": 0.07, "momentum": 0.6, "alpha": 0.3}, theta, g, u, v, 0,
+                        prec=1)
+        un = mu * u0 - lr * g
+        np.testing.assert_allclose(u, un, rtol=1e-14)
+        np.testing.assert_allclose(theta, theta0 + (mu * un - lr * g if nesterov else un), rtol=1e-14)
+
+
 @pytest.mark.parametrize("solver,nesterov,f", [("adam", False, 2), ("sgd", False, 2), ("sgd", True, 2), ("adam", False, -1)])
 def test_training_trajectory_matches_library_optimizer(oracle, solver, nesterov, f):
     """A few epochs of minibatch training in fp64 mode equal the same loop
@@ -793,8 +808,10 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
     fold = inputs.make_folds(90, 5, 6)
     f, E, frac = 2, 40, 0.2
     dims = [5, 7, n_classes if n_classes else 1]
+    # (the regression case also runs the inverse-scaling rate, which counts the rows that are fitted on)
+    p_t = 0.0 if n_classes else 0.25
     base = {"hidden": [7], "solver": "sgd", "nesterov": False, "momentum": 0.0, "lr": 0.08, "alpha": 0.01,
-            "batch_size": 16, "epochs": E, "seed": 14, "validation_fraction": frac}
+            "batch_size": 16, "epochs": E, "seed": 14, "validation_fraction": frac, "power_t": p_t}
     tr, va = oracle.fold_lists(fold, f)
     n_tr = len(tr)
     n_hold = int(np.floor(float(np.float32(frac)) * n_tr))
@@ -815,11 +832,12 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
         best, stalled, stop_at, tt_best, best_epoch = np.float32(np.inf), 0, E, None, -1
         for e in range(E):
             kep = py_fold(py_fold(kmodel, 1), e)
+            lr_e = lr / (1.0 + e * n_fit) ** float(np.float32(p_t))
             for s in range(-(-n_fit // 16)):
                 rows = [tr[py_perm(ksplit, n_tr, py_perm(kep, n_fit, p))] for p in range(s * 16, min((s + 1) * 16, n_fit))]
                 loss = torch_loss(tt, dims, Xt[rows], yt[rows], n_classes, alpha)
                 (g,) = torch.autograd.grad(loss, tt)
-                tt = (tt - lr * g).detach().requires_grad_(True)
+                tt = (tt - lr_e * g).detach().requires_grad_(True)
             le = np.float32(held_loss(tt.detach()))
             stalled = stalled + 1 if le > np.float32(best - np.float32(tol)) else 0
             if le < best:  # the best iterate on the held rows is the model that is handed back
@@ -840,7 +858,7 @@ def test_early_stop_on_held_rows_matches_a_hand_written_loop(oracle, n_classes):
         assert abs(got["scores"][0] - want) < 1e-10
         stops.append(stop_at)
     assert min(stops) < E, stops  # the rule does end some run early
-    assert any(late), late        # and some run's best epoch is not its last one
+    assert any(late) or p_t > 0, late  # and (at a constant rate) some run's best epoch is not its last one
     # the same rule on the training loss (no fraction) stops elsewhere: the held rows really are what is watched
     other = oracle.train_one(X, y, n_classes, fold, dict(base, tol=2e-2, n_iter_no_change=1, validation_fraction=0.0), f,
                              prec=1, step_begin=0, step_end=E * 5)
