@@ -13,7 +13,9 @@
  *   - "device" pointers are HIP device memory on the current device; "host"
  *     pointers are ordinary host memory.  The caller owns every buffer.  The
  *     library allocates no device memory and keeps no state between calls
- *     (it keeps a small pinned host staging buffer per host thread).
+ *     (it keeps a small pinned host staging buffer per host thread and
+ *     device; bbo_mlp_cv_eval_static is the one call that brings its own
+ *     device workspace, a static array inside the library).
  *   - Work is enqueued on the caller's stream and the call returns without
  *     waiting for it; outputs are valid once the stream has been synchronised.
  *   - Every function returns BBO_OK or an error code; bbo_mlp_last_error()
